@@ -1,0 +1,190 @@
+"""CPU oracle of the big-little MoE layer -- TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes front end of ``mobile_oracle.cpp`` (plain C++, double arithmetic) plus a
+pure-Python model of the expert cache (``cache_model``).  Nothing under this folder is
+part of the product: only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
+leg of ``bench.py`` may import it, and it imports nothing from the HIP package.
+
+Storage conventions: activations and weights are numpy arrays of dtype ``float32`` or
+``uint16`` (bf16 bit patterns); the oracle widens them exactly and computes in double.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mobile_oracle.cpp")
+_LIB = os.path.join(_HERE, "libmobile_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (host only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-std=c++17", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        for name in ("oracle_gate_logits", "oracle_token_confidence", "oracle_route",
+                     "oracle_dispatch", "oracle_swiglu_rows", "oracle_expert_ffn",
+                     "oracle_combine", "oracle_num_threads"):
+            getattr(_lib, name).restype = ctypes.c_int
+    return _lib
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.uint16:
+        return 0
+    if a.dtype == np.float32:
+        return 1
+    raise TypeError(f"oracle reads uint16 (bf16 bits) or float32 arrays, got {a.dtype}")
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _c(a: np.ndarray, dtype=None) -> np.ndarray:
+    a = np.ascontiguousarray(a) if dtype is None else np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError(f"{what}: bad argument (rc={rc})")
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:
+    x, Wg = _c(x), _c(Wg)
+    T, H = x.shape
+    E = Wg.shape[0]
+    assert Wg.shape[1] == H and _dtype_code(x) == _dtype_code(Wg)
+    b = None if bias is None else _c(bias, np.float32)
+    out = np.empty((T, E), np.float32)
+    _check(_load().oracle_gate_logits(_p(x), _p(Wg), _p(b), T, H, E, _dtype_code(x), _p(out)),
+           "gate_logits")
+    return out
+
+
+def token_confidence(lm_logits: np.ndarray) -> np.ndarray:
+    z = _c(lm_logits, np.float32)
+    T, V = z.shape
+    out = np.empty((T,), np.float32)
+    _check(_load().oracle_token_confidence(_p(z), T, V, _p(out)), "token_confidence")
+    return out
+
+
+def route(logits: np.ndarray, conf: Optional[np.ndarray], gamma: float, k_big: int,
+          k_little: int, renorm: bool):
+    """-> (topk_idx int32 [T,K], topk_w float32 [T,K], important uint8 [T], k_t int32 [T])"""
+    lg = _c(logits, np.float32)
+    T, E = lg.shape
+    cf = None if conf is None else _c(conf, np.float32)
+    idx = np.empty((T, k_big), np.int32)
+    w = np.empty((T, k_big), np.float32)
+    imp = np.empty((T,), np.uint8)
+    kt = np.empty((T,), np.int32)
+    _check(_load().oracle_route(_p(lg), _p(cf), ctypes.c_float(gamma), T, E, k_big, k_little,
+                                int(bool(renorm)), _p(idx), _p(w), _p(imp), _p(kt)), "route")
+    return idx, w, imp, kt
+
+
+def dispatch(topk_idx: np.ndarray, k_t: np.ndarray, E: int):
+    """-> (expert_offsets [E+1], sorted_token [T*K], sorted_rank [T*K], inv_pos [T,K]) int32"""
+    idx = _c(topk_idx, np.int32)
+    kt = _c(k_t, np.int32)
+    T, K = idx.shape
+    off = np.empty((E + 1,), np.int32)
+    st = np.empty((T * K,), np.int32)
+    sr = np.empty((T * K,), np.int32)
+    inv = np.empty((T, K), np.int32)
+    _check(_load().oracle_dispatch(_p(idx), _p(kt), T, E, K, _p(off), _p(st), _p(sr), _p(inv)),
+           "dispatch")
+    return off, st, sr, inv
+
+
+def swiglu_rows(x: np.ndarray, blob: np.ndarray, I: int,
+                tok: Optional[np.ndarray] = None) -> np.ndarray:
+    """One expert (blob = [W_gate I*H | W_up I*H | W_down H*I] flat) on rows ``tok`` of x
+    (all rows in order when ``tok`` is None).  -> float64 [n,H]"""
+    x, blob = _c(x), _c(blob)
+    T, H = x.shape
+    assert blob.size == 3 * H * I and _dtype_code(blob) == _dtype_code(x)
+    tk = None if tok is None else _c(tok, np.int32)
+    n = T if tk is None else tk.shape[0]
+    y = np.empty((n, H), np.float64)
+    _check(_load().oracle_swiglu_rows(_p(x), _dtype_code(x), H, I, _p(blob), _p(tk), n, _p(y)),
+           "swiglu_rows")
+    return y
+
+
+def expert_ffn(x: np.ndarray, expert_w: Sequence[np.ndarray], I: int, expert_offsets: np.ndarray,
+               sorted_token: np.ndarray) -> np.ndarray:
+    """-> float64 [P,H], row p = expert FFN of the pair at dispatch position p"""
+    x = _c(x)
+    T, H = x.shape
+    E = len(expert_w)
+    blobs = [_c(b) for b in expert_w]
+    for b in blobs:
+        assert b.size == 3 * H * I and _dtype_code(b) == _dtype_code(x)
+    ptrs = (ctypes.c_void_p * E)(*[b.ctypes.data for b in blobs])
+    off = _c(expert_offsets, np.int32)
+    st = _c(sorted_token, np.int32)
+    P = int(off[E])
+    y = np.zeros((P, H), np.float64)
+    _check(_load().oracle_expert_ffn(_p(x), _dtype_code(x), H, I, E, _p(off), _p(st), ptrs, _p(y)),
+           "expert_ffn")
+    return y
+
+
+def combine(y: np.ndarray, topk_w: np.ndarray, inv_pos: np.ndarray, k_t: np.ndarray,
+            shared: Optional[np.ndarray], T: int, H: int) -> np.ndarray:
+    """-> float64 [T,H];  shared: float64 [n_shared,T,H] or None"""
+    y = _c(y, np.float64)
+    w = _c(topk_w, np.float32)
+    inv = _c(inv_pos, np.int32)
+    kt = _c(k_t, np.int32)
+    K = w.shape[1]
+    sh = None if shared is None else _c(shared, np.float64)
+    ns = 0 if sh is None else sh.shape[0]
+    out = np.empty((T, H), np.float64)
+    _check(_load().oracle_combine(_p(y), _p(w), _p(inv), _p(kt), _p(sh), ns, T, H, K, _p(out)),
+           "combine")
+    return out
+
+
+def moe_layer(x: np.ndarray, Wg: np.ndarray, gate_bias: Optional[np.ndarray],
+              expert_w: Sequence[np.ndarray], I: int, shared_w: Sequence[np.ndarray],
+              shared_I: Sequence[int], conf: Optional[np.ndarray], gamma: float, k_big: int,
+              k_little: int, renorm: bool, logits: Optional[np.ndarray] = None) -> dict:
+    """The whole layer, step by step (Sec. II-A selection + execution, Alg. 1 flagging)."""
+    x = _c(x)
+    T, H = x.shape
+    E = len(expert_w)
+    if logits is None:
+        logits = gate_logits(x, Wg, gate_bias)
+    idx, w, imp, kt = route(logits, conf, gamma, k_big, k_little, renorm)
+    off, st, sr, inv = dispatch(idx, kt, E)
+    y = expert_ffn(x, expert_w, I, off, st)
+    shared = None
+    if len(shared_w):
+        shared = np.stack([swiglu_rows(x, b, Is) for b, Is in zip(shared_w, shared_I)])
+    out = combine(y, w, inv, kt, shared, T, H)
+    return dict(logits=logits, topk_idx=idx, topk_w=w, important=imp, k_t=kt, expert_offsets=off,
+                sorted_token=st, sorted_rank=sr, inv_pos=inv, y=y, shared=shared, out=out)

@@ -1,0 +1,263 @@
+// CPU oracle for the big-little MoE layer (MoBiLE, arXiv 2510.12357).
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what the layer
+// computes.  It shares no code with the HIP library and must never be called from the
+// product path; only tests, the smoke check and the benchmark's CPU-baseline leg use it.
+//
+// Everything floating point is evaluated in double.  Router logits are the one exception:
+// they are stored as fp32 because the expert selection is defined on the fp32 logits
+// (both the oracle and the GPU path take that integer decision on the same fp32 values).
+//
+// No blocking, fusion or reordering: every function is the loop nest of its definition.
+// Rows of independent work are spread over host threads with OpenMP; the arithmetic of a
+// single output element is never split.
+//
+// Passages followed (paper sections):
+//   Sec. II-A   selection stage (router picks experts, yields routing weights) and
+//               execution stage (hidden states through the selected experts, summed)
+//   Sec. III-A  big model = K experts, little model = K/2 experts of the same layer
+//   Alg. 1      keep the little result iff max(p) > gamma, otherwise fall back to big
+//   Sec. III-B  the confidence is the highest probability of the output distribution
+//
+// Parity pins: see tests/test_oracle_*.py (brute-force dense evaluation, textbook top-K,
+// closed forms, structural invariants).  No function here is unpinned.
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+// dtype codes of the storage formats the oracle can read
+constexpr int kBF16 = 0;   // uint16 holding the upper half of an IEEE fp32
+constexpr int kFP32 = 1;
+
+inline double load_elem(const void* base, size_t i, int dtype) {
+  if (dtype == kFP32) return (double)static_cast<const float*>(base)[i];
+  uint32_t bits = (uint32_t)static_cast<const uint16_t*>(base)[i] << 16;
+  float f;
+  std::memcpy(&f, &bits, sizeof f);
+  return (double)f;
+}
+
+inline size_t elem_size(int dtype) { return dtype == kFP32 ? 4 : 2; }
+
+// NaN router scores take part in selection and softmax as minus infinity.
+inline double clean_logit(float v) {
+  return std::isnan(v) ? -std::numeric_limits<double>::infinity() : (double)v;
+}
+
+}  // namespace
+
+extern "C" {
+
+// Sec. II-A, selection stage: logits[t][e] = sum_h x[t][h] * Wg[e][h] (+ bias[e]).
+// x [T,H], Wg [E,H] row-major in `dtype`; bias fp32 or NULL; logits fp32 [T,E].
+int oracle_gate_logits(const void* x, const void* Wg, const float* bias, int T, int H, int E,
+                       int dtype, float* logits) {
+  if (!x || !Wg || !logits || T < 0 || H <= 0 || E <= 0) return -1;
+#pragma omp parallel for schedule(static)
+  for (int t = 0; t < T; ++t) {
+    for (int e = 0; e < E; ++e) {
+      double acc = 0.0;
+      for (int h = 0; h < H; ++h)
+        acc += load_elem(x, (size_t)t * H + h, dtype) * load_elem(Wg, (size_t)e * H + h, dtype);
+      if (bias) acc += (double)bias[e];
+      logits[(size_t)t * E + e] = (float)acc;
+    }
+  }
+  return 0;
+}
+
+// Sec. III-B / Alg. 1: confidence of a token = largest probability of softmax(z_t)
+//   = 1 / sum_v exp(z_tv - max_v z_tv).
+int oracle_token_confidence(const float* lm_logits, int T, int V, float* conf) {
+  if (!lm_logits || !conf || T < 0 || V <= 0) return -1;
+  for (int t = 0; t < T; ++t) {
+    const float* z = lm_logits + (size_t)t * V;
+    double m = -std::numeric_limits<double>::infinity();
+    for (int v = 0; v < V; ++v) m = std::fmax(m, (double)z[v]);
+    double s = 0.0;
+    for (int v = 0; v < V; ++v) s += std::exp((double)z[v] - m);
+    conf[t] = (float)(1.0 / s);
+  }
+  return 0;
+}
+
+// Alg. 1 (test max(p) > gamma) + Sec. III-A (K vs K/2 experts) + Sec. II-A (routing weights).
+//   important[t] = !(conf[t] > gamma)   (conf == NULL: every token important)
+//   k_t[t]       = important ? k_big : k_little
+//   idx[t][j]    = j-th expert of token t in the order (logit descending, index ascending),
+//                  j < k_t; -1 beyond
+//   w[t][j]      = softmax over ALL E logits, taken at idx[t][j]; with renorm != 0 divided
+//                  by the sum over the k_t selected; 0 beyond k_t
+int oracle_route(const float* logits, const float* conf, float gamma, int T, int E, int k_big,
+                 int k_little, int renorm, int32_t* idx, float* w, uint8_t* important,
+                 int32_t* k_t) {
+  if (!logits || !idx || !w || !important || !k_t) return -1;
+  if (T < 0 || E <= 0 || k_little < 1 || k_little > k_big || k_big > E) return -1;
+  const double ninf = -std::numeric_limits<double>::infinity();
+  for (int t = 0; t < T; ++t) {
+    const float* row = logits + (size_t)t * E;
+    const bool imp = conf ? !(conf[t] > gamma) : true;
+    important[t] = imp ? 1 : 0;
+    const int k = imp ? k_big : k_little;
+    k_t[t] = k;
+
+    // softmax over all experts
+    std::vector<double> p(E);
+    double m = ninf;
+    for (int e = 0; e < E; ++e) m = std::fmax(m, clean_logit(row[e]));
+    double s = 0.0;
+    for (int e = 0; e < E; ++e) {
+      p[e] = (m == ninf) ? 0.0 : std::exp(clean_logit(row[e]) - m);
+      s += p[e];
+    }
+    for (int e = 0; e < E; ++e) p[e] = (s > 0.0) ? p[e] / s : 0.0;
+
+    // plain selection: k rounds of "best expert not taken yet"
+    std::vector<char> taken(E, 0);
+    double wsum = 0.0;
+    for (int j = 0; j < k_big; ++j) {
+      if (j >= k) {
+        idx[(size_t)t * k_big + j] = -1;
+        w[(size_t)t * k_big + j] = 0.0f;
+        continue;
+      }
+      int best = -1;
+      for (int e = 0; e < E; ++e) {
+        if (taken[e]) continue;
+        if (best < 0 || clean_logit(row[e]) > clean_logit(row[best])) best = e;  // ties keep lower e
+      }
+      taken[best] = 1;
+      idx[(size_t)t * k_big + j] = best;
+      wsum += p[best];
+    }
+    for (int j = 0; j < k; ++j) {
+      double v = p[idx[(size_t)t * k_big + j]];
+      if (renorm) v = (wsum > 0.0) ? v / wsum : 0.0;
+      w[(size_t)t * k_big + j] = (float)v;
+    }
+  }
+  return 0;
+}
+
+// Execution stage needs the (token, rank) pairs grouped per expert.  The order is fixed:
+// expert ascending, then token ascending (a token names an expert at most once).
+//   offsets[E+1]      exclusive prefix of per-expert pair counts, offsets[E] = P
+//   sorted_token[p]   token of the pair at position p      (-1 for p >= P)
+//   sorted_rank[p]    its rank j in the token's selection  (-1 for p >= P)
+//   inv_pos[t][j]     position of pair (t, j)              (-1 for j >= k_t)
+int oracle_dispatch(const int32_t* idx, const int32_t* k_t, int T, int E, int K, int32_t* offsets,
+                    int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos) {
+  if (!idx || !k_t || !offsets || !sorted_token || !sorted_rank || !inv_pos) return -1;
+  for (size_t i = 0; i < (size_t)T * K; ++i) {
+    sorted_token[i] = -1;
+    sorted_rank[i] = -1;
+    inv_pos[i] = -1;
+  }
+  int pos = 0;
+  for (int e = 0; e < E; ++e) {
+    offsets[e] = pos;
+    for (int t = 0; t < T; ++t) {
+      for (int j = 0; j < k_t[t]; ++j) {
+        if (idx[(size_t)t * K + j] == e) {
+          sorted_token[pos] = t;
+          sorted_rank[pos] = j;
+          inv_pos[(size_t)t * K + j] = pos;
+          ++pos;
+        }
+      }
+    }
+  }
+  offsets[E] = pos;
+  return 0;
+}
+
+// SwiGLU feed-forward of one expert on a list of token rows.
+//   blob = [W_gate I x H | W_up I x H | W_down H x I], each row-major, in `dtype`
+//   for row r (token tok[r], or r itself when tok == NULL):
+//     g_i = sum_h W_gate[i][h] x[h];  u_i = sum_h W_up[i][h] x[h]
+//     a_i = g_i / (1 + exp(-g_i)) * u_i
+//     y[r][c] = sum_i W_down[c][i] a_i
+// y is double [n,H].
+int oracle_swiglu_rows(const void* x, int dtype, int H, int I, const void* blob,
+                       const int32_t* tok, int n, double* y) {
+  if (!x || !blob || !y || H <= 0 || I <= 0 || n < 0) return -1;
+  const char* base = static_cast<const char*>(blob);
+  const void* Wgate = base;
+  const void* Wup = base + (size_t)I * H * elem_size(dtype);
+  const void* Wdown = base + 2 * (size_t)I * H * elem_size(dtype);
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int r = 0; r < n; ++r) {
+    const size_t t = tok ? (size_t)tok[r] : (size_t)r;
+    std::vector<double> a(I);
+    for (int i = 0; i < I; ++i) {
+      double g = 0.0, u = 0.0;
+      for (int h = 0; h < H; ++h) {
+        const double xv = load_elem(x, t * H + h, dtype);
+        g += load_elem(Wgate, (size_t)i * H + h, dtype) * xv;
+        u += load_elem(Wup, (size_t)i * H + h, dtype) * xv;
+      }
+      a[i] = g / (1.0 + std::exp(-g)) * u;
+    }
+    for (int c = 0; c < H; ++c) {
+      double acc = 0.0;
+      for (int i = 0; i < I; ++i) acc += load_elem(Wdown, (size_t)c * I + i, dtype) * a[i];
+      y[(size_t)r * H + c] = acc;
+    }
+  }
+  return 0;
+}
+
+// Execution stage over the dispatched pairs: expert e processes positions
+// offsets[e] .. offsets[e+1]-1.  expert_w[e] points at expert e's blob (host memory).
+int oracle_expert_ffn(const void* x, int dtype, int H, int I, int E, const int32_t* offsets,
+                      const int32_t* sorted_token, const void* const* expert_w, double* y) {
+  if (!offsets || !sorted_token || !expert_w) return -1;
+  for (int e = 0; e < E; ++e) {
+    const int b = offsets[e], n = offsets[e + 1] - b;
+    if (n == 0) continue;
+    int rc = oracle_swiglu_rows(x, dtype, H, I, expert_w[e], sorted_token + b, n,
+                                y + (size_t)b * H);
+    if (rc) return rc;
+  }
+  return 0;
+}
+
+// "finally summed": out[t][c] = sum_{j<k_t} w[t][j] * y[inv_pos[t][j]][c]  (j ascending)
+//                              + sum_s shared[s][t][c]
+// shared: n_shared stacked [T,H] double arrays (always-on experts, weight 1) or NULL.
+int oracle_combine(const double* y, const float* w, const int32_t* inv_pos, const int32_t* k_t,
+                   const double* shared, int n_shared, int T, int H, int K, double* out) {
+  if (!w || !inv_pos || !k_t || !out) return -1;
+  for (int t = 0; t < T; ++t) {
+    for (int c = 0; c < H; ++c) {
+      double acc = 0.0;
+      for (int j = 0; j < k_t[t]; ++j)
+        acc += (double)w[(size_t)t * K + j] * y[(size_t)inv_pos[(size_t)t * K + j] * H + c];
+      for (int s = 0; s < n_shared; ++s) acc += shared[((size_t)s * T + t) * H + c];
+      out[(size_t)t * H + c] = acc;
+    }
+  }
+  return 0;
+}
+
+int oracle_num_threads(void) {
+  int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+  {
+#pragma omp single
+    n = omp_get_num_threads();
+  }
+#endif
+  return n;
+}
+
+}  // extern "C"

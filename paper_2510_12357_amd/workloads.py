@@ -1,0 +1,157 @@
+"""Seeded synthetic MoE layers (inputs only -- none of the method's arithmetic lives here).
+
+Both the CPU oracle's tests and the GPU tests / benchmark take their host buffers from this
+module, so the two sides always see bit-identical inputs.  Everything is numpy on the host;
+bf16 tensors are carried as ``uint16`` bit patterns.
+
+The shapes follow the layer configurations this build is measured on (fine-grained MoE
+layers like the two models of the paper's evaluation section, plus a coarse 8-expert layer
+and a tiny fp32 layer); the value distributions are N(0,1) activations, N(0,0.02) expert
+weights and a per-token confidence whose fraction below the threshold gamma equals a chosen
+fallback ratio r (the paper's tables report r between 0.10 and 0.29 at gamma = 0.7).
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+
+@dataclasses.dataclass(frozen=True)
+class LayerConfig:
+    name: str
+    T: int                      # tokens in the step
+    H: int                      # hidden size
+    E: int                      # routed experts
+    I: int                      # routed expert intermediate size
+    k_big: int                  # experts of an important token (the model's default K)
+    k_little: int               # experts of every other token (K/2)
+    shared_I: Tuple[int, ...] = ()   # always-on shared experts (intermediate sizes)
+    dtype: str = "bf16"         # storage type of x and all weights: "bf16" | "fp32"
+    renorm: bool = False        # renormalise routing weights over the selected experts
+    gamma: float = 0.7          # fallback threshold
+    gate_std: float = 0.02
+    gate_bias_std: float = 0.0  # > 0: per-expert logit bias (imbalanced expert loads)
+    w_std: float = 0.02
+    fallback_ratio: float = 0.2
+
+    def with_(self, **kw) -> "LayerConfig":
+        return dataclasses.replace(self, **kw)
+
+    @property
+    def expert_params(self) -> int:
+        return 3 * self.H * self.I
+
+
+# The five measured configurations (tokens T is the default; decode sweeps override it).
+CONFIGS = {
+    "tiny_fp32": LayerConfig("tiny_fp32", T=64, H=256, E=8, I=512, k_big=2, k_little=1,
+                             dtype="fp32", renorm=True, gate_std=0.1),
+    "fine60_decode": LayerConfig("fine60_decode", T=64, H=2048, E=60, I=1408, k_big=4,
+                                 k_little=2, shared_I=(5632,)),
+    "fine64_prefill": LayerConfig("fine64_prefill", T=2048, H=2048, E=64, I=1024, k_big=8,
+                                  k_little=4, gate_bias_std=1.0),
+    "shared2_offload": LayerConfig("shared2_offload", T=16, H=2048, E=64, I=1408, k_big=6,
+                                   k_little=3, shared_I=(1408, 1408)),
+    "coarse8": LayerConfig("coarse8", T=4096, H=4096, E=8, I=14336, k_big=2, k_little=1,
+                           renorm=True),
+}
+
+
+# ----------------------------------------------------------------------------- storage types
+def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns (finite inputs)."""
+    b = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rnd = ((b >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    return ((b + rnd) >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def _store(a: np.ndarray, dtype: str) -> np.ndarray:
+    if dtype == "fp32":
+        return np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "bf16":
+        return f32_to_bf16_bits(a)
+    raise ValueError(dtype)
+
+
+def as_f32(a: np.ndarray) -> np.ndarray:
+    """Exact fp32 view of a stored tensor (uint16 bf16 bits or float32)."""
+    return bf16_bits_to_f32(a) if a.dtype == np.uint16 else np.asarray(a, dtype=np.float32)
+
+
+# ----------------------------------------------------------------------------- generators
+def _rng(seed: int, tensor_id: int) -> np.random.Generator:
+    # one independent counter-based stream per (seed, tensor)
+    return np.random.Generator(np.random.Philox(key=[np.uint64(seed), np.uint64(tensor_id)]))
+
+
+_ID_X, _ID_WG, _ID_BIAS, _ID_CONF, _ID_LM, _ID_HS = 1, 2, 3, 4, 5, 6
+_ID_EXPERT0, _ID_SHARED0 = 1000, 100000
+
+
+def _normal(seed: int, tid: int, shape, std: float) -> np.ndarray:
+    return (_rng(seed, tid).standard_normal(shape, dtype=np.float32) * np.float32(std))
+
+
+@dataclasses.dataclass
+class Layer:
+    cfg: LayerConfig
+    x: np.ndarray                       # [T,H]
+    Wg: np.ndarray                      # [E,H]
+    gate_bias: Optional[np.ndarray]     # [E] fp32 or None
+    expert_w: List[np.ndarray]          # E flat blobs [W_gate I*H | W_up I*H | W_down H*I]
+    shared_w: List[np.ndarray]          # one flat blob per shared expert
+    conf: np.ndarray                    # [T] fp32 per-token confidence
+
+
+def make_confidence(seed: int, T: int, gamma: float, r: float) -> np.ndarray:
+    """conf with P(conf <= gamma) = r: u ~ U(0,1]; u <= r maps below gamma, else above."""
+    u = 1.0 - _rng(seed, _ID_CONF).random(T)           # (0,1]
+    if r <= 0.0:
+        c = gamma + (1.0 - gamma) * u
+    elif r >= 1.0:
+        c = gamma * u
+    else:
+        c = np.where(u <= r, gamma * u / r, gamma + (1.0 - gamma) * (u - r) / (1.0 - r))
+    return c.astype(np.float32)
+
+
+def make_lm_logits(seed: int, T: int, V: int, r: float, std: float = 3.0,
+                   spike: float = 16.0) -> np.ndarray:
+    """Synthetic LM-head outputs [T,V]: N(0,std) noise; a fraction 1-r of the rows gets one
+    dominant entry so that their largest softmax probability is close to 1."""
+    g = _rng(seed, _ID_LM)
+    z = g.standard_normal((T, V), dtype=np.float32) * np.float32(std)
+    confident = g.random(T) >= r
+    hot = g.integers(0, V, size=T)
+    z[np.arange(T)[confident], hot[confident]] += np.float32(spike)
+    return z
+
+
+def make_router_noise(seed: int, T: int, E: int, sigma: float) -> np.ndarray:
+    """Additive noise that turns a layer's logits into stale "router states" of an earlier
+    pass (used to drive prefetch with imperfect predictions)."""
+    return _normal(seed, _ID_HS, (T, E), sigma)
+
+
+def make_expert_blob(cfg: LayerConfig, seed: int, e: int, I: Optional[int] = None,
+                     shared: bool = False) -> np.ndarray:
+    I = cfg.I if I is None else I
+    tid = (_ID_SHARED0 if shared else _ID_EXPERT0) + e
+    return _store(_normal(seed, tid, (3 * cfg.H * I,), cfg.w_std), cfg.dtype)
+
+
+def make_layer(cfg: LayerConfig, seed: int = 0, experts: bool = True) -> Layer:
+    x = _store(_normal(seed, _ID_X, (cfg.T, cfg.H), 1.0), cfg.dtype)
+    Wg = _store(_normal(seed, _ID_WG, (cfg.E, cfg.H), cfg.gate_std), cfg.dtype)
+    bias = _normal(seed, _ID_BIAS, (cfg.E,), cfg.gate_bias_std) if cfg.gate_bias_std > 0 else None
+    ew = [make_expert_blob(cfg, seed, e) for e in range(cfg.E)] if experts else []
+    sw = [make_expert_blob(cfg, seed, s, I=Is, shared=True) for s, Is in enumerate(cfg.shared_I)] \
+        if experts else []
+    conf = make_confidence(seed, cfg.T, cfg.gamma, cfg.fallback_ratio)
+    return Layer(cfg, x, Wg, bias, ew, sw, conf)
