@@ -1,0 +1,225 @@
+/*
+ * mobile_moe.h -- C ABI of the big-little Mixture-of-Experts layer hot path for AMD MI355X
+ * (gfx950), after "MoBiLE: Efficient Mixture-of-Experts Inference on Consumer GPU with
+ * Mixture of Big Little Experts" (arXiv 2510.12357).
+ *
+ * One decode or prefill step of one MoE layer is the call sequence
+ *
+ *     moe_route  ->  moe_dispatch  ->  [expert_cache_fetch]  ->  moe_expert_ffn  ->  moe_combine
+ *
+ * which follows the paper's two stages (Sec. II-A): a selection stage in which the router
+ * picks experts and produces routing weights, and an execution stage in which the hidden
+ * states pass through every selected expert and are summed.  The big-little rule (Sec. III-A,
+ * Alg. 1) makes the number of experts a per-token quantity: a token whose confidence
+ * max(p) is above the threshold gamma keeps the "little" selection of k_little = K/2 experts,
+ * every other ("important") token falls back to the "big" selection of k_big = K experts.
+ * When expert weights live in host DRAM (Sec. II-B, III-B) expert_cache_fetch brings the
+ * needed experts into a small HBM slot cache, on demand or ahead of time from the router
+ * outputs of an earlier pass.
+ *
+ * General conventions
+ *   - Every function returns 0 (MOE_OK) or a negative MOE_E_* code; moe_last_error() gives a
+ *     thread-local message for the last failure.  Arguments are validated on the host before
+ *     anything is enqueued; a failed call enqueues nothing.
+ *   - "device" pointers are HBM addresses owned by the caller; "host" pointers are ordinary
+ *     process memory.  The library never allocates or frees caller tensors.  Scratch memory is
+ *     passed in (`ws`, size from the matching *_workspace_bytes query, 256-byte aligned).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued asynchronously on it; no call synchronises with the host except where stated.
+ *   - Tensors are row-major and dense.  dtype MOE_BF16: activations / weights are bf16,
+ *     products accumulate in fp32.  dtype MOE_FP32: fp32 storage and arithmetic.
+ *   - Shape limits: H % 8 == 0, I % 8 == 0, every shared_I % 8 == 0, 1 <= k_little <= k_big
+ *     <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS, n_shared <= MOE_MAX_SHARED,
+ *     T * k_big < 2^31 / max(H, I).  Violations give MOE_E_SHAPE / MOE_E_UNSUPPORTED.
+ *   - Expert weight blob (one per routed or shared expert, contiguous, 16-byte aligned):
+ *         [ W_gate : I x H | W_up : I x H | W_down : H x I ]      (each row-major)
+ *     so that one expert is one host-to-device copy.  The feed-forward is SwiGLU:
+ *         y = W_down ( silu(W_gate x) * (W_up x) ).
+ */
+#ifndef MOBILE_MOE_H_
+#define MOBILE_MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_MAX_SHARED 4
+#define MOE_MAX_EXPERTS 256
+#define MOE_MAX_TOPK 16
+
+enum { MOE_BF16 = 0, MOE_FP32 = 1 };
+
+enum {
+  MOE_OK = 0,
+  MOE_E_BADARG = -1,      /* null pointer, negative size, bad enum */
+  MOE_E_SHAPE = -2,       /* sizes inconsistent with each other */
+  MOE_E_UNSUPPORTED = -3, /* valid but outside the limits listed above */
+  MOE_E_HIP = -4,         /* a HIP runtime call failed (message holds its error string) */
+  MOE_E_CACHE_FULL = -5,  /* a DEMAND fetch names more experts than the cache has slots */
+  MOE_E_WORKSPACE = -6    /* workspace missing, misaligned or too small */
+};
+
+/* Layer description shared by all calls of a step. */
+typedef struct moe_config {
+  int32_t T;        /* tokens in this step (T == 0 is legal: nothing is enqueued)          */
+  int32_t H;        /* hidden size                                                          */
+  int32_t E;        /* routed experts                                                       */
+  int32_t I;        /* intermediate size of a routed expert                                 */
+  int32_t k_big;    /* experts of an important token: the model's default K (Sec. III-A)    */
+  int32_t k_little; /* experts of every other token: K/2 in the paper, any 1..k_big here    */
+  int32_t n_shared; /* always-on shared experts (weight 1, every token); 0 = none           */
+  int32_t shared_I[MOE_MAX_SHARED]; /* their intermediate sizes                             */
+  int32_t dtype;    /* MOE_BF16 | MOE_FP32: storage of x, Wg, expert blobs, out             */
+  int32_t renorm;   /* 0: routing weight = softmax over all E; 1: renormalised over the k_t
+                       selected experts                                                     */
+  float gamma;      /* fallback threshold of Alg. 1 (paper default 0.7)                     */
+} moe_config;
+
+const char* moe_last_error(void);
+
+/* Number of compute units of the current device and the library's build tag (diagnostics). */
+int moe_device_info(int32_t* n_cu, int32_t* is_gfx950);
+
+/* ------------------------------------------------------------------------------------------
+ * Selection stage (Sec. II-A) with the big-little rule (Sec. III-A, Alg. 1).
+ *
+ *   logits[t][e] = sum_h x[t][h] * Wg[e][h] + gate_bias[e]              (skipped if logits_given)
+ *   important[t] = !(conf[t] > gamma)      (equality and NaN fall back; conf NULL: all important)
+ *   k_t[t]       = important[t] ? k_big : k_little
+ *   topk_idx[t][j], j < k_t[t]: experts in the order (logit descending, expert id ascending),
+ *                  taken on the fp32 logits; a NaN logit counts as -inf; -1 for j >= k_t[t]
+ *   topk_w[t][j] = softmax over all E logits at topk_idx[t][j] (divided by the sum over the
+ *                  k_t selected if cfg->renorm); 0 for j >= k_t[t]
+ *
+ * Because the little selection is a prefix of the big one, a token's fallback re-run with
+ * k_big experts reuses the first k_little experts of its little pass (Sec. III-A).
+ *
+ * x        device [T,H] dtype          Wg        device [E,H] dtype
+ * gate_bias device [E] fp32 or NULL    conf      device [T] fp32 or NULL
+ * logits   device [T,E] fp32: output, or input when logits_given != 0 (x, Wg may then be NULL)
+ * topk_idx device [T,k_big] int32      topk_w    device [T,k_big] fp32
+ * important device [T] uint8           k_t       device [T] int32
+ */
+int moe_route(const moe_config* cfg, const void* x, const void* Wg, const float* gate_bias,
+              const float* conf, float* logits, int logits_given, int32_t* topk_idx,
+              float* topk_w, uint8_t* important, int32_t* k_t, void* stream);
+
+/* Confidence of Alg. 1 / Sec. III-B: the largest probability of the model's output
+ * distribution, conf[t] = max_v softmax(lm_logits[t])_v = 1 / sum_v exp(z_tv - max_v z_tv).
+ * lm_logits device [T,V] fp32, conf device [T] fp32. */
+int moe_token_confidence(const float* lm_logits, int32_t T, int32_t V, float* conf, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Token-to-expert dispatch with a variable expert count per token: the (t, j < k_t[t]) pairs
+ * are put in the unique order (expert ascending, token ascending) the execution stage
+ * (Sec. II-A) consumes.  P = sum_t k_t[t].
+ *
+ *   expert_offsets device [E+1] int32  exclusive prefix of pairs per expert; [E] = P
+ *   sorted_token   device [T*k_big]    token of the pair at each position, -1 beyond P
+ *   sorted_rank    device [T*k_big]    rank j of that pair,                -1 beyond P
+ *   inv_pos        device [T,k_big]    position of pair (t,j),             -1 for j >= k_t[t]
+ * Integer-only, atomics-free, deterministic.
+ */
+size_t moe_dispatch_workspace_bytes(const moe_config* cfg);
+int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t,
+                 int32_t* expert_offsets, int32_t* sorted_token, int32_t* sorted_rank,
+                 int32_t* inv_pos, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Execution stage (Sec. II-A): grouped SwiGLU feed-forward over the dispatched pairs, plus
+ * the always-on shared experts.
+ *
+ *   for every routed expert e with expert_w[e] != NULL and position p in
+ *   [expert_offsets[e], expert_offsets[e+1]):     y[p][:] = FFN_e( x[sorted_token[p]][:] )
+ *   for every shared expert s and token t:        shared_out[s][t][:] = FFN_s( x[t][:] )
+ *
+ * expert_w   DEVICE array of E device pointers to expert blobs.  A NULL entry skips that
+ *            expert (its rows of y are left untouched): this is how a step is run in several
+ *            waves when the HBM cache holds fewer experts than the step needs.
+ * shared_w   HOST array of n_shared device pointers (ignored when run_shared == 0)
+ * y          device [T*k_big, H] fp32 (rows >= P untouched)
+ * shared_out device [n_shared, T, H] fp32 (NULL allowed when nothing shared is run)
+ * run_routed / run_shared  select which of the two parts this call computes
+ * ws         device scratch holding the SwiGLU activations
+ * The number of pairs per expert is read on the device; the host never waits for it.
+ */
+size_t moe_expert_ffn_workspace_bytes(const moe_config* cfg);
+int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_t* expert_offsets,
+                   const int32_t* sorted_token, const void* const* expert_w,
+                   const void* const* shared_w, int run_routed, int run_shared, float* y,
+                   float* shared_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * "... and finally summed" (Sec. II-A):
+ *   out[t][:] = sum_{j < k_t[t]} topk_w[t][j] * y[inv_pos[t][j]][:]  +  sum_s shared_out[s][t][:]
+ * summed in fp32 in ascending j, then s.   out device [T,H] dtype.
+ */
+int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,
+                const int32_t* inv_pos, const int32_t* k_t, const float* shared_out, void* out,
+                void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Fallback fetch and prefetch of expert weights (Sec. II-B: experts stay in host DRAM and are
+ * loaded when the router asks for them; Sec. III-B: for a token that falls back, the router
+ * outputs of its discarded little pass name the experts of the big pass ahead of time, for
+ * any number of layers ahead).
+ *
+ * The cache is a set of n_slots HBM slots of blob_bytes each, filled by hipMemcpyAsync from a
+ * pinned host arena holding all E blobs back to back, on a side stream of default priority.
+ * Policy (deterministic, host-side integers only):
+ *   - every call advances a logical clock; every expert the call names that is resident
+ *     afterwards gets that time stamp
+ *   - MOE_FETCH_DEMAND: n <= n_slots distinct experts.  Resident ones are hits.  Misses are
+ *     loaded in ascending expert id; the victim is the least recently stamped slot that holds
+ *     no expert of this call, lowest slot id first among equals (empty slots are oldest).
+ *     The compute stream is made to wait for the copies, and the device pointer table
+ *     (moe_cache_expert_table) is rewritten on the compute stream so that exactly the experts
+ *     of this call point at their slots and all others are NULL.
+ *   - MOE_FETCH_PREFETCH: any n, experts in priority order.  Resident ones are re-stamped.
+ *     A miss is loaded only if a victim exists that is neither named by this call nor part of
+ *     the most recent DEMAND call; otherwise it is dropped (slot_of = -1).  The pointer table
+ *     and the compute stream are not touched.
+ *   - a copy into a slot never starts before the kernels that were enqueued on the compute
+ *     stream, up to the time of this call, have finished reading the slot's previous expert.
+ */
+typedef struct moe_cache moe_cache_t;
+
+enum { MOE_FETCH_DEMAND = 0, MOE_FETCH_PREFETCH = 1 };
+
+typedef struct moe_fetch_stats {
+  int32_t hits;       /* named experts already resident                 */
+  int32_t misses;     /* experts copied by this call                    */
+  int32_t dropped;    /* PREFETCH only: misses without an evictable slot */
+  int32_t reserved;
+  uint64_t bytes_h2d; /* misses * blob_bytes                            */
+} moe_fetch_stats;
+
+/* host_blobs: pinned host memory, E * blob_bytes, must outlive the cache.
+ * device_slots: device memory, n_slots * blob_bytes, caller-owned, 256-byte aligned.
+ * Creates the side stream and the events; returns NULL on failure (see moe_last_error). */
+moe_cache_t* moe_cache_create(int32_t E, size_t blob_bytes, int32_t n_slots,
+                              const void* host_blobs, void* device_slots);
+void moe_cache_destroy(moe_cache_t* cache);
+
+/* DEVICE array of E device pointers, owned by the cache: pass it as expert_w. */
+const void* const* moe_cache_expert_table(moe_cache_t* cache);
+
+/* expert_ids host [n]; slot_of host [n] out (slot index, or -1 when dropped); stats may be NULL.
+ * compute_stream: the stream the consuming kernels run on. */
+int expert_cache_fetch(moe_cache_t* cache, const int32_t* expert_ids, int32_t n, int32_t mode,
+                       int32_t* slot_of, moe_fetch_stats* stats, void* compute_stream);
+
+/* Host-side view of the cache state (tests, metrics): resident_expert host [n_slots] out,
+ * -1 for an empty slot.  Returns n_slots. */
+int moe_cache_snapshot(moe_cache_t* cache, int32_t* resident_expert);
+
+/* Blocks the host until every copy issued so far has landed (tests, shutdown). */
+int moe_cache_sync(moe_cache_t* cache);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOBILE_MOE_H_ */

@@ -1,0 +1,276 @@
+"""ctypes front end of ``libmobile_moe.so`` -- argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+``include/mobile_moe.h``; tensors are torch tensors (device memory and streams are all that
+torch is used for) and are passed down as raw pointers.  Nothing is computed in Python, and
+there is no fallback: if the HIP library is missing, loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+from .workloads import LayerConfig
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmobile_moe.so")
+
+MOE_BF16, MOE_FP32 = 0, 1
+MOE_FETCH_DEMAND, MOE_FETCH_PREFETCH = 0, 1
+MOE_MAX_SHARED = 4
+MOE_OK = 0
+ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "MOE_E_HIP",
+          -5: "MOE_E_CACHE_FULL", -6: "MOE_E_WORKSPACE"}
+
+EXPORTS = ("moe_last_error", "moe_device_info", "moe_route", "moe_token_confidence",
+           "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_expert_ffn_workspace_bytes",
+           "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
+           "moe_cache_expert_table", "expert_cache_fetch", "moe_cache_snapshot", "moe_cache_sync")
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{ERRORS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class moe_config(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("H", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("I", ctypes.c_int32), ("k_big", ctypes.c_int32), ("k_little", ctypes.c_int32),
+                ("n_shared", ctypes.c_int32), ("shared_I", ctypes.c_int32 * MOE_MAX_SHARED),
+                ("dtype", ctypes.c_int32), ("renorm", ctypes.c_int32), ("gamma", ctypes.c_float)]
+
+
+class moe_fetch_stats(ctypes.Structure):
+    _fields_ = [("hits", ctypes.c_int32), ("misses", ctypes.c_int32), ("dropped", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("bytes_h2d", ctypes.c_uint64)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the HIP library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           "`python -m paper_2510_12357_amd.build` (hipcc, gfx950)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    cfgp = ctypes.POINTER(moe_config)
+    lib.moe_last_error.restype = ctypes.c_char_p
+    lib.moe_last_error.argtypes = []
+    lib.moe_device_info.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.moe_route.argtypes = [cfgp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp]
+    lib.moe_token_confidence.argtypes = [vp, i32, i32, vp, vp]
+    lib.moe_dispatch_workspace_bytes.argtypes = [cfgp]
+    lib.moe_dispatch_workspace_bytes.restype = sz
+    lib.moe_dispatch.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_expert_ffn_workspace_bytes.argtypes = [cfgp]
+    lib.moe_expert_ffn_workspace_bytes.restype = sz
+    lib.moe_expert_ffn.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
+                                   ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.moe_combine.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
+    lib.moe_cache_create.argtypes = [i32, sz, i32, vp, vp]
+    lib.moe_cache_create.restype = vp
+    lib.moe_cache_destroy.argtypes = [vp]
+    lib.moe_cache_destroy.restype = None
+    lib.moe_cache_expert_table.argtypes = [vp]
+    lib.moe_cache_expert_table.restype = vp
+    lib.expert_cache_fetch.argtypes = [vp, ctypes.POINTER(i32), i32, i32, ctypes.POINTER(i32),
+                                       ctypes.POINTER(moe_fetch_stats), vp]
+    lib.moe_cache_snapshot.argtypes = [vp, ctypes.POINTER(i32)]
+    lib.moe_cache_sync.argtypes = [vp]
+    for name in ("moe_device_info", "moe_route", "moe_token_confidence", "moe_dispatch",
+                 "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_cache_snapshot",
+                 "moe_cache_sync"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> None:
+    if rc != MOE_OK:
+        raise MoeError(rc, load_library().moe_last_error().decode())
+
+
+def make_config(cfg: LayerConfig, T: Optional[int] = None) -> moe_config:
+    c = moe_config()
+    c.T = cfg.T if T is None else T
+    c.H, c.E, c.I, c.k_big, c.k_little = cfg.H, cfg.E, cfg.I, cfg.k_big, cfg.k_little
+    c.n_shared = len(cfg.shared_I)
+    for i, v in enumerate(cfg.shared_I):
+        c.shared_I[i] = v
+    c.dtype = MOE_FP32 if cfg.dtype == "fp32" else MOE_BF16
+    c.renorm = int(cfg.renorm)
+    c.gamma = cfg.gamma
+    return c
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors passed to the C ABI must be dense"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, torch.cuda.Stream):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+# ------------------------------------------------------------------------------ entry points
+def moe_last_error() -> str:
+    return load_library().moe_last_error().decode()
+
+
+def moe_device_info():
+    n_cu, is950 = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(load_library().moe_device_info(ctypes.byref(n_cu), ctypes.byref(is950)))
+    return n_cu.value, bool(is950.value)
+
+
+def moe_route(cfg: moe_config, x, Wg, gate_bias, conf, logits, logits_given, topk_idx, topk_w,
+              important, k_t, stream=None) -> None:
+    _check(load_library().moe_route(ctypes.byref(cfg), _ptr(x), _ptr(Wg), _ptr(gate_bias), _ptr(conf),
+                                    _ptr(logits), int(bool(logits_given)), _ptr(topk_idx),
+                                    _ptr(topk_w), _ptr(important), _ptr(k_t), _stream(stream)))
+
+
+def moe_token_confidence(lm_logits, T: int, V: int, conf, stream=None) -> None:
+    _check(load_library().moe_token_confidence(_ptr(lm_logits), T, V, _ptr(conf), _stream(stream)))
+
+
+def moe_dispatch_workspace_bytes(cfg: moe_config) -> int:
+    return int(load_library().moe_dispatch_workspace_bytes(ctypes.byref(cfg)))
+
+
+def moe_dispatch(cfg: moe_config, topk_idx, k_t, expert_offsets, sorted_token, sorted_rank,
+                 inv_pos, ws, ws_bytes: int, stream=None) -> None:
+    _check(load_library().moe_dispatch(ctypes.byref(cfg), _ptr(topk_idx), _ptr(k_t),
+                                       _ptr(expert_offsets), _ptr(sorted_token), _ptr(sorted_rank),
+                                       _ptr(inv_pos), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def moe_expert_ffn_workspace_bytes(cfg: moe_config) -> int:
+    return int(load_library().moe_expert_ffn_workspace_bytes(ctypes.byref(cfg)))
+
+
+def moe_expert_ffn(cfg: moe_config, x, expert_offsets, sorted_token, expert_w, shared_w: Sequence,
+                   run_routed, run_shared, y, shared_out, ws, ws_bytes: int, stream=None) -> None:
+    """expert_w: device int64 tensor [E] of blob addresses, or a raw device address (int);
+    shared_w: sequence of device tensors (their addresses form the host pointer array)."""
+    sw = (ctypes.c_void_p * max(1, len(shared_w)))(*[t.data_ptr() for t in shared_w])
+    ew = ctypes.c_void_p(expert_w) if isinstance(expert_w, int) else _ptr(expert_w)
+    _check(load_library().moe_expert_ffn(ctypes.byref(cfg), _ptr(x), _ptr(expert_offsets),
+                                         _ptr(sorted_token), ew, sw, int(bool(run_routed)),
+                                         int(bool(run_shared)), _ptr(y), _ptr(shared_out), _ptr(ws),
+                                         ws_bytes, _stream(stream)))
+
+
+def moe_combine(cfg: moe_config, y, topk_w, inv_pos, k_t, shared_out, out, stream=None) -> None:
+    _check(load_library().moe_combine(ctypes.byref(cfg), _ptr(y), _ptr(topk_w), _ptr(inv_pos),
+                                      _ptr(k_t), _ptr(shared_out), _ptr(out), _stream(stream)))
+
+
+def moe_cache_create(E: int, blob_bytes: int, n_slots: int, host_blobs: torch.Tensor,
+                     device_slots: torch.Tensor) -> int:
+    assert host_blobs.is_pinned(), "host arena must be pinned memory"
+    h = load_library().moe_cache_create(E, blob_bytes, n_slots, _ptr(host_blobs), _ptr(device_slots))
+    if not h:
+        raise MoeError(-1, moe_last_error())
+    return h
+
+
+def moe_cache_destroy(cache: int) -> None:
+    load_library().moe_cache_destroy(ctypes.c_void_p(cache))
+
+
+def moe_cache_expert_table(cache: int) -> int:
+    return int(load_library().moe_cache_expert_table(ctypes.c_void_p(cache)))
+
+
+def expert_cache_fetch(cache: int, expert_ids: Sequence[int], mode: int, stream=None):
+    """-> (slot_of list, moe_fetch_stats)"""
+    n = len(expert_ids)
+    ids = (ctypes.c_int32 * max(1, n))(*expert_ids)
+    slots = (ctypes.c_int32 * max(1, n))()
+    st = moe_fetch_stats()
+    _check(load_library().expert_cache_fetch(ctypes.c_void_p(cache), ids, n, mode, slots,
+                                             ctypes.byref(st), _stream(stream)))
+    return list(slots[:n]), st
+
+
+def moe_cache_snapshot(cache: int, n_slots: int):
+    out = (ctypes.c_int32 * n_slots)()
+    rc = load_library().moe_cache_snapshot(ctypes.c_void_p(cache), out)
+    if rc < 0:
+        _check(rc)
+    return list(out)
+
+
+def moe_cache_sync(cache: int) -> None:
+    _check(load_library().moe_cache_sync(ctypes.c_void_p(cache)))
+
+
+# ------------------------------------------------------------------------------ plumbing helpers
+def torch_dtype(cfg: LayerConfig):
+    return torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
+
+
+def to_device(a, cfg: LayerConfig, device="cuda") -> torch.Tensor:
+    """Uploads a stored host tensor (float32, or uint16 holding bf16 bits) without changing bits."""
+    import numpy as np
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+class StepBuffers:
+    """Device buffers of one layer step (allocation only; the step itself is the C calls)."""
+
+    def __init__(self, cfg: LayerConfig, T: Optional[int] = None, device="cuda"):
+        T = cfg.T if T is None else T
+        self.cfg, self.T = cfg, T
+        self.c = make_config(cfg, T)
+        K, E, H = cfg.k_big, cfg.E, cfg.H
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.logits = torch.empty((T, E), **f32)
+        self.topk_idx = torch.empty((T, K), **i32)
+        self.topk_w = torch.empty((T, K), **f32)
+        self.important = torch.empty((T,), dtype=torch.uint8, device=device)
+        self.k_t = torch.empty((T,), **i32)
+        self.expert_offsets = torch.empty((E + 1,), **i32)
+        self.sorted_token = torch.empty((T * K,), **i32)
+        self.sorted_rank = torch.empty((T * K,), **i32)
+        self.inv_pos = torch.empty((T, K), **i32)
+        self.y = torch.zeros((T * K, H), **f32)
+        ns = len(cfg.shared_I)
+        self.shared_out = torch.zeros((ns, T, H), **f32) if ns else None
+        self.out = torch.empty((T, H), dtype=torch_dtype(cfg), device=device)
+        self.dws_bytes = moe_dispatch_workspace_bytes(self.c)
+        self.dws = torch.empty((self.dws_bytes,), dtype=torch.uint8, device=device)
+        self.fws_bytes = moe_expert_ffn_workspace_bytes(self.c)
+        self.fws = torch.empty((self.fws_bytes,), dtype=torch.uint8, device=device)
+
+
+def layer_step(b: StepBuffers, x, Wg, gate_bias, conf, expert_table, shared_w, logits_given=False,
+               stream=None) -> torch.Tensor:
+    """One step of the layer with all experts resident: the four C calls back to back."""
+    moe_route(b.c, x, Wg, gate_bias, conf, b.logits, logits_given, b.topk_idx, b.topk_w, b.important,
+              b.k_t, stream)
+    moe_dispatch(b.c, b.topk_idx, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                 b.dws, b.dws_bytes, stream)
+    moe_expert_ffn(b.c, x, b.expert_offsets, b.sorted_token, expert_table, shared_w, True, True, b.y,
+                   b.shared_out, b.fws, b.fws_bytes, stream)
+    moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out, stream)
+    return b.out

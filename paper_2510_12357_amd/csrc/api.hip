@@ -1,0 +1,196 @@
+// C-ABI entry points: host-side validation and kernel sequencing.  Every shape is checked here
+// against what the kernels and their grids assume before anything is enqueued.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "internal.h"
+
+namespace mm {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  if (e == hipSuccess) return MOE_OK;
+  return fail(MOE_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int device_cu_count() {
+  static thread_local int cached_dev = -1, cached_cu = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (dev != cached_dev) {
+    int cu = 0;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) cu = 256;
+    cached_dev = dev; cached_cu = cu;
+  }
+  return cached_cu;
+}
+
+int validate_config(const moe_config* c) {
+  if (!c) return fail(MOE_E_BADARG, "config is NULL");
+  if (c->dtype != MOE_BF16 && c->dtype != MOE_FP32) return fail(MOE_E_BADARG, "dtype %d", c->dtype);
+  if (c->T < 0 || c->H <= 0 || c->E <= 0 || c->I <= 0) return fail(MOE_E_SHAPE, "T=%d H=%d E=%d I=%d", c->T, c->H, c->E, c->I);
+  if (c->k_little < 1 || c->k_little > c->k_big || c->k_big > c->E)
+    return fail(MOE_E_SHAPE, "need 1 <= k_little (%d) <= k_big (%d) <= E (%d)", c->k_little, c->k_big, c->E);
+  if (c->E > MOE_MAX_EXPERTS) return fail(MOE_E_UNSUPPORTED, "E=%d above %d", c->E, MOE_MAX_EXPERTS);
+  if (c->k_big > MOE_MAX_TOPK) return fail(MOE_E_UNSUPPORTED, "k_big=%d above %d", c->k_big, MOE_MAX_TOPK);
+  if (c->n_shared < 0 || c->n_shared > MOE_MAX_SHARED) return fail(MOE_E_UNSUPPORTED, "n_shared=%d outside [0,%d]", c->n_shared, MOE_MAX_SHARED);
+  if (c->H % 8 || c->I % 8) return fail(MOE_E_UNSUPPORTED, "H=%d and I=%d must be multiples of 8", c->H, c->I);
+  int maxdim = c->H > c->I ? c->H : c->I;
+  for (int s = 0; s < c->n_shared; ++s) {
+    if (c->shared_I[s] <= 0 || c->shared_I[s] % 8) return fail(MOE_E_UNSUPPORTED, "shared_I[%d]=%d must be a positive multiple of 8", s, c->shared_I[s]);
+    if (c->shared_I[s] > maxdim) maxdim = c->shared_I[s];
+  }
+  if ((long long)c->T * c->k_big * (long long)maxdim >= (1ll << 31))
+    return fail(MOE_E_UNSUPPORTED, "T*k_big*max(H,I) = %lld does not fit 31 bits", (long long)c->T * c->k_big * maxdim);
+  if (!(c->gamma == c->gamma)) return fail(MOE_E_BADARG, "gamma is NaN");
+  return MOE_OK;
+}
+
+namespace {
+struct FfnLayout {
+  size_t h_routed, h_shared[MOE_MAX_SHARED], total;
+};
+FfnLayout ffn_layout(const moe_config& c) {
+  FfnLayout L;
+  size_t off = 0;
+  const size_t eb = elem_bytes(c.dtype);
+  L.h_routed = off;
+  off += align256((size_t)c.T * c.k_big * c.I * eb);
+  for (int s = 0; s < MOE_MAX_SHARED; ++s) {
+    L.h_shared[s] = off;
+    if (s < c.n_shared) off += align256((size_t)c.T * c.shared_I[s] * eb);
+  }
+  L.total = off < 256 ? 256 : off;
+  return L;
+}
+}  // namespace
+
+}  // namespace mm
+
+using namespace mm;
+
+extern "C" const char* moe_last_error(void) { return g_err; }
+
+extern "C" int moe_device_info(int32_t* n_cu, int32_t* is_gfx950) {
+  int dev = 0;
+  MM_HIP(hipGetDevice(&dev));
+  hipDeviceProp_t p;
+  MM_HIP(hipGetDeviceProperties(&p, dev));
+  if (n_cu) *n_cu = p.multiProcessorCount;
+  if (is_gfx950) *is_gfx950 = (strncmp(p.gcnArchName, "gfx950", 6) == 0) ? 1 : 0;
+  return MOE_OK;
+}
+
+extern "C" int moe_route(const moe_config* cfg, const void* x, const void* Wg, const float* gate_bias,
+                         const float* conf, float* logits, int logits_given, int32_t* topk_idx,
+                         float* topk_w, uint8_t* important, int32_t* k_t, void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (cfg->T == 0) return MOE_OK;
+  if (!logits || !topk_idx || !topk_w || !important || !k_t)
+    return fail(MOE_E_BADARG, "moe_route: logits/topk_idx/topk_w/important/k_t must not be NULL");
+  if (!logits_given && (!x || !Wg)) return fail(MOE_E_BADARG, "moe_route: x and Wg are needed unless logits_given");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!logits_given) {
+    StreamArgs a = {};
+    a.T = cfg->T; a.H = cfg->H; a.E = cfg->E; a.I = cfg->I;
+    a.x = x; a.Wg = Wg; a.bias = gate_bias; a.logits = logits;
+    rc = launch_stream(kRouter, cfg->dtype, a, s);
+    if (rc) return rc;
+  }
+  return launch_route(*cfg, conf, logits, topk_idx, topk_w, important, k_t, s);
+}
+
+extern "C" int moe_token_confidence(const float* lm_logits, int32_t T, int32_t V, float* conf, void* stream) {
+  if (T < 0 || V <= 0) return fail(MOE_E_SHAPE, "moe_token_confidence: T=%d V=%d", T, V);
+  if (T > 0 && (!lm_logits || !conf)) return fail(MOE_E_BADARG, "moe_token_confidence: null pointer");
+  return launch_confidence(lm_logits, T, V, conf, static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t moe_dispatch_workspace_bytes(const moe_config* cfg) {
+  if (validate_config(cfg)) return 0;
+  return align256(sizeof(int32_t) * (size_t)cfg->E);
+}
+
+extern "C" int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t,
+                            int32_t* expert_offsets, int32_t* sorted_token, int32_t* sorted_rank,
+                            int32_t* inv_pos, void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!expert_offsets) return fail(MOE_E_BADARG, "moe_dispatch: expert_offsets is NULL");
+  if (cfg->T > 0 && (!topk_idx || !k_t || !sorted_token || !sorted_rank || !inv_pos))
+    return fail(MOE_E_BADARG, "moe_dispatch: null tensor");
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < moe_dispatch_workspace_bytes(cfg))
+    return fail(MOE_E_WORKSPACE, "moe_dispatch: workspace %p of %zu bytes (need %zu, 256-byte aligned)", ws,
+                ws_bytes, moe_dispatch_workspace_bytes(cfg));
+  return launch_dispatch(*cfg, topk_idx, k_t, expert_offsets, sorted_token, sorted_rank, inv_pos,
+                         static_cast<int32_t*>(ws), static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t moe_expert_ffn_workspace_bytes(const moe_config* cfg) {
+  if (validate_config(cfg)) return 0;
+  return ffn_layout(*cfg).total;
+}
+
+extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_t* expert_offsets,
+                              const int32_t* sorted_token, const void* const* expert_w,
+                              const void* const* shared_w, int run_routed, int run_shared, float* y,
+                              float* shared_out, void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  const bool routed = run_routed != 0;
+  const bool shared = run_shared != 0 && cfg->n_shared > 0;
+  if (cfg->T == 0 || (!routed && !shared)) return MOE_OK;
+  if (!x) return fail(MOE_E_BADARG, "moe_expert_ffn: x is NULL");
+  if (routed && (!expert_offsets || !sorted_token || !expert_w || !y))
+    return fail(MOE_E_BADARG, "moe_expert_ffn: routed part needs expert_offsets, sorted_token, expert_w, y");
+  if (shared && (!shared_w || !shared_out))
+    return fail(MOE_E_BADARG, "moe_expert_ffn: shared part needs shared_w and shared_out");
+  if (shared)
+    for (int s = 0; s < cfg->n_shared; ++s)
+      if (!shared_w[s]) return fail(MOE_E_BADARG, "moe_expert_ffn: shared_w[%d] is NULL", s);
+  const FfnLayout L = ffn_layout(*cfg);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < L.total)
+    return fail(MOE_E_WORKSPACE, "moe_expert_ffn: workspace %p of %zu bytes (need %zu, 256-byte aligned)", ws,
+                ws_bytes, L.total);
+
+  StreamArgs a = {};
+  a.T = cfg->T; a.H = cfg->H; a.E = cfg->E; a.I = cfg->I;
+  a.n_routed = routed ? cfg->E : 0;
+  a.n_shared = shared ? cfg->n_shared : 0;
+  a.expert_w = expert_w; a.offsets = expert_offsets; a.sorted_token = sorted_token;
+  a.max_pairs = cfg->T * cfg->k_big;
+  a.x = x; a.y = y; a.shared_out = shared_out;
+  char* wsb = static_cast<char*>(ws);
+  a.h_routed = wsb + L.h_routed;
+  for (int s = 0; s < a.n_shared; ++s) {
+    a.shared_I[s] = cfg->shared_I[s];
+    a.shared_w[s] = shared_w[s];
+    a.h_shared[s] = wsb + L.h_shared[s];
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = launch_stream(kGateUp, cfg->dtype, a, s);
+  if (rc) return rc;
+  return launch_stream(kDown, cfg->dtype, a, s);
+}
+
+extern "C" int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,
+                           const int32_t* inv_pos, const int32_t* k_t, const float* shared_out, void* out,
+                           void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (cfg->T == 0) return MOE_OK;
+  if (!y || !topk_w || !inv_pos || !k_t || !out) return fail(MOE_E_BADARG, "moe_combine: null tensor");
+  if (cfg->n_shared > 0 && !shared_out) return fail(MOE_E_BADARG, "moe_combine: shared_out is NULL but n_shared=%d", cfg->n_shared);
+  return launch_combine(*cfg, y, topk_w, inv_pos, k_t, shared_out, out, static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,67 @@
+// Internal declarations shared by the translation units of libmobile_moe.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mobile_moe.h"
+
+namespace mm {
+
+// ---- error reporting (thread-local message behind moe_last_error) -------------------------
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int hip_fail(hipError_t e, const char* what);
+#define MM_HIP(expr)                                   \
+  do {                                                 \
+    hipError_t _e = (expr);                            \
+    if (_e != hipSuccess) return ::mm::hip_fail(_e, #expr); \
+  } while (0)
+
+int validate_config(const moe_config* cfg);
+int device_cu_count();
+
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+inline size_t elem_bytes(int dtype) { return dtype == MOE_FP32 ? 4 : 2; }
+
+// ---- skinny grouped GEMM  D[r][n] = sum_k W[n][k] * B[r][k]  (weights streamed once) --------
+// Three uses: router logits, gate/up projection with fused SwiGLU, down projection.
+enum StreamMode { kRouter = 0, kGateUp = 1, kDown = 2 };
+
+struct StreamArgs {
+  int T, H, E, I;
+  int n_routed;                       // E when the routed experts are run, else 0
+  int n_shared;                       // shared experts run by this launch
+  int shared_I[MOE_MAX_SHARED];
+  const void* shared_w[MOE_MAX_SHARED];
+  const void* const* expert_w;        // device table [E]
+  const int32_t* offsets;             // device [E+1]
+  const int32_t* sorted_token;        // device [T*k_big]
+  int max_pairs;                      // T * k_big
+  const void* x;                      // [T,H]
+  void* h_routed;                     // [T*k_big, I]   SwiGLU activations (storage dtype)
+  void* h_shared[MOE_MAX_SHARED];     // [T, I_s]
+  float* y;                           // [T*k_big, H]
+  float* shared_out;                  // [n_shared, T, H]
+  const void* Wg;                     // router: [E,H]
+  const float* bias;                  // router: [E] or null
+  float* logits;                      // router: [T,E]
+};
+
+int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s);
+
+// ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime, bf16) -------------------------
+int launch_tiled_ffn(const StreamArgs& a, hipStream_t s);
+
+// ---- selection, dispatch, combine -----------------------------------------------------------
+int launch_route(const moe_config& c, const float* conf, const float* logits, int32_t* idx,
+                 float* w, uint8_t* important, int32_t* k_t, hipStream_t s);
+int launch_confidence(const float* z, int T, int V, float* conf, hipStream_t s);
+int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int32_t* offsets,
+                    int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos, int32_t* counts,
+                    hipStream_t s);
+int launch_combine(const moe_config& c, const float* y, const float* w, const int32_t* inv_pos,
+                   const int32_t* k_t, const float* shared_out, void* out, hipStream_t s);
+int launch_table_update(const void** table, int E, const int32_t* ids, const int32_t* slots, int n,
+                        char* slot_base, size_t blob_bytes, hipStream_t s);
+
+}  // namespace mm
