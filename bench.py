@@ -1,0 +1,294 @@
+#!/usr/bin/env python3
+"""Benchmark of the big-little MoE layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra]
+
+A step is one pass of the whole hot path (moe_route -> moe_dispatch -> moe_expert_ffn ->
+moe_combine, all through the C ABI) over one batch of seeded synthetic input that is already
+resident in HBM.  Consecutive steps cycle through several distinct layers (weights and
+activations), so that a step's weights come from HBM and not from the last-level cache.
+
+Prints ONE JSON line: whole-job tokens/s (`value`), the roofline of the dominant kernel (the
+gate+up weight-streaming FFN kernel, timed with HIP events around each of its launches in a
+second pass of the same K steps), the CPU oracle timed on the host cores on a bounded sample,
+and under `extra` the other decode batch sizes, the prefill layer and the modeled speedup of
+the paper's Eq. 1 from measured all-little / all-big step times.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="fine60_decode_b64",
+                    help="fine60_decode_b{1,8,32,64} | fine64_prefill | coarse8_decode_b1 | coarse8_prefill")
+    ap.add_argument("--ratio", type=float, default=0.2, help="fallback ratio r of the synthetic confidences")
+    ap.add_argument("--layers", type=int, default=0, help="distinct layers cycled (0 = auto)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+def workload_config(name: str, ratio: float):
+    from paper_2510_12357_amd import workloads as wl
+    if name.startswith("fine60_decode_b"):
+        return wl.CONFIGS["fine60_decode"].with_(T=int(name.split("_b")[1]), fallback_ratio=ratio)
+    if name == "fine64_prefill":
+        return wl.CONFIGS["fine64_prefill"].with_(fallback_ratio=ratio)
+    if name == "coarse8_prefill":
+        return wl.CONFIGS["coarse8"].with_(fallback_ratio=ratio)
+    if name.startswith("coarse8_decode_b"):
+        return wl.CONFIGS["coarse8"].with_(T=int(name.split("_b")[1]), fallback_ratio=ratio)
+    raise SystemExit(f"unknown workload {name}")
+
+
+class DeviceLayers:
+    """L synthetic layers generated on the device with a seeded torch generator (inputs only)."""
+
+    def __init__(self, cfg, L: int, seed: int = 0):
+        import torch
+        from paper_2510_12357_amd import workloads as wl
+        self.cfg, self.L = cfg, L
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+        blob = 3 * cfg.H * cfg.I
+
+        def randn(shape, std):
+            return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+
+        self.x, self.Wg, self.bias, self.experts, self.table, self.shared, self.conf = [], [], [], [], [], [], []
+        for l in range(L):
+            self.x.append(randn((cfg.T, cfg.H), 1.0))
+            self.Wg.append(randn((cfg.E, cfg.H), cfg.gate_std))
+            self.bias.append(torch.randn((cfg.E,), generator=g, device="cuda") * cfg.gate_bias_std
+                             if cfg.gate_bias_std > 0 else None)
+            ex = torch.empty((cfg.E, blob), dtype=dt, device="cuda")
+            for e in range(cfg.E):                       # expert by expert: bounded fp32 temporaries
+                ex[e] = randn((blob,), cfg.w_std)
+            self.experts.append(ex)
+            stride = ex.stride(0) * ex.element_size()
+            self.table.append(torch.tensor([ex.data_ptr() + e * stride for e in range(cfg.E)],
+                                           dtype=torch.int64, device="cuda"))
+            self.shared.append([randn((3 * cfg.H * Is,), cfg.w_std) for Is in cfg.shared_I])
+            conf = wl.make_confidence(seed + l, cfg.T, cfg.gamma, cfg.fallback_ratio)
+            self.conf.append(torch.from_numpy(conf).cuda())
+        torch.cuda.synchronize()
+
+    def bytes_per_layer(self) -> int:
+        c = self.cfg
+        eb = 2 if c.dtype == "bf16" else 4
+        return eb * (c.E * 3 * c.H * c.I + sum(3 * c.H * i for i in c.shared_I) + c.E * c.H)
+
+
+def auto_layers(cfg) -> int:
+    eb = 2 if cfg.dtype == "bf16" else 4
+    per = eb * (cfg.E * 3 * cfg.H * cfg.I + sum(3 * cfg.H * i for i in cfg.shared_I))
+    # enough distinct weights that a layer is evicted from the 256 MB last-level cache before
+    # it is reused, within a budget of ~12 GB
+    return int(max(2, min(8, (12 << 30) // per)))
+
+
+def run_steps(mm, torch, layers: DeviceLayers, bufs, n: int, first: int = 0):
+    L = layers.L
+    for i in range(first, first + n):
+        l = i % L
+        mm.layer_step(bufs, layers.x[l], layers.Wg[l], layers.bias[l], layers.conf[l], layers.table[l],
+                      layers.shared[l])
+
+
+def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: bool = True):
+    """-> dict with ms_per_step, tokens/s, per-kernel ms, routing statistics"""
+    L = L or auto_layers(cfg)
+    layers = DeviceLayers(cfg, L)
+    bufs = mm.StepBuffers(cfg)
+    run_steps(mm, torch, layers, bufs, warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(mm, torch, layers, bufs, steps, first=warmup)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    res = dict(ms_per_step=dt * 1e3 / steps, tokens_per_s=cfg.T * steps / dt, layers=L)
+
+    # routing statistics of the timed layers: pairs P and distinct experts D per step
+    Ps, Ds = [], []
+    for l in range(L):
+        run_steps(mm, torch, layers, bufs, 1, first=l)
+        torch.cuda.synchronize()
+        off = bufs.expert_offsets.cpu().numpy()
+        Ps.append(int(off[-1]))
+        Ds.append(int((np.diff(off) > 0).sum()))
+    res["P_mean"], res["D_mean"] = float(np.mean(Ps)), float(np.mean(Ds))
+
+    if profile:
+        mm.moe_profile_enable(True)
+        run_steps(mm, torch, layers, bufs, steps, first=warmup)
+        torch.cuda.synchronize()
+        kern = {}
+        for k, name in enumerate(mm.PROFILE_KINDS):
+            n, ms = mm.moe_profile_read(k)
+            if n:
+                kern[name] = dict(launches=n, avg_us=ms * 1e3 / n)
+        mm.moe_profile_enable(False)
+        res["kernels"] = kern
+    res["_layers"], res["_bufs"] = layers, bufs
+    return res
+
+
+def algorithmic_work(cfg, P: float, D: float):
+    """Bytes and flops one step must move / do (weights of the D touched experts once, the shared
+    experts, the router, activations in and out; flops of the P pair FFNs, shared FFNs, router)."""
+    eb = 2 if cfg.dtype == "bf16" else 4
+    H, I, T, E = cfg.H, cfg.I, cfg.T, cfg.E
+    sh = sum(cfg.shared_I)
+    step_bytes = eb * (D * 3 * H * I + 3 * H * sh + E * H) + 2 * eb * T * H
+    step_flops = 2 * 3 * H * I * P + 2 * T * 3 * H * sh + 2 * T * E * H
+    # gate+up kernel alone: two of the three matrices of every touched expert and shared expert,
+    # the activations it reads, the SwiGLU activations it writes
+    gu_bytes = eb * (D * 2 * H * I + 2 * H * sh) + eb * T * H + eb * (P * I + T * sh)
+    gu_flops = 2 * 2 * H * I * P + 2 * T * 2 * H * sh
+    dn_bytes = eb * (D * H * I + H * sh) + eb * (P * I + T * sh) + 4 * (P * H + len(cfg.shared_I) * T * H)
+    return dict(step_bytes=step_bytes, step_flops=step_flops, gate_up_bytes=gu_bytes,
+                gate_up_flops=gu_flops, down_bytes=dn_bytes)
+
+
+def cpu_baseline(torch, cfg, layers: DeviceLayers, budget_s: float = 12.0):
+    """The oracle as it stands, on the host cores, on the tokens of layer 0 (bounded sample)."""
+    import oracle
+
+    def host(t):
+        t = t.detach().cpu()
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).numpy().view(np.uint16)
+        return t.numpy()
+
+    x = host(layers.x[0])
+    Wg = host(layers.Wg[0])
+    bias = None if layers.bias[0] is None else host(layers.bias[0])
+    ew = [host(layers.experts[0][e]) for e in range(cfg.E)]
+    sw = [host(s) for s in layers.shared[0]]
+    conf = host(layers.conf[0])
+    n_tok = min(cfg.T, 64)
+    done_tokens, t_used = 0, 0.0
+    while True:
+        t0 = time.perf_counter()
+        oracle.moe_layer(x[:n_tok], Wg, bias, ew, cfg.I, sw, cfg.shared_I, conf[:n_tok], cfg.gamma,
+                         cfg.k_big, cfg.k_little, cfg.renorm)
+        t_used += time.perf_counter() - t0
+        done_tokens += n_tok
+        if t_used >= budget_s or done_tokens >= 64 * 64:
+            break
+    return dict(value=done_tokens / t_used, unit="tokens/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{done_tokens} tokens of layer 0 ({n_tok} per call, {t_used:.1f} s, fp64, OpenMP)")
+
+
+def stored_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
+    p = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(p) as f:
+            return json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures the single-GPU hot path only: every box of this build has "
+                         "one GPU, so --gpus N with N > 1 is not run (value is one GPU's throughput).")
+    import torch
+    from paper_2510_12357_amd import binding as mm
+    mm.load_library()                         # fails loudly when the HIP library is missing
+    if not torch.cuda.is_available():
+        raise SystemExit("no GPU visible")
+    torch.cuda.set_device(0)
+
+    cfg = workload_config(args.workload, args.ratio)
+    main_res = time_workload(mm, torch, cfg, args.steps, args.warmup, args.layers)
+    work = algorithmic_work(cfg, main_res["P_mean"], main_res["D_mean"])
+    kern = main_res["kernels"]
+    gu = kern["ffn_gate_up"]
+    prefill = cfg.T >= 1024
+    if prefill and work["gate_up_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e12 > work["gate_up_bytes"] / HBM_PEAK_GBS / 1e9:
+        ach = work["gate_up_flops"] / (gu["avg_us"] * 1e-6) / 1e12
+        roofline = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=stored_traffic(args.workload))
+    else:
+        ach = work["gate_up_bytes"] / (gu["avg_us"] * 1e-6) / 1e9
+        roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
+                        traffic=stored_traffic(args.workload))
+    roofline["kernel"] = "stream_kernel<BF16,kGateUp> (ffn_gate_up)"
+    roofline["avg_us"] = gu["avg_us"]
+    roofline["algorithmic_bytes"] = work["gate_up_bytes"]
+
+    cpu = None if args.no_cpu else cpu_baseline(torch, cfg, main_res["_layers"])
+
+    step_floor_us = max(work["step_bytes"] / HBM_PEAK_GBS / 1e3, work["step_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e6)
+    extra = dict(kernels_us={k: round(v["avg_us"], 2) for k, v in kern.items()},
+                 step_algorithmic_bytes=work["step_bytes"], step_algorithmic_flops=work["step_flops"],
+                 step_roofline_floor_us=step_floor_us,
+                 step_roofline_frac=step_floor_us / (main_res["ms_per_step"] * 1e3),
+                 pairs_per_step=main_res["P_mean"], experts_touched_per_step=main_res["D_mean"])
+    del main_res["_layers"], main_res["_bufs"]
+    torch.cuda.empty_cache()
+
+    if not args.no_extra:
+        others = {}
+        k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 2)
+        names = [n for n in ("fine60_decode_b1", "fine60_decode_b8", "fine60_decode_b32", "fine60_decode_b64",
+                             "fine64_prefill") if n != args.workload]
+        for name in names:
+            c2 = workload_config(name, args.ratio)
+            r2 = time_workload(mm, torch, c2, k2, w2)
+            wk = algorithmic_work(c2, r2["P_mean"], r2["D_mean"])
+            floor = max(wk["step_bytes"] / HBM_PEAK_GBS / 1e3, wk["step_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e6)
+            g2 = r2["kernels"]["ffn_gate_up"]["avg_us"]
+            others[name] = dict(tokens_per_s=r2["tokens_per_s"], us_per_step=r2["ms_per_step"] * 1e3,
+                                step_roofline_frac=floor / (r2["ms_per_step"] * 1e3),
+                                gate_up_us=g2, gate_up_hbm_frac=wk["gate_up_bytes"] / (g2 * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                gate_up_mfma_frac=wk["gate_up_flops"] / (g2 * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                kernels_us={k: round(v["avg_us"], 2) for k, v in r2["kernels"].items()})
+            del r2
+            torch.cuda.empty_cache()
+        # Eq. 1 of the paper from measured layer times: T (all big), T_l (all little), T_b (all big,
+        # weights resident, so T_b = T here); single-token decode
+        tl = time_workload(mm, torch, workload_config("fine60_decode_b1", 0.0), k2, w2, profile=False)
+        tb = time_workload(mm, torch, workload_config("fine60_decode_b1", 1.0), k2, w2, profile=False)
+        T_, Tl_, Tb_ = tb["ms_per_step"], tl["ms_per_step"], tb["ms_per_step"]
+        others["eq1_b1"] = dict(T_us=T_ * 1e3, T_little_us=Tl_ * 1e3, T_big_us=Tb_ * 1e3,
+                                speedup_r0_11=T_ / (Tl_ + 0.11 * Tb_), speedup_r0_21=T_ / (Tl_ + 0.21 * Tb_),
+                                note="HBM-resident layer on MI355X; the paper's 1.57-1.72x are end-to-end with "
+                                     "PCIe offloading on other hardware (context only)")
+        extra["other_workloads"] = others
+
+    line = dict(metric="MoE-layer tokens/s (decode b=1..64, prefill 2k) + % HBM/MFMA roofline",
+                value=main_res["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+                ms_per_step=main_res["ms_per_step"], higher_is_better=True, scaling="weak", vs_baseline=None,
+                dtype=cfg.dtype, data="synthetic",
+                config=dict(workload=args.workload, tokens=cfg.T, hidden=cfg.H, experts=cfg.E,
+                            intermediate=cfg.I, k_big=cfg.k_big, k_little=cfg.k_little,
+                            shared_intermediate=list(cfg.shared_I), fallback_ratio=cfg.fallback_ratio,
+                            gamma=cfg.gamma, layers_cycled=main_res["layers"]),
+                roofline=roofline, cpu_baseline=cpu, extra=extra)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -83,6 +83,15 @@ const char* moe_last_error(void);
 /* Number of compute units of the current device and the library's build tag (diagnostics). */
 int moe_device_info(int32_t* n_cu, int32_t* is_gfx950);
 
+/* Per-kernel timing for measurement runs (not thread-safe; off by default).  While enabled, every
+ * kernel launch site of the calls below is bracketed by a pair of HIP events on the call's stream.
+ * moe_profile_enable(1) also clears earlier records.  moe_profile_read waits for the events of
+ * one kind and returns how many launch sites were recorded and their summed duration.
+ * Kinds: 0 router GEMM, 1 softmax/top-k/importance, 2 dispatch, 3 FFN gate+up (SwiGLU),
+ * 4 FFN down, 5 combine, 6 token confidence. */
+int moe_profile_enable(int on);
+int moe_profile_read(int kind, int64_t* launches, double* total_ms);
+
 /* ------------------------------------------------------------------------------------------
  * Selection stage (Sec. II-A) with the big-little rule (Sec. III-A, Alg. 1).
  *

@@ -25,7 +25,7 @@ MOE_OK = 0
 ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "MOE_E_HIP",
           -5: "MOE_E_CACHE_FULL", -6: "MOE_E_WORKSPACE"}
 
-EXPORTS = ("moe_last_error", "moe_device_info", "moe_route", "moe_token_confidence",
+EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_expert_ffn_workspace_bytes",
            "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_cache_snapshot", "moe_cache_sync")
@@ -66,6 +66,9 @@ def load_library() -> ctypes.CDLL:
     lib.moe_last_error.restype = ctypes.c_char_p
     lib.moe_last_error.argtypes = []
     lib.moe_device_info.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    lib.moe_profile_enable.argtypes = [ctypes.c_int]
+    lib.moe_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
+                                     ctypes.POINTER(ctypes.c_double)]
     lib.moe_route.argtypes = [cfgp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp]
     lib.moe_token_confidence.argtypes = [vp, i32, i32, vp, vp]
     lib.moe_dispatch_workspace_bytes.argtypes = [cfgp]
@@ -86,7 +89,7 @@ def load_library() -> ctypes.CDLL:
                                        ctypes.POINTER(moe_fetch_stats), vp]
     lib.moe_cache_snapshot.argtypes = [vp, ctypes.POINTER(i32)]
     lib.moe_cache_sync.argtypes = [vp]
-    for name in ("moe_device_info", "moe_route", "moe_token_confidence", "moe_dispatch",
+    for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence", "moe_dispatch",
                  "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_cache_snapshot",
                  "moe_cache_sync"):
         getattr(lib, name).restype = ctypes.c_int
@@ -136,6 +139,21 @@ def moe_device_info():
     n_cu, is950 = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(load_library().moe_device_info(ctypes.byref(n_cu), ctypes.byref(is950)))
     return n_cu.value, bool(is950.value)
+
+
+PROFILE_KINDS = ("router_gemm", "route_topk", "dispatch", "ffn_gate_up", "ffn_down", "combine",
+                 "token_confidence")
+
+
+def moe_profile_enable(on: bool) -> None:
+    _check(load_library().moe_profile_enable(int(bool(on))))
+
+
+def moe_profile_read(kind: int):
+    """-> (launch sites recorded, summed duration in ms) of one kernel kind"""
+    n, ms = ctypes.c_int64(0), ctypes.c_double(0.0)
+    _check(load_library().moe_profile_read(kind, ctypes.byref(n), ctypes.byref(ms)))
+    return n.value, ms.value
 
 
 def moe_route(cfg: moe_config, x, Wg, gate_bias, conf, logits, logits_given, topk_idx, topk_w,

@@ -4,6 +4,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "internal.h"
 
 namespace mm {
@@ -21,6 +23,36 @@ int fail(int code, const char* fmt, ...) {
 int hip_fail(hipError_t e, const char* what) {
   if (e == hipSuccess) return MOE_OK;
   return fail(MOE_E_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+// ---- per-kernel timing ------------------------------------------------------------------------
+namespace {
+struct ProfState {
+  bool on = false;
+  std::vector<hipEvent_t> ev;      // 2 per record: begin, end
+  std::vector<int> kind;           // per record
+  size_t used = 0;                 // records in use
+  static constexpr size_t kMaxRecords = 1 << 15;
+} g_prof;
+}  // namespace
+
+void prof_mark(int kind, bool begin, hipStream_t s) {
+  if (!g_prof.on) return;
+  if (begin) {
+    if (g_prof.used >= ProfState::kMaxRecords) return;
+    if (g_prof.used * 2 >= g_prof.ev.size()) {
+      hipEvent_t a, b;
+      if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { g_prof.on = false; return; }
+      g_prof.ev.push_back(a); g_prof.ev.push_back(b);
+      g_prof.kind.push_back(kind);
+    }
+    g_prof.kind[g_prof.used] = kind;
+    (void)hipEventRecord(g_prof.ev[2 * g_prof.used], s);
+  } else {
+    if (g_prof.used >= ProfState::kMaxRecords || g_prof.used * 2 >= g_prof.ev.size()) return;
+    (void)hipEventRecord(g_prof.ev[2 * g_prof.used + 1], s);
+    g_prof.used++;
+  }
 }
 
 int device_cu_count() {
@@ -81,6 +113,27 @@ using namespace mm;
 
 extern "C" const char* moe_last_error(void) { return g_err; }
 
+extern "C" int moe_profile_enable(int on) {
+  g_prof.on = on != 0;
+  g_prof.used = 0;
+  return MOE_OK;
+}
+
+extern "C" int moe_profile_read(int kind, int64_t* launches, double* total_ms) {
+  if (kind < 0 || kind >= kProfKinds || !launches || !total_ms) return fail(MOE_E_BADARG, "moe_profile_read: kind %d", kind);
+  int64_t n = 0;
+  double ms = 0.0;
+  for (size_t i = 0; i < g_prof.used; ++i) {
+    if (g_prof.kind[i] != kind) continue;
+    MM_HIP(hipEventSynchronize(g_prof.ev[2 * i + 1]));
+    float t = 0.f;
+    MM_HIP(hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]));
+    ms += t; ++n;
+  }
+  *launches = n; *total_ms = ms;
+  return MOE_OK;
+}
+
 extern "C" int moe_device_info(int32_t* n_cu, int32_t* is_gfx950) {
   int dev = 0;
   MM_HIP(hipGetDevice(&dev));
@@ -105,15 +158,18 @@ extern "C" int moe_route(const moe_config* cfg, const void* x, const void* Wg, c
     StreamArgs a = {};
     a.T = cfg->T; a.H = cfg->H; a.E = cfg->E; a.I = cfg->I;
     a.x = x; a.Wg = Wg; a.bias = gate_bias; a.logits = logits;
+    ProfScope ps(kProfRouterGemm, s);
     rc = launch_stream(kRouter, cfg->dtype, a, s);
     if (rc) return rc;
   }
+  ProfScope ps(kProfRouteTopk, s);
   return launch_route(*cfg, conf, logits, topk_idx, topk_w, important, k_t, s);
 }
 
 extern "C" int moe_token_confidence(const float* lm_logits, int32_t T, int32_t V, float* conf, void* stream) {
   if (T < 0 || V <= 0) return fail(MOE_E_SHAPE, "moe_token_confidence: T=%d V=%d", T, V);
   if (T > 0 && (!lm_logits || !conf)) return fail(MOE_E_BADARG, "moe_token_confidence: null pointer");
+  ProfScope ps(kProfConfidence, static_cast<hipStream_t>(stream));
   return launch_confidence(lm_logits, T, V, conf, static_cast<hipStream_t>(stream));
 }
 
@@ -133,6 +189,7 @@ extern "C" int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, cons
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < moe_dispatch_workspace_bytes(cfg))
     return fail(MOE_E_WORKSPACE, "moe_dispatch: workspace %p of %zu bytes (need %zu, 256-byte aligned)", ws,
                 ws_bytes, moe_dispatch_workspace_bytes(cfg));
+  ProfScope ps(kProfDispatch, static_cast<hipStream_t>(stream));
   return launch_dispatch(*cfg, topk_idx, k_t, expert_offsets, sorted_token, sorted_rank, inv_pos,
                          static_cast<int32_t*>(ws), static_cast<hipStream_t>(stream));
 }
@@ -179,8 +236,12 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
     a.h_shared[s] = wsb + L.h_shared[s];
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = launch_stream(kGateUp, cfg->dtype, a, s);
-  if (rc) return rc;
+  {
+    ProfScope ps(kProfFfnGateUp, s);
+    rc = launch_stream(kGateUp, cfg->dtype, a, s);
+    if (rc) return rc;
+  }
+  ProfScope ps(kProfFfnDown, s);
   return launch_stream(kDown, cfg->dtype, a, s);
 }
 
@@ -192,5 +253,6 @@ extern "C" int moe_combine(const moe_config* cfg, const float* y, const float* t
   if (cfg->T == 0) return MOE_OK;
   if (!y || !topk_w || !inv_pos || !k_t || !out) return fail(MOE_E_BADARG, "moe_combine: null tensor");
   if (cfg->n_shared > 0 && !shared_out) return fail(MOE_E_BADARG, "moe_combine: shared_out is NULL but n_shared=%d", cfg->n_shared);
+  ProfScope ps(kProfCombine, static_cast<hipStream_t>(stream));
   return launch_combine(*cfg, y, topk_w, inv_pos, k_t, shared_out, out, static_cast<hipStream_t>(stream));
 }

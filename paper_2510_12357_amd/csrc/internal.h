@@ -18,6 +18,16 @@ int hip_fail(hipError_t e, const char* what);
   } while (0)
 
 int validate_config(const moe_config* cfg);
+
+// ---- optional per-kernel timing (moe_profile_*): an event pair around each launch site -------
+enum ProfKind { kProfRouterGemm = 0, kProfRouteTopk, kProfDispatch, kProfFfnGateUp, kProfFfnDown,
+                kProfCombine, kProfConfidence, kProfKinds };
+void prof_mark(int kind, bool begin, hipStream_t s);
+struct ProfScope {
+  int kind; hipStream_t s;
+  ProfScope(int k, hipStream_t st) : kind(k), s(st) { prof_mark(kind, true, s); }
+  ~ProfScope() { prof_mark(kind, false, s); }
+};
 int device_cu_count();
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -61,7 +71,5 @@ int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t,
                     hipStream_t s);
 int launch_combine(const moe_config& c, const float* y, const float* w, const int32_t* inv_pos,
                    const int32_t* k_t, const float* shared_out, void* out, hipStream_t s);
-int launch_table_update(const void** table, int E, const int32_t* ids, const int32_t* slots, int n,
-                        char* slot_base, size_t blob_bytes, hipStream_t s);
 
 }  // namespace mm
