@@ -143,19 +143,23 @@ int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* 
  *
  *   for every routed expert e with expert_w[e] != NULL and position p in
  *   [expert_offsets[e], expert_offsets[e+1]):     y[p][:] = FFN_e( x[sorted_token[p]][:] )
- *   for every shared expert s and token t:        shared_out[s][t][:] = FFN_s( x[t][:] )
+ *   for every shared expert s and token t:        FFN_s( x[t][:] ) is written as one or more partial
+ *            sums over slices of the intermediate dimension, one [T,H] slab of shared_out each;
+ *            the sum of all S = moe_shared_out_slabs(cfg) slabs is sum_s FFN_s(x[t]).
  *
  * expert_w   DEVICE array of E device pointers to expert blobs.  A NULL entry skips that
  *            expert (its rows of y are left untouched): this is how a step is run in several
  *            waves when the HBM cache holds fewer experts than the step needs.
  * shared_w   HOST array of n_shared device pointers (ignored when run_shared == 0)
  * y          device [T*k_big, H] fp32 (rows >= P untouched)
- * shared_out device [n_shared, T, H] fp32 (NULL allowed when nothing shared is run)
+ * shared_out device [S, T, H] fp32, S = moe_shared_out_slabs(cfg) >= n_shared (NULL allowed when
+ *            nothing shared is run)
  * run_routed / run_shared  select which of the two parts this call computes
  * ws         device scratch holding the SwiGLU activations
  * The number of pairs per expert is read on the device; the host never waits for it.
  */
 size_t moe_expert_ffn_workspace_bytes(const moe_config* cfg);
+int32_t moe_shared_out_slabs(const moe_config* cfg); /* 0 without shared experts; -1 on a bad config */
 int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_t* expert_offsets,
                    const int32_t* sorted_token, const void* const* expert_w,
                    const void* const* shared_w, int run_routed, int run_shared, float* y,
@@ -164,7 +168,8 @@ int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_t* expert_o
 /* ------------------------------------------------------------------------------------------
  * "... and finally summed" (Sec. II-A):
  *   out[t][:] = sum_{j < k_t[t]} topk_w[t][j] * y[inv_pos[t][j]][:]  +  sum_s shared_out[s][t][:]
- * summed in fp32 in ascending j, then s.   out device [T,H] dtype.
+ * with s over the S slabs that moe_expert_ffn wrote; summed in fp32 in ascending j, then ascending
+ * s, rounded once.   out device [T,H] dtype.
  */
 int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,
                 const int32_t* inv_pos, const int32_t* k_t, const float* shared_out, void* out,

@@ -27,7 +27,7 @@ ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "M
 
 EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_expert_ffn_workspace_bytes",
-           "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
+           "moe_shared_out_slabs", "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_cache_snapshot", "moe_cache_sync")
 
 
@@ -76,6 +76,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_dispatch.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.moe_expert_ffn_workspace_bytes.argtypes = [cfgp]
     lib.moe_expert_ffn_workspace_bytes.restype = sz
+    lib.moe_shared_out_slabs.argtypes = [cfgp]
+    lib.moe_shared_out_slabs.restype = i32
     lib.moe_expert_ffn.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
                                    ctypes.c_int, vp, vp, vp, sz, vp]
     lib.moe_combine.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
@@ -182,6 +184,10 @@ def moe_expert_ffn_workspace_bytes(cfg: moe_config) -> int:
     return int(load_library().moe_expert_ffn_workspace_bytes(ctypes.byref(cfg)))
 
 
+def moe_shared_out_slabs(cfg: moe_config) -> int:
+    return int(load_library().moe_shared_out_slabs(ctypes.byref(cfg)))
+
+
 def moe_expert_ffn(cfg: moe_config, x, expert_offsets, sorted_token, expert_w, shared_w: Sequence,
                    run_routed, run_shared, y, shared_out, ws, ws_bytes: int, stream=None) -> None:
     """expert_w: device int64 tensor [E] of blob addresses, or a raw device address (int);
@@ -272,8 +278,8 @@ class StepBuffers:
         self.sorted_rank = torch.empty((T * K,), **i32)
         self.inv_pos = torch.empty((T, K), **i32)
         self.y = torch.zeros((T * K, H), **f32)
-        ns = len(cfg.shared_I)
-        self.shared_out = torch.zeros((ns, T, H), **f32) if ns else None
+        ns = moe_shared_out_slabs(self.c)
+        self.shared_out = torch.zeros((ns, T, H), **f32) if ns > 0 else None
         self.out = torch.empty((T, H), dtype=torch_dtype(cfg), device=device)
         self.dws_bytes = moe_dispatch_workspace_bytes(self.c)
         self.dws = torch.empty((self.dws_bytes,), dtype=torch.uint8, device=device)

@@ -84,8 +84,34 @@ int validate_config(const moe_config* c) {
   }
   if ((long long)c->T * c->k_big * (long long)maxdim >= (1ll << 31))
     return fail(MOE_E_UNSUPPORTED, "T*k_big*max(H,I) = %lld does not fit 31 bits", (long long)c->T * c->k_big * maxdim);
+  // every tensor the kernels address through a 32-bit buffer offset must stay below 2 GiB
+  const long long eb = (long long)elem_bytes(c->dtype);
+  const long long biggest = eb * maxdim * (long long)(3 * c->H > c->T * c->k_big ? 3 * c->H : c->T * c->k_big);
+  const long long act = eb * (long long)c->T * (c->H > maxdim ? c->H : maxdim);
+  const long long gate = eb * (long long)c->E * c->H;
+  if (biggest >= (1ll << 31) || act >= (1ll << 31) || gate >= (1ll << 31))
+    return fail(MOE_E_UNSUPPORTED, "a tensor of this layer reaches 2 GiB (expert blob, activations or gate matrix)");
   if (!(c->gamma == c->gamma)) return fail(MOE_E_BADARG, "gamma is NaN");
   return MOE_OK;
+}
+
+SlabPlan slab_plan(const moe_config& c) {
+  SlabPlan P = {};
+  const int target = c.I > 1024 ? c.I : 1024;          // chunk about as long as a routed expert's I
+  for (int s = 0; s < c.n_shared; ++s) {
+    const int Is = c.shared_I[s];
+    int n = (Is + target - 1) / target;
+    if (n > kMaxKSplit) n = kMaxKSplit;
+    int chunk = ((Is + n - 1) / n + 31) / 32 * 32;
+    n = (Is + chunk - 1) / chunk;
+    P.kchunk[s] = chunk;
+    for (int k = 0; k < n; ++k) {
+      P.slab_shared[P.n_slabs] = s;
+      P.slab_chunk[P.n_slabs] = k;
+      P.n_slabs++;
+    }
+  }
+  return P;
 }
 
 namespace {
@@ -154,12 +180,18 @@ extern "C" int moe_route(const moe_config* cfg, const void* x, const void* Wg, c
     return fail(MOE_E_BADARG, "moe_route: logits/topk_idx/topk_w/important/k_t must not be NULL");
   if (!logits_given && (!x || !Wg)) return fail(MOE_E_BADARG, "moe_route: x and Wg are needed unless logits_given");
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // decode sizes: plain-FMA GEMV spread over many waves; larger T: MFMA router GEMM
+  constexpr int kGemvMaxT = 256;
   if (!logits_given) {
-    StreamArgs a = {};
-    a.T = cfg->T; a.H = cfg->H; a.E = cfg->E; a.I = cfg->I;
-    a.x = x; a.Wg = Wg; a.bias = gate_bias; a.logits = logits;
     ProfScope ps(kProfRouterGemm, s);
-    rc = launch_stream(kRouter, cfg->dtype, a, s);
+    if (cfg->T <= kGemvMaxT) {
+      rc = launch_gate_gemv(*cfg, x, Wg, gate_bias, logits, s);
+    } else {
+      StreamArgs a = {};
+      a.T = cfg->T; a.H = cfg->H; a.E = cfg->E; a.I = cfg->I;
+      a.x = x; a.Wg = Wg; a.bias = gate_bias; a.logits = logits;
+      rc = launch_stream(kRouter, cfg->dtype, a, s);
+    }
     if (rc) return rc;
   }
   ProfScope ps(kProfRouteTopk, s);
@@ -192,6 +224,11 @@ extern "C" int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, cons
   ProfScope ps(kProfDispatch, static_cast<hipStream_t>(stream));
   return launch_dispatch(*cfg, topk_idx, k_t, expert_offsets, sorted_token, sorted_rank, inv_pos,
                          static_cast<int32_t*>(ws), static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t moe_shared_out_slabs(const moe_config* cfg) {
+  if (validate_config(cfg)) return -1;
+  return slab_plan(*cfg).n_slabs;
 }
 
 extern "C" size_t moe_expert_ffn_workspace_bytes(const moe_config* cfg) {
@@ -230,11 +267,15 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
   a.x = x; a.y = y; a.shared_out = shared_out;
   char* wsb = static_cast<char*>(ws);
   a.h_routed = wsb + L.h_routed;
+  const SlabPlan plan = slab_plan(*cfg);
   for (int s = 0; s < a.n_shared; ++s) {
     a.shared_I[s] = cfg->shared_I[s];
+    a.shared_kchunk[s] = plan.kchunk[s];
     a.shared_w[s] = shared_w[s];
     a.h_shared[s] = wsb + L.h_shared[s];
   }
+  a.n_slabs = shared ? plan.n_slabs : 0;
+  for (int i = 0; i < a.n_slabs; ++i) { a.slab_shared[i] = plan.slab_shared[i]; a.slab_chunk[i] = plan.slab_chunk[i]; }
   hipStream_t s = static_cast<hipStream_t>(stream);
   {
     ProfScope ps(kProfFfnGateUp, s);

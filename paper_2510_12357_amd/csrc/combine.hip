@@ -1,6 +1,7 @@
 // Weighted sum that closes the execution stage (Sec. II-A: the outputs of the selected experts
 // are "finally summed"):
 //   out[t][:] = sum_{j < k_t[t]} topk_w[t][j] * y[inv_pos[t][j]][:] + sum_s shared_out[s][t][:]
+// where s runs over the slabs of shared_out (partial sums of the shared experts' outputs),
 // accumulated in fp32 in ascending j, then ascending s, and rounded once to the storage dtype.
 // Pure streaming: each thread owns four consecutive columns (16-byte loads, 8/16-byte stores).
 #include "internal.h"
@@ -46,7 +47,7 @@ int launch_combine(const moe_config& c, const float* y, const float* w, const in
                    const int32_t* k_t, const float* shared_out, void* out, hipStream_t s) {
   if (c.T == 0) return MOE_OK;
   const dim3 grid((unsigned)c.T, (unsigned)((c.H / 4 + kThreads - 1) / kThreads));
-  const int ns = shared_out ? c.n_shared : 0;
+  const int ns = shared_out ? slab_plan(c).n_slabs : 0;
   if (c.dtype == MOE_BF16)
     hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(kThreads), 0, s, y, w, inv_pos, k_t, shared_out,
                        ns, c.T, c.H, c.k_big, c.T * c.k_big, out);

@@ -50,21 +50,41 @@ __device__ __forceinline__ void fill_pads(int first, int stride, int P, int T, i
   }
 }
 
+// rank at which token t names expert e in the LDS copy of the selection (-1 = not named);
+// entries beyond k_t were stored as -1, so no k_t lookup is needed here
+__device__ __forceinline__ int match_rank_lds(const int* s_idx, int t, int T, int K, int e) {
+  if (t >= T) return -1;
+  int found = -1;
+  for (int j = K - 1; j >= 0; --j)
+    if (s_idx[t * K + j] == e) found = j;
+  return found;
+}
+
 __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int E, int K,
     int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_token,
     int32_t* __restrict__ sorted_rank, int32_t* __restrict__ inv_pos) {
+  __shared__ int s_idx[kSmallT * MOE_MAX_TOPK];
   __shared__ int s_count[MOE_MAX_EXPERTS];
   __shared__ int s_off[MOE_MAX_EXPERTS + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   constexpr int kWaves = kSmallThreads / 64;
 
+  // stage the selection once: every later pass reads LDS only
+  for (int i = tid; i < T * K; i += kSmallThreads) {
+    const int t = i / K, j = i - t * K;
+    int kt = k_t[t];
+    kt = kt < 0 ? 0 : (kt > K ? K : kt);
+    const int e = idx[i];
+    const bool pair = j < kt && (unsigned)e < (unsigned)E;
+    s_idx[i] = pair ? e : -1;
+    if (!pair) inv_pos[i] = -1;
+  }
+  __syncthreads();
   for (int e = wave; e < E; e += kWaves) {
     int cnt = 0;
-    for (int t0 = 0; t0 < T; t0 += 64) {
-      const bool hit = match_rank(idx, k_t, t0 + lane, T, K, e) >= 0;
-      cnt += __popcll(__ballot(hit));
-    }
+    for (int t0 = 0; t0 < T; t0 += 64)
+      cnt += __popcll(__ballot(match_rank_lds(s_idx, t0 + lane, T, K, e) >= 0));
     if (lane == 0) s_count[e] = cnt;
   }
   __syncthreads();
@@ -86,7 +106,7 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
     int pos = s_off[e];
     for (int t0 = 0; t0 < T; t0 += 64) {
       const int t = t0 + lane;
-      const int j = match_rank(idx, k_t, t, T, K, e);
+      const int j = match_rank_lds(s_idx, t, T, K, e);
       const unsigned long long b = __ballot(j >= 0);
       if (j >= 0) {
         const int p = pos + __popcll(b & lanemask_lt(lane));
@@ -98,7 +118,8 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
     }
   }
   for (int e = tid; e <= E; e += kSmallThreads) offsets[e] = s_off[e];
-  fill_pads(tid, kSmallThreads, s_off[E], T, E, K, idx, k_t, sorted_token, sorted_rank, inv_pos);
+  const int P = s_off[E];
+  for (int i = P + tid; i < T * K; i += kSmallThreads) { sorted_token[i] = -1; sorted_rank[i] = -1; }
 }
 
 // ---- large T: one workgroup per expert -----------------------------------------------------

@@ -37,11 +37,27 @@ inline size_t elem_bytes(int dtype) { return dtype == MOE_FP32 ? 4 : 2; }
 // Three uses: router logits, gate/up projection with fused SwiGLU, down projection.
 enum StreamMode { kRouter = 0, kGateUp = 1, kDown = 2 };
 
+// The down projection of a wide shared expert is cut along its contraction into chunks that
+// are computed as independent groups and written to separate [T,H] slabs of shared_out.
+constexpr int kMaxKSplit = 4;
+constexpr int kMaxSlabs = MOE_MAX_SHARED * kMaxKSplit;
+struct SlabPlan {
+  int n_slabs;
+  int kchunk[MOE_MAX_SHARED];          // chunk length per shared expert (multiple of 32)
+  int slab_shared[kMaxSlabs];          // slab -> shared expert
+  int slab_chunk[kMaxSlabs];           // slab -> chunk index within that expert
+};
+SlabPlan slab_plan(const moe_config& c);
+
 struct StreamArgs {
   int T, H, E, I;
   int n_routed;                       // E when the routed experts are run, else 0
   int n_shared;                       // shared experts run by this launch
   int shared_I[MOE_MAX_SHARED];
+  int shared_kchunk[MOE_MAX_SHARED];
+  int n_slabs;                        // groups of the shared down projection
+  int slab_shared[kMaxSlabs];
+  int slab_chunk[kMaxSlabs];
   const void* shared_w[MOE_MAX_SHARED];
   const void* const* expert_w;        // device table [E]
   const int32_t* offsets;             // device [E+1]
@@ -51,7 +67,7 @@ struct StreamArgs {
   void* h_routed;                     // [T*k_big, I]   SwiGLU activations (storage dtype)
   void* h_shared[MOE_MAX_SHARED];     // [T, I_s]
   float* y;                           // [T*k_big, H]
-  float* shared_out;                  // [n_shared, T, H]
+  float* shared_out;                  // [n_slabs, T, H]
   const void* Wg;                     // router: [E,H]
   const float* bias;                  // router: [E] or null
   float* logits;                      // router: [T,E]
@@ -65,6 +81,8 @@ int launch_tiled_ffn(const StreamArgs& a, hipStream_t s);
 // ---- selection, dispatch, combine -----------------------------------------------------------
 int launch_route(const moe_config& c, const float* conf, const float* logits, int32_t* idx,
                  float* w, uint8_t* important, int32_t* k_t, hipStream_t s);
+int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,
+                     hipStream_t s);
 int launch_confidence(const float* z, int T, int V, float* conf, hipStream_t s);
 int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int32_t* offsets,
                     int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos, int32_t* counts,

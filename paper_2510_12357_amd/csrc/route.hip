@@ -1,10 +1,15 @@
-// Selection stage after the router GEMM (Sec. II-A) with the big-little rule (Sec. III-A,
-// Alg. 1): softmax over all experts, importance flag from the token's confidence, and the
-// k_t best experts in the order (logit descending, expert id ascending).
+// Selection stage (Sec. II-A) with the big-little rule (Sec. III-A, Alg. 1): softmax over all
+// experts, importance flag from the token's confidence, and the k_t best experts in the order
+// (logit descending, expert id ascending).
 //
-// One wavefront per token; an expert row of up to 256 logits lives in registers (4 per lane)
-// and every reduction is a butterfly of cross-lane shuffles.  All selection decisions are
-// comparisons on the fp32 logits, so they are exact and reproducible bit for bit.
+// Selection runs in one wavefront per token; an expert row of up to 256 logits lives in
+// registers (4 per lane) and every reduction is a butterfly of cross-lane shuffles.  All
+// selection decisions are comparisons on the fp32 logits, so they are exact and reproducible.
+//
+// Kernels:
+//   gate_gemv_kernel  router logits at decode sizes (few tokens): plain fp32 FMAs, one wave per
+//                     small block of logits, so that even one token spreads over E waves
+//   route_kernel      softmax / importance / top-k on given logits
 #include <math.h>
 
 #include "internal.h"
@@ -31,20 +36,24 @@ __device__ __forceinline__ int wave_min_int(int v) {
   return v;
 }
 
-__global__ __launch_bounds__(kWavesPerBlock * 64) void route_kernel(
-    const float* __restrict__ logits, const float* __restrict__ conf, float gamma, int T, int E,
-    int k_big, int k_little, int renorm, int32_t* __restrict__ idx, float* __restrict__ w,
-    uint8_t* __restrict__ important, int32_t* __restrict__ k_t) {
-  const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
-  if (t >= T) return;                                  // whole wave leaves together
+struct RouteParams {
+  const float* conf;
+  float gamma;
+  int T, E, k_big, k_little, renorm;
+  int32_t* idx;
+  float* w;
+  uint8_t* important;
+  int32_t* k_t;
+};
 
+// One wave selects for token t.  raw[c] = logit of expert lane + 64*c (anything for e >= E).
+__device__ __forceinline__ void select_token(const RouteParams& P, int t, int lane, const float (&raw)[kPerLane]) {
   const float NINF = -INFINITY;
+  const int E = P.E;
   float v[kPerLane];
 #pragma unroll
   for (int c = 0; c < kPerLane; ++c) {
-    const int e = lane + 64 * c;
-    float x = (e < E) ? logits[(size_t)t * E + e] : NINF;
+    const float x = (lane + 64 * c < E) ? raw[c] : NINF;
     v[c] = (x != x) ? NINF : x;                        // NaN counts as -inf
   }
   // softmax statistics over all E
@@ -56,16 +65,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void route_kernel(
   float s = 0.f;
 #pragma unroll
   for (int c = 0; c < kPerLane; ++c) {
-    const int e = lane + 64 * c;
-    p[c] = (e < E && m != NINF) ? expf(v[c] - m) : 0.f;
+    p[c] = (lane + 64 * c < E && m != NINF) ? expf(v[c] - m) : 0.f;
     s += p[c];
   }
   s = wave_sum(s);
   const float inv_s = s > 0.f ? 1.f / s : 0.f;
 
   // Alg. 1: the little result is kept only if the confidence is strictly above gamma
-  const bool imp = conf ? !(conf[t] > gamma) : true;
-  const int k = imp ? k_big : k_little;
+  const bool imp = P.conf ? !(P.conf[t] > P.gamma) : true;
+  const int k = imp ? P.k_big : P.k_little;
 
   // k rounds of "best expert not taken yet"
   unsigned taken = 0;                                  // bit c: this lane's c-th expert is taken
@@ -76,17 +84,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void route_kernel(
     float best = NINF;
     bool any = false;
 #pragma unroll
-    for (int c = 0; c < kPerLane; ++c) {
-      const int e = lane + 64 * c;
-      if (e < E && !((taken >> c) & 1u)) { best = any ? fmaxf(best, v[c]) : v[c]; any = true; }
-    }
+    for (int c = 0; c < kPerLane; ++c)
+      if (lane + 64 * c < E && !((taken >> c) & 1u)) { best = any ? fmaxf(best, v[c]) : v[c]; any = true; }
     const float gbest = wave_max(any ? best : NINF);
     int cand = 0x7fffffff;                             // lowest expert id holding the best value
 #pragma unroll
-    for (int c = kPerLane - 1; c >= 0; --c) {
-      const int e = lane + 64 * c;
-      if (e < E && !((taken >> c) & 1u) && v[c] == gbest) cand = e;
-    }
+    for (int c = kPerLane - 1; c >= 0; --c)
+      if (lane + 64 * c < E && !((taken >> c) & 1u) && v[c] == gbest) cand = lane + 64 * c;
     const int sel = wave_min_int(cand);
     float psel = 0.f;
 #pragma unroll
@@ -96,15 +100,99 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void route_kernel(
     wsum += psel;
     if (lane == j) { my_w = psel; my_e = sel; }
   }
-  if (renorm) my_w = wsum > 0.f ? my_w / wsum : 0.f;
-  if (lane < k_big) {
-    idx[(size_t)t * k_big + lane] = lane < k ? my_e : -1;
-    w[(size_t)t * k_big + lane] = lane < k ? my_w : 0.f;
+  if (P.renorm) my_w = wsum > 0.f ? my_w / wsum : 0.f;
+  if (lane < P.k_big) {
+    P.idx[(size_t)t * P.k_big + lane] = lane < k ? my_e : -1;
+    P.w[(size_t)t * P.k_big + lane] = lane < k ? my_w : 0.f;
   }
   if (lane == 0) {
-    important[t] = imp ? 1 : 0;
-    k_t[t] = k;
+    P.important[t] = imp ? 1 : 0;
+    P.k_t[t] = k;
   }
+}
+
+__global__ __launch_bounds__(kWavesPerBlock * 64) void route_kernel(const float* __restrict__ logits,
+                                                                     const RouteParams P) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (t >= P.T) return;                                // whole wave leaves together
+  float raw[kPerLane];
+#pragma unroll
+  for (int c = 0; c < kPerLane; ++c) {
+    const int e = lane + 64 * c;
+    raw[c] = (e < P.E) ? logits[(size_t)t * P.E + e] : 0.f;
+  }
+  select_token(P, t, lane, raw);
+}
+
+// ---- fused router for decode sizes ----------------------------------------------------------
+__device__ __forceinline__ void load8(const uint16_t* p, float (&f)[8]) {
+  const uint4 u = *reinterpret_cast<const uint4*>(p);
+  const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = __uint_as_float(w[i] << 16);            // bf16 -> fp32 is a 16-bit shift
+    f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void load8(const float* p, float (&f)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+}
+
+// One wave per block of TE experts x TT tokens: the lanes split the hidden dimension, every
+// operand chunk is a 16/32-byte load, and the block's sums are reduced with shuffles.  Decode
+// batches give E*T/(TE*TT) waves, enough to pull the gate matrix at full speed.
+constexpr int kGemvWaves = 4;
+
+template <typename S, int TE, int TT>
+__global__ __launch_bounds__(kGemvWaves * 64) void gate_gemv_kernel(const S* __restrict__ x,
+                                                                     const S* __restrict__ Wg,
+                                                                     const float* __restrict__ bias, int T,
+                                                                     int H, int E,
+                                                                     float* __restrict__ logits) {
+  const int lane = threadIdx.x & 63;
+  const int wid = blockIdx.x * kGemvWaves + (threadIdx.x >> 6);
+  const int n_eb = (E + TE - 1) / TE, n_tb = (T + TT - 1) / TT;
+  if (wid >= n_eb * n_tb) return;                      // whole wave leaves together
+  const int e0 = (wid % n_eb) * TE, t0 = (wid / n_eb) * TT;
+  float acc[TE][TT];
+#pragma unroll
+  for (int a = 0; a < TE; ++a)
+#pragma unroll
+    for (int b = 0; b < TT; ++b) acc[a][b] = 0.f;
+  const int nchunk = H >> 3;                           // 8 elements per chunk
+  for (int c = lane; c < nchunk; c += 64) {
+    float xv[TT][8];
+#pragma unroll
+    for (int b = 0; b < TT; ++b) load8(x + (size_t)min(t0 + b, T - 1) * H + c * 8, xv[b]);
+#pragma unroll
+    for (int a = 0; a < TE; ++a) {
+      float wv[8];
+      load8(Wg + (size_t)min(e0 + a, E - 1) * H + c * 8, wv);   // clamped rows are discarded below
+#pragma unroll
+      for (int b = 0; b < TT; ++b)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[a][b] = fmaf(xv[b][i], wv[i], acc[a][b]);
+    }
+  }
+#pragma unroll
+  for (int a = 0; a < TE; ++a)
+#pragma unroll
+    for (int b = 0; b < TT; ++b) {
+      const float sum = wave_sum(acc[a][b]);
+      const int e = e0 + a, t = t0 + b;
+      if (lane == 0 && e < E && t < T) logits[(size_t)t * E + e] = sum + (bias ? bias[e] : 0.f);
+    }
+}
+
+template <typename S, int TE, int TT>
+void launch_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,
+                 hipStream_t s) {
+  const int waves = ((c.E + TE - 1) / TE) * ((c.T + TT - 1) / TT);
+  hipLaunchKernelGGL((gate_gemv_kernel<S, TE, TT>), dim3((unsigned)((waves + kGemvWaves - 1) / kGemvWaves)),
+                     dim3(kGemvWaves * 64), 0, s, static_cast<const S*>(x), static_cast<const S*>(Wg), bias,
+                     c.T, c.H, c.E, logits);
 }
 
 // conf[t] = 1 / sum_v exp(z_tv - max_v z_tv): one workgroup per token, two sweeps over the row.
@@ -136,15 +224,37 @@ __global__ __launch_bounds__(kConfThreads) void confidence_kernel(const float* _
   }
 }
 
+RouteParams make_params(const moe_config& c, const float* conf, int32_t* idx, float* w, uint8_t* important,
+                        int32_t* k_t) {
+  RouteParams P;
+  P.conf = conf; P.gamma = c.gamma; P.T = c.T; P.E = c.E; P.k_big = c.k_big; P.k_little = c.k_little;
+  P.renorm = c.renorm; P.idx = idx; P.w = w; P.important = important; P.k_t = k_t;
+  return P;
+}
+
 }  // namespace
 
 int launch_route(const moe_config& c, const float* conf, const float* logits, int32_t* idx, float* w,
                  uint8_t* important, int32_t* k_t, hipStream_t s) {
   if (c.T == 0) return MOE_OK;
   const unsigned grid = (unsigned)((c.T + kWavesPerBlock - 1) / kWavesPerBlock);
-  hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(kWavesPerBlock * 64), 0, s, logits, conf, c.gamma,
-                     c.T, c.E, c.k_big, c.k_little, c.renorm, idx, w, important, k_t);
+  hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(kWavesPerBlock * 64), 0, s, logits,
+                     make_params(c, conf, idx, w, important, k_t));
   return hip_fail(hipGetLastError(), "route_kernel launch");
+}
+
+int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,
+                     hipStream_t s) {
+  if (c.T == 0) return MOE_OK;
+  const bool bf = c.dtype == MOE_BF16;
+  if (c.T <= 4) {
+    if (bf) launch_gemv<uint16_t, 1, 1>(c, x, Wg, bias, logits, s); else launch_gemv<float, 1, 1>(c, x, Wg, bias, logits, s);
+  } else if (c.T <= 32) {
+    if (bf) launch_gemv<uint16_t, 1, 4>(c, x, Wg, bias, logits, s); else launch_gemv<float, 1, 4>(c, x, Wg, bias, logits, s);
+  } else {
+    if (bf) launch_gemv<uint16_t, 2, 4>(c, x, Wg, bias, logits, s); else launch_gemv<float, 2, 4>(c, x, Wg, bias, logits, s);
+  }
+  return hip_fail(hipGetLastError(), "gate_gemv_kernel launch");
 }
 
 int launch_confidence(const float* z, int T, int V, float* conf, hipStream_t s) {

@@ -12,13 +12,24 @@
 //     16 rows x 64 bytes per load instruction, and the waves of a workgroup interleave over
 //     the K dimension so that a workgroup touches 16 rows x (NW*64) contiguous bytes at a time.
 //     No weight element is needed by more than one wave, so LDS staging would only add traffic.
-//   * Tokens are the "B" operand (up to 4 tiles of 16 tokens per work item); rows beyond the
-//     group's token count are predicated off, so activation traffic follows the real m.
+//   * All operand loads are raw buffer loads: a lane whose row, token or k chunk does not exist
+//     gets an offset beyond the buffer's size, for which the hardware returns zeros without a
+//     memory access.  The K loop is therefore straight-line code (no branches, no selects), and
+//     activation traffic follows the real number of tokens.
+//   * Loads run ahead of the MFMAs in a ring of registers (kDepth k-steps deep): every k-step
+//     consumes the oldest ring entry and refills it with the load of the k-step kDepth ahead, so
+//     a wave keeps a fixed number of bytes in flight.
 //   * The K split across waves is reduced through LDS, then the epilogue (SwiGLU / bias) runs
 //     on the reduced tile.  Summation order is fixed => results are deterministic.
 //   * Work items (group, row tile, token block) are enumerated on the device from
 //     expert_offsets, so the host never learns the per-expert token counts; workgroups are
-//     persistent and stride over the item list, which terminates after a bounded count.
+//     persistent and stride over the item list, which terminates after a bounded count.  The
+//     groups with many tokens (shared experts) come first in the list.
+//   * A long contraction (down projection of a wide shared expert) is cut into K chunks that
+//     become separate groups writing separate output slabs; the combine kernel adds the slabs
+//     in a fixed order.
+#include <stdlib.h>
+
 #include "internal.h"
 
 namespace mm {
@@ -26,21 +37,41 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
 
-constexpr int kNW = 4;             // waves per workgroup (K interleave factor)
-constexpr int kThreads = kNW * 64;
 constexpr int kRT = 2;             // row tiles (16 rows each) per work item
-constexpr int kNT = 4;             // token tiles (16 tokens each) per work item
-constexpr int kMaxGroups = MOE_MAX_EXPERTS + MOE_MAX_SHARED;
+#ifndef MOE_STREAM_NT
+#define MOE_STREAM_NT 4
+#endif
+constexpr int kNT = MOE_STREAM_NT; // token tiles (16 tokens each) per work item, at most
+constexpr int kMaxGroups = MOE_MAX_EXPERTS + kMaxSlabs;
+constexpr unsigned kOob = 0x80000000u;   // offset no buffer reaches (every buffer is < 2 GiB)
+
+#ifndef MOE_STREAM_D1
+#define MOE_STREAM_D1 4
+#endif
+#ifndef MOE_STREAM_D4
+#define MOE_STREAM_D4 2
+#endif
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  // wave-uniform by construction; readfirstlane tells the compiler so
+  const uint64_t a = (uint64_t)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)a);
+  const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32));
+  const unsigned n = __builtin_amdgcn_readfirstlane(bytes);
+  return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)n, 0x00020000);
+}
 
 // ---- element-type specifics -----------------------------------------------------------------
 struct BF16 {
   typedef uint16_t storage;
   typedef bf16x8 frag;                       // 8 consecutive k
-  static constexpr int kUnroll = 4;
-  static __device__ __forceinline__ frag zero() { return frag{0, 0, 0, 0, 0, 0, 0, 0}; }
-  static __device__ __forceinline__ frag load(const storage* p) {
-    return *reinterpret_cast<const frag*>(p);
+  static constexpr int kDepth1 = MOE_STREAM_D1;  // k-steps in flight with 1 token tile
+  static constexpr int kDepth4 = MOE_STREAM_D4;  // ... with up to 4 token tiles
+  static __device__ __forceinline__ frag load(__amdgpu_buffer_rsrc_t r, unsigned off) {
+    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return __builtin_bit_cast(frag, v);
   }
   static __device__ __forceinline__ f32x4 mma(const frag& a, const frag& b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -55,12 +86,12 @@ struct BF16 {
 struct FP32 {
   typedef float storage;
   struct frag { f32x4 lo, hi; };             // 8 consecutive k
-  static constexpr int kUnroll = 2;
-  static __device__ __forceinline__ frag zero() { return frag{{0, 0, 0, 0}, {0, 0, 0, 0}}; }
-  static __device__ __forceinline__ frag load(const storage* p) {
+  static constexpr int kDepth1 = 4;
+  static constexpr int kDepth4 = 2;
+  static __device__ __forceinline__ frag load(__amdgpu_buffer_rsrc_t r, unsigned off) {
     frag f;
-    f.lo = *reinterpret_cast<const f32x4*>(p);
-    f.hi = *reinterpret_cast<const f32x4*>(p + 4);
+    f.lo = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+    f.hi = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)(off + 16u), 0, 0));
     return f;
   }
   // eight 16x16x4 fp32 MFMAs: instruction i contracts the i-th element of every lane's chunk,
@@ -79,50 +110,72 @@ struct FP32 {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// Description of one group of the grouped GEMM, resolved on the device.
-template <typename ET>
+// One group of the grouped GEMM, fully resolved on the device (kept in LDS).
 struct Group {
-  int m;                                 // token rows
-  int N;                                 // weight rows
-  int K;                                 // contraction length
-  int row0;                              // first dispatch position (routed) or 0 (shared/router)
-  const typename ET::storage* w0;        // first weight matrix  (gate / down / Wg)
-  const typename ET::storage* w1;        // second weight matrix (up) for kGateUp
-  int shared_idx;                        // -1 routed/router
+  int m;            // token rows
+  int N;            // weight rows
+  int K;            // contraction length of this group (a K chunk for split groups)
+  int ldw;          // elements between weight rows = elements between B rows
+  int row0;         // first dispatch position (routed), 0 otherwise
+  int gather;       // 1: B row r is x[sorted_token[row0 + r]] (routed gate/up)
+  unsigned wbytes;  // bytes readable from w0 (both matrices for gate/up)
+  unsigned bbytes;  // bytes readable from b
+  const void* w0;   // first weight matrix, already advanced to the K chunk
+  const void* b;    // B rows, already advanced to the K chunk (and to row0 for routed kDown)
+  void* out;        // h rows / y rows / slab base, already advanced to row0 where it applies
 };
 
+// Group order: shared experts (many tokens => heaviest items) first, then the routed experts.
 template <typename ET, int MODE>
-__device__ __forceinline__ Group<ET> resolve_group(const StreamArgs& a, int g) {
+__device__ __forceinline__ Group resolve_group(const StreamArgs& a, int g) {
   typedef typename ET::storage S;
-  Group<ET> G;
-  G.shared_idx = -1;
+  constexpr unsigned esz = sizeof(S);
+  Group G;
+  G.gather = 0; G.row0 = 0;
   if (MODE == kRouter) {
-    G.m = a.T; G.N = a.E; G.K = a.H; G.row0 = 0;
-    G.w0 = static_cast<const S*>(a.Wg); G.w1 = nullptr;
+    G.m = a.T; G.N = a.E; G.K = a.H; G.ldw = a.H;
+    G.w0 = a.Wg; G.b = a.x; G.out = a.logits;
+    G.wbytes = (unsigned)a.E * a.H * esz; G.bbytes = (unsigned)a.T * a.H * esz;
     return G;
   }
-  int Ig;
-  const S* blob;
-  if (g < a.n_routed) {
-    const int b = clampi(a.offsets[g], 0, a.max_pairs);
-    const int e = clampi(a.offsets[g + 1], b, a.max_pairs);
-    blob = static_cast<const S*>(a.expert_w[g]);
-    G.m = blob ? min(e - b, a.T) : 0;
-    G.row0 = b;
-    Ig = a.I;
-  } else {
-    const int s = g - a.n_routed;
-    G.shared_idx = s;
-    blob = static_cast<const S*>(a.shared_w[s]);
-    G.m = a.T; G.row0 = 0;
-    Ig = a.shared_I[s];
+  const int n_sh_groups = (MODE == kDown) ? a.n_slabs : a.n_shared;
+  if (g < n_sh_groups) {
+    int s = g, chunk = 0;
+    if (MODE == kDown) { s = a.slab_shared[g]; chunk = a.slab_chunk[g]; }
+    const int Is = a.shared_I[s];
+    const S* blob = static_cast<const S*>(a.shared_w[s]);
+    G.m = a.T;
+    if (MODE == kGateUp) {
+      G.N = Is; G.K = a.H; G.ldw = a.H;
+      G.w0 = blob; G.b = a.x; G.out = a.h_shared[s];
+      G.wbytes = 2u * Is * a.H * esz; G.bbytes = (unsigned)a.T * a.H * esz;
+    } else {
+      const int kb = chunk * a.shared_kchunk[s];
+      G.N = a.H; G.K = min(a.shared_kchunk[s], Is - kb); G.ldw = Is;
+      G.w0 = blob + 2 * (size_t)Is * a.H + kb;
+      G.b = static_cast<const S*>(a.h_shared[s]) + kb;
+      G.out = a.shared_out + (size_t)g * a.T * a.H;
+      G.wbytes = ((unsigned)a.H * Is - kb) * esz; G.bbytes = ((unsigned)a.T * Is - kb) * esz;
+    }
+    return G;
   }
+  const int e = g - n_sh_groups;
+  const int b0 = clampi(a.offsets[e], 0, a.max_pairs);
+  const int b1 = clampi(a.offsets[e + 1], b0, a.max_pairs);
+  const S* blob = static_cast<const S*>(a.expert_w[e]);
+  G.m = blob ? min(b1 - b0, a.T) : 0;
+  G.row0 = b0;
   if (MODE == kGateUp) {
-    G.N = Ig; G.K = a.H;
-    G.w0 = blob; G.w1 = blob + (size_t)Ig * a.H;
+    G.N = a.I; G.K = a.H; G.ldw = a.H; G.gather = 1;
+    G.w0 = blob; G.b = a.x;
+    G.out = static_cast<S*>(a.h_routed) + (size_t)b0 * a.I;
+    G.wbytes = 2u * a.I * a.H * esz; G.bbytes = (unsigned)a.T * a.H * esz;
   } else {
-    G.N = a.H; G.K = Ig;
-    G.w0 = blob + 2 * (size_t)Ig * a.H; G.w1 = nullptr;
+    G.N = a.H; G.K = a.I; G.ldw = a.I;
+    G.w0 = blob + 2 * (size_t)a.I * a.H;
+    G.b = static_cast<const S*>(a.h_routed) + (size_t)b0 * a.I;
+    G.out = a.y + (size_t)b0 * a.H;
+    G.wbytes = (unsigned)a.H * a.I * esz; G.bbytes = (unsigned)G.m * a.I * esz;
   }
   return G;
 }
@@ -130,25 +183,65 @@ __device__ __forceinline__ Group<ET> resolve_group(const StreamArgs& a, int g) {
 template <int MODE>
 __device__ __forceinline__ int rows_per_item() { return MODE == kGateUp ? 16 : 16 * kRT; }
 
-template <typename ET, int MODE>
-__global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
-  typedef typename ET::storage S;
+// K loop of one work item for one wave: k-steps ks = wave, wave + NW, ...  (32 k each).
+// aoff / boff: byte offsets of this lane's rows at k = 0 (kOob for rows that do not exist).
+template <typename ET, int NTI, int DEPTH, int NW>
+__device__ __forceinline__ void k_loop(f32x4 (&acc)[kRT][kNT], __amdgpu_buffer_rsrc_t ra_rsrc,
+                                       __amdgpu_buffer_rsrc_t rb_rsrc, const unsigned (&aoff)[kRT],
+                                       const unsigned (&boff)[kNT], int K, int wave, int q) {
   typedef typename ET::frag Frag;
-  constexpr int U = ET::kUnroll;
+  constexpr unsigned esz = sizeof(typename ET::storage);
+  Frag ra[DEPTH][kRT], rb[DEPTH][NTI];
+  const int nks = (K + 31) >> 5;
+  const int nsteps = (nks + NW - 1) / NW;                   // same for every wave of the workgroup
+  auto fill = [&](int d, int step) {
+    const int k0 = (wave + step * NW) * 32 + q * 8;
+    const bool kval = k0 < K;
+    const unsigned koff = (unsigned)k0 * esz;               // kOob + koff stays out of range
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) ra[d][rt] = ET::load(ra_rsrc, kval ? aoff[rt] + koff : kOob);
+#pragma unroll
+    for (int nt = 0; nt < NTI; ++nt) rb[d][nt] = ET::load(rb_rsrc, kval ? boff[nt] + koff : kOob);
+  };
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) fill(d, d);
+  for (int i = 0; i < nsteps; i += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+#pragma unroll
+      for (int nt = 0; nt < NTI; ++nt)
+#pragma unroll
+        for (int rt = 0; rt < kRT; ++rt) acc[rt][nt] = ET::mma(ra[d][rt], rb[d][nt], acc[rt][nt]);
+      fill(d, i + d + DEPTH);                               // k-steps past the end fetch nothing
+      // keep the per-step order (consume oldest, refill it): without this the scheduler hoists
+      // all MFMAs above all loads and the ring degenerates into load-all / wait-all / compute-all
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// NW = waves of a workgroup that split the K dimension of one work item.
+template <typename ET, int MODE, int NW>
+__global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
+  typedef typename ET::storage S;
+  constexpr int kThreads = NW * 64;
+  constexpr unsigned esz = sizeof(S);
 
   __shared__ int s_cnt[kMaxGroups];
   __shared__ int s_prefix[kMaxGroups + 1];
-  __shared__ float s_red[kNW][kRT * kNT][4][64];
+  __shared__ Group s_group[kMaxGroups];
+  __shared__ float s_red[NW][kRT * kNT][4][64];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q = lane >> 4, c16 = lane & 15;
-  const int n_groups = (MODE == kRouter) ? 1 : a.n_routed + a.n_shared;
+  const int n_groups = (MODE == kRouter) ? 1 : a.n_routed + (MODE == kDown ? a.n_slabs : a.n_shared);
 
-  // ---- item list: tiles per group, exclusive prefix (wave 0) ----
+  // ---- group table and item list: tiles per group, exclusive prefix (wave 0) ----
   for (int g = tid; g < n_groups; g += kThreads) {
-    const Group<ET> G = resolve_group<ET, MODE>(a, g);
+    const Group G = resolve_group<ET, MODE>(a, g);
     const int rows = (G.N + rows_per_item<MODE>() - 1) / rows_per_item<MODE>();
     const int tgs = (G.m + 16 * kNT - 1) / (16 * kNT);
+    s_group[g] = G;
     s_cnt[g] = rows * tgs;
   }
   __syncthreads();
@@ -178,43 +271,32 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
       if (s_prefix[mid] <= item) lo = mid; else hi = mid;
     }
     const int g = lo;
-    const Group<ET> G = resolve_group<ET, MODE>(a, g);
+    const Group G = s_group[g];
     const int local = item - s_prefix[g];
     const int tgs = (G.m + 16 * kNT - 1) / (16 * kNT);
     const int row_item = local / tgs;
     const int r0 = (local - row_item * tgs) * (16 * kNT);
     const int n0 = row_item * rows_per_item<MODE>();
     const int ntn = min(kNT, (G.m - r0 + 15) >> 4);       // token tiles in use (wave-uniform)
-    const int K = G.K;
 
-    // ---- operand row pointers ----
-    const S* Arow[kRT];
-    bool Aval[kRT];
+    // ---- operand buffers and this lane's row offsets ----
+    const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(G.w0, G.wbytes);
+    const __amdgpu_buffer_rsrc_t rb_rsrc = make_rsrc(G.b, G.bbytes);
+    unsigned aoff[kRT], boff[kNT];
 #pragma unroll
     for (int rt = 0; rt < kRT; ++rt) {
       const int n = (MODE == kGateUp) ? n0 + c16 : n0 + rt * 16 + c16;
-      const S* base = (MODE == kGateUp && rt == 1) ? G.w1 : G.w0;
-      Aval[rt] = n < G.N;
-      Arow[rt] = base + (size_t)n * K;
+      unsigned off = (unsigned)n * (unsigned)G.ldw * esz;
+      if (MODE == kGateUp && rt == 1) off += (unsigned)G.N * (unsigned)G.ldw * esz;   // W_up follows W_gate
+      aoff[rt] = n < G.N ? off : kOob;
     }
-    const S* Brow[kNT];
-    bool Bval[kNT];
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
       const int r = r0 + nt * 16 + c16;
-      Bval[nt] = r < G.m;
-      size_t row = 0;
-      if (Bval[nt]) {
-        if (MODE == kGateUp && G.shared_idx < 0) row = (size_t)clampi(a.sorted_token[G.row0 + r], 0, a.T - 1);
-        else row = (size_t)r;
-      }
-      const S* bbase;
-      if (MODE == kDown)
-        bbase = (G.shared_idx >= 0) ? static_cast<const S*>(a.h_shared[G.shared_idx])
-                                    : static_cast<const S*>(a.h_routed) + (size_t)G.row0 * K;
-      else
-        bbase = static_cast<const S*>(a.x);
-      Brow[nt] = bbase + row * K;
+      const bool val = nt < ntn && r < G.m;
+      int row = r;
+      if (G.gather) row = val ? clampi(a.sorted_token[G.row0 + r], 0, a.T - 1) : 0;
+      boff[nt] = val ? (unsigned)row * (unsigned)G.ldw * esz : kOob;
     }
 
     f32x4 acc[kRT][kNT];
@@ -223,29 +305,8 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
 #pragma unroll
       for (int nt = 0; nt < kNT; ++nt) acc[rt][nt] = f32x4{0, 0, 0, 0};
 
-    // ---- K loop: the waves of the workgroup interleave over 32-wide k steps ----
-    const int nks = (K + 31) >> 5;
-    for (int ks = wave; ks < nks; ks += kNW * U) {
-      Frag fa[U][kRT], fb[U][kNT];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int k0 = (ks + u * kNW) * 32 + q * 8;
-        const bool kval = k0 < K;
-#pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) fa[u][rt] = (kval && Aval[rt]) ? ET::load(Arow[rt] + k0) : ET::zero();
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-          if (nt < ntn) fb[u][nt] = (kval && Bval[nt]) ? ET::load(Brow[nt] + k0) : ET::zero();
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-          if (nt < ntn) {
-#pragma unroll
-            for (int rt = 0; rt < kRT; ++rt) acc[rt][nt] = ET::mma(fa[u][rt], fb[u][nt], acc[rt][nt]);
-          }
-    }
+    if (ntn == 1 || kNT == 1) k_loop<ET, 1, ET::kDepth1, NW>(acc, ra_rsrc, rb_rsrc, aoff, boff, G.K, wave, q);
+    else                      k_loop<ET, kNT, ET::kDepth4, NW>(acc, ra_rsrc, rb_rsrc, aoff, boff, G.K, wave, q);
 
     // ---- reduce the K split through LDS ----
 #pragma unroll
@@ -259,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
     __syncthreads();
 
     // ---- epilogue: wave w owns token tiles w, w+NW, ... ----
-    for (int nt = wave; nt < ntn; nt += kNW) {
+    for (int nt = wave; nt < ntn; nt += NW) {
       float val[kRT][4];
 #pragma unroll
       for (int rt = 0; rt < kRT; ++rt)
@@ -267,7 +328,7 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
         for (int v = 0; v < 4; ++v) {
           float sum = 0.f;
 #pragma unroll
-          for (int w = 0; w < kNW; ++w) sum += s_red[w][rt * kNT + nt][v][lane];
+          for (int w = 0; w < NW; ++w) sum += s_red[w][rt * kNT + nt][v][lane];
           val[rt][v] = sum;
         }
       const int r = r0 + nt * 16 + c16;
@@ -281,18 +342,14 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
               const float gte = val[0][v];
               hv[v] = gte / (1.f + __expf(-gte)) * val[1][v];
             }
-            S* hbase = (G.shared_idx >= 0) ? static_cast<S*>(a.h_shared[G.shared_idx])
-                                           : static_cast<S*>(a.h_routed) + (size_t)G.row0 * G.N;
-            ET::store4(hbase + (size_t)r * G.N + i, hv[0], hv[1], hv[2], hv[3]);
+            ET::store4(static_cast<S*>(G.out) + (size_t)r * G.N + i, hv[0], hv[1], hv[2], hv[3]);
           }
         } else if (MODE == kDown) {
-          float* obase = (G.shared_idx >= 0) ? a.shared_out + (size_t)G.shared_idx * a.T * a.H
-                                             : a.y + (size_t)G.row0 * a.H;
 #pragma unroll
           for (int rt = 0; rt < kRT; ++rt) {
             const int c = n0 + rt * 16 + 4 * q;
             if (c < G.N)
-              *reinterpret_cast<f32x4*>(obase + (size_t)r * a.H + c) =
+              *reinterpret_cast<f32x4*>(static_cast<float*>(G.out) + (size_t)r * a.H + c) =
                   f32x4{val[rt][0], val[rt][1], val[rt][2], val[rt][3]};
           }
         } else {  // kRouter
@@ -310,8 +367,9 @@ __global__ __launch_bounds__(kThreads) void stream_kernel(const StreamArgs a) {
   }
 }
 
-template <typename ET, int MODE>
+template <typename ET, int MODE, int NW>
 int launch_typed(const StreamArgs& a, hipStream_t s) {
+  constexpr int kThreads = NW * 64;
   // upper bound of the item count (the device computes the exact list)
   const long tg_all = (a.T + 16 * kNT - 1) / (16 * kNT);
   long items = 0;
@@ -324,13 +382,24 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
     const long routed_rows = row_items(MODE == kGateUp ? a.I : a.H, per);
     const long pairs_blocks = (a.max_pairs + 16 * kNT - 1) / (16 * kNT) + a.n_routed;
     items += a.n_routed ? routed_rows * (pairs_blocks < a.n_routed * tg_all ? pairs_blocks : a.n_routed * tg_all) : 0;
-    for (int sidx = 0; sidx < a.n_shared; ++sidx)
-      items += row_items(MODE == kGateUp ? a.shared_I[sidx] : a.H, per) * tg_all;
+    if (MODE == kGateUp)
+      for (int sidx = 0; sidx < a.n_shared; ++sidx) items += row_items(a.shared_I[sidx], per) * tg_all;
+    else
+      items += (long)a.n_slabs * row_items(a.H, per) * tg_all;
   }
   if (items <= 0) return MOE_OK;
-  long grid = (long)device_cu_count() * 4;
+  // persistent workgroups: exactly as many as are resident at once, so that the static striding
+  // over the item list never leaves a second, partially filled round of workgroups
+  static int per_cu = 0;
+  if (per_cu == 0) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, stream_kernel<ET, MODE, NW>, kThreads, 0) != hipSuccess || n < 1) n = 2;
+    if (const char* env = getenv("MOE_STREAM_WG_PER_CU")) { const int v = atoi(env); if (v > 0) n = v; }
+    per_cu = n;
+  }
+  long grid = (long)device_cu_count() * per_cu;
   if (grid > items) grid = items;
-  hipLaunchKernelGGL((stream_kernel<ET, MODE>), dim3((unsigned)grid), dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL((stream_kernel<ET, MODE, NW>), dim3((unsigned)grid), dim3(kThreads), 0, s, a);
   return hip_fail(hipGetLastError(), "stream_kernel launch");
 }
 
@@ -339,15 +408,15 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s) {
   if (dtype == MOE_BF16) {
     switch (mode) {
-      case kRouter: return launch_typed<BF16, kRouter>(a, s);
-      case kGateUp: return launch_typed<BF16, kGateUp>(a, s);
-      case kDown: return launch_typed<BF16, kDown>(a, s);
+      case kRouter: return launch_typed<BF16, kRouter, 4>(a, s);
+      case kGateUp: return launch_typed<BF16, kGateUp, 4>(a, s);
+      case kDown: return launch_typed<BF16, kDown, 4>(a, s);
     }
   } else {
     switch (mode) {
-      case kRouter: return launch_typed<FP32, kRouter>(a, s);
-      case kGateUp: return launch_typed<FP32, kGateUp>(a, s);
-      case kDown: return launch_typed<FP32, kDown>(a, s);
+      case kRouter: return launch_typed<FP32, kRouter, 4>(a, s);
+      case kGateUp: return launch_typed<FP32, kGateUp, 4>(a, s);
+      case kDown: return launch_typed<FP32, kDown, 4>(a, s);
     }
   }
   return fail(MOE_E_BADARG, "bad stream mode/dtype");
