@@ -2,6 +2,7 @@
 // against what the kernels and their grids assume before anything is enqueued.
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -277,13 +278,21 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
   a.n_slabs = shared ? plan.n_slabs : 0;
   for (int i = 0; i < a.n_slabs; ++i) { a.slab_shared[i] = plan.slab_shared[i]; a.slab_chunk[i] = plan.slab_chunk[i]; }
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // Regime: with many tokens per step the experts see enough rows for LDS-tiled MFMA GEMMs;
+  // below that the weights are streamed once through the skinny kernel.
+  static int tiled_min_t = -1;
+  if (tiled_min_t < 0) {
+    tiled_min_t = 256;
+    if (const char* env = getenv("MOE_TILED_MIN_T")) tiled_min_t = atoi(env) > 0 ? atoi(env) : 1 << 30;
+  }
+  const bool tiled = cfg->dtype == MOE_BF16 && cfg->T >= tiled_min_t;
   {
     ProfScope ps(kProfFfnGateUp, s);
-    rc = launch_stream(kGateUp, cfg->dtype, a, s);
+    rc = tiled ? launch_tiled(kGateUp, a, s) : launch_stream(kGateUp, cfg->dtype, a, s);
     if (rc) return rc;
   }
   ProfScope ps(kProfFfnDown, s);
-  return launch_stream(kDown, cfg->dtype, a, s);
+  return tiled ? launch_tiled(kDown, a, s) : launch_stream(kDown, cfg->dtype, a, s);
 }
 
 extern "C" int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,

@@ -76,7 +76,7 @@ struct StreamArgs {
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s);
 
 // ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime, bf16) -------------------------
-int launch_tiled_ffn(const StreamArgs& a, hipStream_t s);
+int launch_tiled(StreamMode mode, const StreamArgs& a, hipStream_t s);
 
 // ---- selection, dispatch, combine -----------------------------------------------------------
 int launch_route(const moe_config& c, const float* conf, const float* logits, int32_t* idx,
