@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="distinct layers cycled (0 = auto)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of known size (scale for the rocprofv3 HBM counters)")
     return ap.parse_args()
 
 
@@ -219,6 +221,17 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("no GPU visible")
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps(dict(calibration="device copy", launches=10, read_bytes_per_launch=n,
+                              write_bytes_per_launch=n)))
+        return
 
     cfg = workload_config(args.workload, args.ratio)
     main_res = time_workload(mm, torch, cfg, args.steps, args.warmup, args.layers)

@@ -226,6 +226,17 @@ const void* const* moe_cache_expert_table(moe_cache_t* cache);
 int expert_cache_fetch(moe_cache_t* cache, const int32_t* expert_ids, int32_t n, int32_t mode,
                        int32_t* slot_of, moe_fetch_stats* stats, void* compute_stream);
 
+/* The execution stage of one step when the routed experts live in host DRAM (Sec. II-B): copies
+ * expert_offsets to the host and WAITS for it (the one host synchronisation of such a step: the
+ * router decides which experts must be loaded), then runs the shared experts and, in waves of at
+ * most n_slots experts (resident ones first), expert_cache_fetch(DEMAND) + the grouped FFN of
+ * that wave's experts.  Arguments as moe_expert_ffn; total (sum of the waves' statistics) and
+ * n_waves may be NULL. */
+int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* cache, const void* x,
+                          const int32_t* expert_offsets, const int32_t* sorted_token,
+                          const void* const* shared_w, float* y, float* shared_out, void* ws,
+                          size_t ws_bytes, moe_fetch_stats* total, int32_t* n_waves, void* stream);
+
 /* Host-side view of the cache state (tests, metrics): resident_expert host [n_slots] out,
  * -1 for an empty slot.  Returns n_slots. */
 int moe_cache_snapshot(moe_cache_t* cache, int32_t* resident_expert);

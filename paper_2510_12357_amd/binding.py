@@ -28,7 +28,7 @@ ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "M
 EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_expert_ffn_workspace_bytes",
            "moe_shared_out_slabs", "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
-           "moe_cache_expert_table", "expert_cache_fetch", "moe_cache_snapshot", "moe_cache_sync")
+           "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync")
 
 
 class MoeError(RuntimeError):
@@ -89,10 +89,12 @@ def load_library() -> ctypes.CDLL:
     lib.moe_cache_expert_table.restype = vp
     lib.expert_cache_fetch.argtypes = [vp, ctypes.POINTER(i32), i32, i32, ctypes.POINTER(i32),
                                        ctypes.POINTER(moe_fetch_stats), vp]
+    lib.moe_expert_ffn_cached.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, vp, vp, sz,
+                                          ctypes.POINTER(moe_fetch_stats), ctypes.POINTER(i32), vp]
     lib.moe_cache_snapshot.argtypes = [vp, ctypes.POINTER(i32)]
     lib.moe_cache_sync.argtypes = [vp]
     for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence", "moe_dispatch",
-                 "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_cache_snapshot",
+                 "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot",
                  "moe_cache_sync"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -231,6 +233,18 @@ def expert_cache_fetch(cache: int, expert_ids: Sequence[int], mode: int, stream=
     _check(load_library().expert_cache_fetch(ctypes.c_void_p(cache), ids, n, mode, slots,
                                              ctypes.byref(st), _stream(stream)))
     return list(slots[:n]), st
+
+
+def moe_expert_ffn_cached(cfg: moe_config, cache: int, x, expert_offsets, sorted_token, shared_w: Sequence,
+                          y, shared_out, ws, ws_bytes: int, stream=None):
+    """-> (summed moe_fetch_stats, number of waves)"""
+    sw = (ctypes.c_void_p * max(1, len(shared_w)))(*[t.data_ptr() for t in shared_w])
+    st, nw = moe_fetch_stats(), ctypes.c_int32(0)
+    _check(load_library().moe_expert_ffn_cached(ctypes.byref(cfg), ctypes.c_void_p(cache), _ptr(x),
+                                                _ptr(expert_offsets), _ptr(sorted_token), sw, _ptr(y),
+                                                _ptr(shared_out), _ptr(ws), ws_bytes, ctypes.byref(st),
+                                                ctypes.byref(nw), _stream(stream)))
+    return st, nw.value
 
 
 def moe_cache_snapshot(cache: int, n_slots: int):

@@ -10,6 +10,7 @@
 //   released[s]  recorded on the compute stream at the start of the first fetch call after the
 //                slot was handed out by a DEMAND call, i.e. after every kernel that may read the
 //                slot has been enqueued; a later copy into the slot waits for it
+#include <algorithm>
 #include <vector>
 
 #include "internal.h"
@@ -26,6 +27,7 @@ struct moe_cache {
   std::vector<char> pending_release, has_ready, has_released;
   std::vector<hipEvent_t> ready, released;
   uint64_t clock = 0, epoch = 0;
+  int32_t* h_offsets = nullptr;            // pinned host, [E+1]: landing zone of expert_offsets
 };
 
 namespace mm {
@@ -96,6 +98,7 @@ extern "C" moe_cache_t* moe_cache_create(int32_t E, size_t blob_bytes, int32_t n
   bool ok = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->d_table, sizeof(void*) * E) == hipSuccess;
   ok = ok && hipMemset((void*)c->d_table, 0, sizeof(void*) * E) == hipSuccess;
+  ok = ok && hipHostMalloc((void**)&c->h_offsets, sizeof(int32_t) * (E + 1), hipHostMallocDefault) == hipSuccess;
   for (int s = 0; ok && s < n_slots; ++s) {
     hipEvent_t a, b;
     ok = hipEventCreateWithFlags(&a, hipEventDisableTiming) == hipSuccess &&
@@ -116,6 +119,7 @@ extern "C" void moe_cache_destroy(moe_cache_t* c) {
   for (hipEvent_t e : c->ready) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->released) (void)hipEventDestroy(e);
   if (c->d_table) (void)hipFree((void*)c->d_table);
+  if (c->h_offsets) (void)hipHostFree(c->h_offsets);
   delete c;
 }
 
@@ -213,5 +217,58 @@ extern "C" int expert_cache_fetch(moe_cache_t* c, const int32_t* ids, int32_t n,
   }
   st.bytes_h2d = (uint64_t)st.misses * c->blob_bytes;
   if (stats) *stats = st;
+  return MOE_OK;
+}
+
+// One step's execution stage with offloaded experts: the router's decision is brought to the
+// host (the only host synchronisation of a step), the needed experts are fetched in waves of at
+// most n_slots (resident ones first, so their compute overlaps the first copies), and each wave
+// runs the grouped FFN on exactly its experts through the cache's pointer table.
+extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, const void* x,
+                                     const int32_t* expert_offsets, const int32_t* sorted_token,
+                                     const void* const* shared_w, float* y, float* shared_out, void* ws,
+                                     size_t ws_bytes, moe_fetch_stats* total, int32_t* n_waves,
+                                     void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!c) return fail(MOE_E_BADARG, "moe_expert_ffn_cached: cache is NULL");
+  if (cfg->E != c->E) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: cache holds %d experts, layer has %d", c->E, cfg->E);
+  const size_t need = (size_t)3 * cfg->H * cfg->I * elem_bytes(cfg->dtype);
+  if (need != c->blob_bytes) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: blob of %zu bytes, layer needs %zu", c->blob_bytes, need);
+  moe_fetch_stats sum = {0, 0, 0, 0, 0};
+  if (n_waves) *n_waves = 0;
+  if (total) *total = sum;
+  if (cfg->T == 0) return MOE_OK;
+  if (!expert_offsets) return fail(MOE_E_BADARG, "moe_expert_ffn_cached: expert_offsets is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  MM_HIP(hipMemcpyAsync(c->h_offsets, expert_offsets, sizeof(int32_t) * (c->E + 1), hipMemcpyDeviceToHost, s));
+  // shared experts do not depend on the router: enqueue them before waiting for it
+  if (cfg->n_shared > 0) {
+    rc = moe_expert_ffn(cfg, x, expert_offsets, sorted_token, nullptr, shared_w, 0, 1, y, shared_out, ws, ws_bytes, stream);
+    if (rc) return rc;
+  }
+  MM_HIP(hipStreamSynchronize(s));
+  std::vector<int32_t> order;                      // resident experts first, then the misses
+  for (int pass = 0; pass < 2; ++pass)
+    for (int e = 0; e < c->E; ++e) {
+      if (c->h_offsets[e + 1] <= c->h_offsets[e]) continue;
+      const bool resident = c->expert_slot[e] >= 0;
+      if ((pass == 0) == resident) order.push_back(e);
+    }
+  std::vector<int32_t> slots(c->n_slots);
+  int waves = 0;
+  for (size_t i = 0; i < order.size(); i += c->n_slots) {
+    const int n = (int)std::min<size_t>(c->n_slots, order.size() - i);
+    moe_fetch_stats st;
+    rc = expert_cache_fetch(c, order.data() + i, n, MOE_FETCH_DEMAND, slots.data(), &st, stream);
+    if (rc) return rc;
+    sum.hits += st.hits; sum.misses += st.misses; sum.bytes_h2d += st.bytes_h2d;
+    rc = moe_expert_ffn(cfg, x, expert_offsets, sorted_token, moe_cache_expert_table(c), nullptr, 1, 0, y,
+                        shared_out, ws, ws_bytes, stream);
+    if (rc) return rc;
+    ++waves;
+  }
+  if (n_waves) *n_waves = waves;
+  if (total) *total = sum;
   return MOE_OK;
 }

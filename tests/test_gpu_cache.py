@@ -1,0 +1,132 @@
+"""Expert cache on the GPU: fetch/prefetch decisions equal the host-only model, the slots hold the
+host blobs bit for bit, and a layer whose experts live in pinned host DRAM equals the oracle."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle.cache_model import DEMAND, PREFETCH, CacheModel
+from paper_2510_12357_amd import binding as mm
+from paper_2510_12357_amd import workloads as wl
+from gpu_util import TOL_OUT, DeviceLayer, out_to_f64, rel_err, run_oracle_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def make_cache(E, blob_elems, n_slots, seed=0):
+    g = torch.Generator().manual_seed(seed)
+    host = torch.randint(-2 ** 15, 2 ** 15, (E, blob_elems), dtype=torch.int16, generator=g).pin_memory()
+    dev = torch.zeros((n_slots, blob_elems), dtype=torch.int16, device="cuda")
+    h = mm.moe_cache_create(E, blob_elems * 2, n_slots, host, dev)
+    return h, host, dev
+
+
+def test_trace_matches_model_and_bytes_land():
+    E, n_slots, blob = 24, 6, 4096
+    h, host, dev = make_cache(E, blob, n_slots)
+    model = CacheModel(E, n_slots)
+    rnd = random.Random(3)
+    try:
+        for step in range(120):
+            if rnd.random() < 0.55:
+                ids, mode = rnd.sample(range(E), rnd.randint(0, n_slots)), DEMAND
+            else:
+                ids, mode = rnd.sample(range(E), rnd.randint(0, 10)), PREFETCH
+            slots, st = mm.expert_cache_fetch(h, ids, mode)
+            ref_slots, hits, misses, dropped = model.fetch(ids, mode)
+            assert slots == ref_slots, (step, ids, mode)
+            assert (st.hits, st.misses, st.dropped) == (hits, misses, dropped)
+            assert st.bytes_h2d == misses * blob * 2
+            assert mm.moe_cache_snapshot(h, n_slots) == model.slot_expert
+            if mode == DEMAND:
+                torch.cuda.synchronize()          # the compute stream waited for the copies
+                for e, s in zip(ids, slots):
+                    assert torch.equal(dev[s].cpu(), host[e]), (step, e, s)
+        mm.moe_cache_sync(h)
+        for s, e in enumerate(model.slot_expert):
+            if e >= 0:
+                assert torch.equal(dev[s].cpu(), host[e])
+    finally:
+        mm.moe_cache_destroy(h)
+
+
+def test_fetch_errors():
+    h, host, dev = make_cache(8, 1024, 2)
+    try:
+        with pytest.raises(mm.MoeError) as ei:
+            mm.expert_cache_fetch(h, [0, 1, 2], DEMAND)
+        assert ei.value.code == -5
+        with pytest.raises(mm.MoeError) as ei:
+            mm.expert_cache_fetch(h, [1, 1], DEMAND)
+        assert ei.value.code == -1
+        with pytest.raises(mm.MoeError) as ei:
+            mm.expert_cache_fetch(h, [8], PREFETCH)
+        assert ei.value.code == -1
+        slots, st = mm.expert_cache_fetch(h, [], DEMAND)
+        assert slots == [] and st.misses == 0
+    finally:
+        mm.moe_cache_destroy(h)
+
+
+def run_offloaded(cfg, n_slots, seed, steps=2, prefetch=False):
+    """The layer with routed experts in pinned host DRAM behind an n_slots cache."""
+    layer = wl.make_layer(cfg, seed=seed)
+    dl = DeviceLayer(layer)                    # x, Wg, shared experts on the device
+    blob_elems = 3 * cfg.H * cfg.I
+    host = torch.stack([mm.to_device(b, cfg, "cpu") for b in layer.expert_w]).pin_memory()
+    slots_dev = torch.zeros((n_slots, blob_elems), dtype=host.dtype, device="cuda")
+    h = mm.moe_cache_create(cfg.E, blob_elems * host.element_size(), n_slots, host, slots_dev)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    ref = run_oracle_layer(layer, logits=logits)
+    stats = []
+    try:
+        for it in range(steps):
+            b = mm.StepBuffers(cfg)
+            b.logits.copy_(torch.from_numpy(logits))
+            mm.moe_route(b.c, dl.x, dl.Wg, dl.gate_bias, dl.conf, b.logits, True, b.topk_idx, b.topk_w,
+                         b.important, b.k_t)
+            if prefetch and it == 0:
+                # router outputs of the discarded little pass name the big pass's experts (Sec. III-B)
+                flagged = np.nonzero(ref["important"])[0]
+                want = []
+                for t in flagged:
+                    for e in np.argsort(-logits[t], kind="stable")[:cfg.k_big]:
+                        if int(e) not in want:
+                            want.append(int(e))
+                mm.expert_cache_fetch(h, want, PREFETCH)
+            mm.moe_dispatch(b.c, b.topk_idx, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                            b.dws, b.dws_bytes)
+            st, waves = mm.moe_expert_ffn_cached(b.c, h, dl.x, b.expert_offsets, b.sorted_token, dl.shared, b.y,
+                                                 b.shared_out, b.fws, b.fws_bytes)
+            mm.moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out)
+            torch.cuda.synchronize()
+            stats.append((st.hits, st.misses, waves))
+            assert np.array_equal(b.expert_offsets.cpu().numpy(), ref["expert_offsets"])
+            e = rel_err(out_to_f64(b.out), ref["out"])
+            assert e <= TOL_OUT, (it, e)
+    finally:
+        mm.moe_cache_destroy(h)
+    return stats, ref
+
+
+def test_offloaded_layer_small_needs_waves():
+    cfg = wl.LayerConfig("off_small", T=16, H=264, E=12, I=136, k_big=4, k_little=2, shared_I=(72, 40),
+                         gate_std=0.3, w_std=0.1, fallback_ratio=0.3)
+    stats, ref = run_offloaded(cfg, n_slots=3, seed=2)
+    D = int((np.diff(ref["expert_offsets"]) > 0).sum())
+    assert D > 3
+    h0, m0, w0 = stats[0]
+    assert h0 == 0 and m0 == D and w0 == -(-D // 3)           # cold cache: every needed expert is copied
+    h1, m1, w1 = stats[1]
+    assert h1 + m1 == D and h1 >= 1                             # the last wave's experts are still resident
+
+
+def test_shared2_offload_config_full_size():
+    cfg = wl.CONFIGS["shared2_offload"]
+    stats, ref = run_offloaded(cfg, n_slots=16, seed=0, steps=2, prefetch=True)
+    D = int((np.diff(ref["expert_offsets"]) > 0).sum())
+    assert D > 16                                               # the step needs more experts than slots
+    assert stats[0][0] + stats[0][1] == D and stats[0][0] >= 1  # prefetched experts count as hits
+    assert stats[0][2] == -(-D // 16)
