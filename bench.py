@@ -201,12 +201,14 @@ def cpu_baseline(torch, cfg, layers: DeviceLayers, budget_s: float = 12.0):
 
 
 def stored_traffic(workload: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
-    p = os.path.join(ROOT, "profiles", "traffic.json")
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of
+    this workload (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None if absent."""
+    import re
+    p = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
     try:
-        with open(p) as f:
-            return json.load(f).get(workload)
-    except (OSError, ValueError):
+        m = re.search(r"HBM traffic per launch = ([0-9.]+) MB", open(p).read())
+        return float(m.group(1)) * 1e6 if m else None
+    except OSError:
         return None
 
 
