@@ -208,7 +208,7 @@ extern "C" int moe_token_confidence(const float* lm_logits, int32_t T, int32_t V
 
 extern "C" size_t moe_dispatch_workspace_bytes(const moe_config* cfg) {
   if (validate_config(cfg)) return 0;
-  return align256(sizeof(int32_t) * (size_t)cfg->E);
+  return align256(sizeof(int32_t) * (size_t)cfg->E * (size_t)(dispatch_chunks(cfg->T) + 1));
 }
 
 extern "C" int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t,

@@ -7,8 +7,8 @@
 // ascending order and compacting the matches with ballot/popcount prefix sums, so the result is
 // unique and reproducible.  Two shapes:
 //   * T <= kSmallT: one workgroup, one wave per expert (round-robin), one launch.
-//   * larger T: one workgroup per expert; a count kernel, then a scatter kernel that rebuilds
-//     the exclusive prefix of the counts itself.
+//   * larger T: one workgroup per chunk of 128 tokens; a count kernel, then a scatter kernel
+//     that rebuilds the prefixes of the counts itself.
 #include "internal.h"
 
 namespace mm {
@@ -20,34 +20,6 @@ constexpr int kBigThreads = 256;
 
 __device__ __forceinline__ unsigned long long lanemask_lt(int lane) {
   return lane == 0 ? 0ull : (~0ull >> (64 - lane));
-}
-
-// does token t route to expert e?  returns the rank j or -1
-__device__ __forceinline__ int match_rank(const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t,
-                                          int t, int T, int K, int e) {
-  if (t >= T) return -1;
-  int kt = k_t[t];
-  kt = kt < 0 ? 0 : (kt > K ? K : kt);
-  int found = -1;
-  for (int j = 0; j < kt; ++j)
-    if (found < 0 && idx[(size_t)t * K + j] == e) found = j;
-  return found;
-}
-
-// -1 fill of everything that is not a pair: positions >= P and ranks >= k_t
-__device__ __forceinline__ void fill_pads(int first, int stride, int P, int T, int E, int K,
-                                          const int32_t* __restrict__ idx,
-                                          const int32_t* __restrict__ k_t, int32_t* sorted_token,
-                                          int32_t* sorted_rank, int32_t* inv_pos) {
-  const int n = T * K;
-  for (int i = first; i < n; i += stride) {
-    if (i >= P) { sorted_token[i] = -1; sorted_rank[i] = -1; }
-    const int t = i / K, j = i - t * K;
-    int kt = k_t[t];
-    kt = kt < 0 ? 0 : (kt > K ? K : kt);
-    // ranks beyond k_t, and pairs naming an expert id outside [0,E), are not dispatched
-    if (j >= kt || (unsigned)idx[i] >= (unsigned)E) inv_pos[i] = -1;
-  }
 }
 
 // rank at which token t names expert e in the LDS copy of the selection (-1 = not named);
@@ -122,68 +94,123 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
   for (int i = P + tid; i < T * K; i += kSmallThreads) { sorted_token[i] = -1; sorted_rank[i] = -1; }
 }
 
-// ---- large T: one workgroup per expert -----------------------------------------------------
-__device__ __forceinline__ int block_sum(int v, int* s_tmp) {   // kBigThreads threads
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  __syncthreads();
-  if (lane == 0) s_tmp[wave] = v;
-  __syncthreads();
-  int tot = 0;
-#pragma unroll
-  for (int w = 0; w < kBigThreads / 64; ++w) tot += s_tmp[w];
-  return tot;
+// ---- large T: one workgroup per chunk of kChunk tokens ------------------------------------------
+// Pass 1 counts, per chunk, the pairs of every expert (LDS integer atomics: a sum, so the result
+// does not depend on their order).  Pass 2 turns the counts into each chunk's first position
+// inside every expert segment, then places the chunk's pairs expert by expert with ballot
+// prefixes, which keeps tokens ascending inside a segment.
+constexpr int kChunk = 128;
+constexpr int kCountSlab = 32 * MOE_MAX_EXPERTS;        // ints of the count table held in LDS at a time
+
+__device__ __forceinline__ void stage_chunk(const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t,
+                                            int t0, int T, int E, int K, int* s_idx,
+                                            int32_t* __restrict__ inv_pos) {
+  const int n = min(kChunk, T - t0) * K;
+  for (int i = threadIdx.x; i < n; i += kBigThreads) {
+    const int tl = i / K, j = i - tl * K;
+    int kt = k_t[t0 + tl];
+    kt = kt < 0 ? 0 : (kt > K ? K : kt);
+    const int e = idx[(size_t)t0 * K + i];
+    const bool pair = j < kt && (unsigned)e < (unsigned)E;
+    s_idx[i] = pair ? e : -1;
+    if (inv_pos && !pair) inv_pos[(size_t)t0 * K + i] = -1;
+  }
 }
 
 __global__ __launch_bounds__(kBigThreads) void dispatch_count_kernel(
-    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int K,
-    int32_t* __restrict__ counts) {
-  __shared__ int s_tmp[kBigThreads / 64];
-  const int e = blockIdx.x;
-  int cnt = 0;
-  for (int t0 = 0; t0 < T; t0 += kBigThreads)
-    cnt += match_rank(idx, k_t, t0 + threadIdx.x, T, K, e) >= 0 ? 1 : 0;
-  cnt = block_sum(cnt, s_tmp);
-  if (threadIdx.x == 0) counts[e] = cnt;
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int E, int K,
+    int32_t* __restrict__ counts /* [chunks][E] */) {
+  __shared__ int s_idx[kChunk * MOE_MAX_TOPK];
+  __shared__ int s_hist[MOE_MAX_EXPERTS];
+  const int t0 = blockIdx.x * kChunk;
+  for (int e = threadIdx.x; e < E; e += kBigThreads) s_hist[e] = 0;
+  stage_chunk(idx, k_t, t0, T, E, K, s_idx, nullptr);
+  __syncthreads();
+  const int n = min(kChunk, T - t0) * K;
+  for (int i = threadIdx.x; i < n; i += kBigThreads)
+    if (s_idx[i] >= 0) atomicAdd(&s_hist[s_idx[i]], 1);
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += kBigThreads) counts[(size_t)blockIdx.x * E + e] = s_hist[e];
 }
 
 __global__ __launch_bounds__(kBigThreads) void dispatch_scatter_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int E, int K,
-    const int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    const int32_t* __restrict__ counts, int n_chunks, int32_t* __restrict__ offsets,
     int32_t* __restrict__ sorted_token, int32_t* __restrict__ sorted_rank,
     int32_t* __restrict__ inv_pos) {
-  __shared__ int s_tmp[kBigThreads / 64];
-  __shared__ int s_wave[kBigThreads / 64];
-  const int e = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  // exclusive prefix of the counts up to e, and the total P (E <= 256 = one entry per thread)
-  const int mine = tid < E ? counts[tid] : 0;
-  const int before = block_sum(tid < e ? mine : 0, s_tmp);
-  const int P = block_sum(mine, s_tmp);
-  if (tid == 0) {
-    offsets[e] = before;
-    if (e == E - 1) offsets[E] = P;
-  }
-  int pos = before;
-  for (int t0 = 0; t0 < T; t0 += kBigThreads) {
-    const int t = t0 + tid;
-    const int j = match_rank(idx, k_t, t, T, K, e);
-    const unsigned long long b = __ballot(j >= 0);
-    if (lane == 0) s_wave[wave] = __popcll(b);
+  __shared__ int s_idx[kChunk * MOE_MAX_TOPK];
+  __shared__ int s_base[MOE_MAX_EXPERTS];       // first position of this chunk inside expert e's segment
+  __shared__ int s_wsum[kBigThreads / 64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int chunk = blockIdx.x, t0 = chunk * kChunk;
+  stage_chunk(idx, k_t, t0, T, E, K, s_idx, inv_pos);
+  // per expert (one thread each, E <= 256 = kBigThreads): pairs in earlier chunks, pairs in all
+  // chunks.  The count table goes through LDS in slabs with coalesced, independent loads (a
+  // per-thread loop over global memory would pay one memory latency per chunk).
+  __shared__ int s_cnt[kCountSlab];
+  int before = 0, tot = 0;
+  const int slab_chunks = kCountSlab / E;                  // >= 32 chunks per slab
+  for (int c0 = 0; c0 < n_chunks; c0 += slab_chunks) {
+    const int nc = min(slab_chunks, n_chunks - c0);
     __syncthreads();
-    int wbase = 0, tot = 0;
+    for (int i = tid; i < nc * E; i += kBigThreads) s_cnt[i] = counts[(size_t)c0 * E + i];
+    __syncthreads();
+    if (tid < E)
+      for (int c = 0; c < nc; ++c) {
+        const int v = s_cnt[c * E + tid];
+        if (c0 + c < chunk) before += v;
+        tot += v;
+      }
+  }
+  // exclusive prefix of tot over the experts -> expert_offsets
+  int incl = tot;
 #pragma unroll
-    for (int w = 0; w < kBigThreads / 64; ++w) { if (w < wave) wbase += s_wave[w]; tot += s_wave[w]; }
-    if (j >= 0) {
-      const int p = pos + wbase + __popcll(b & lanemask_lt(lane));
-      sorted_token[p] = t;
-      sorted_rank[p] = j;
-      inv_pos[(size_t)t * K + j] = p;
-    }
-    pos += tot;
-    __syncthreads();
+  for (int d = 1; d < 64; d <<= 1) { const int v = __shfl_up(incl, d); if (lane >= d) incl += v; }
+  if (lane == 63) s_wsum[wave] = incl;
+  __syncthreads();
+  int wbase = 0, P = 0;
+#pragma unroll
+  for (int w = 0; w < kBigThreads / 64; ++w) { if (w < wave) wbase += s_wsum[w]; P += s_wsum[w]; }
+  const int off_e = wbase + incl - tot;
+  if (tid < E) {
+    s_base[tid] = off_e + before;
+    if (chunk == 0) offsets[tid] = off_e;
   }
-  fill_pads(e * kBigThreads + tid, E * kBigThreads, P, T, E, K, idx, k_t, sorted_token, sorted_rank, inv_pos);
+  if (chunk == 0 && tid == 0) offsets[E] = P;
+  __syncthreads();
+  const int nt = min(kChunk, T - t0);
+  // each lane keeps the selections of its two tokens (one per 64-token half of the chunk) in
+  // registers, so the loop over experts is compares, a ballot and the stores
+  static_assert(kChunk == 128, "two 64-token halves per chunk");
+  int sel[2][MOE_MAX_TOPK];
+#pragma unroll
+  for (int hb = 0; hb < 2; ++hb)
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+      const int tl = hb * 64 + lane;
+      sel[hb][j] = (tl < nt && j < K) ? s_idx[tl * K + j] : -1;
+    }
+  for (int e = wave; e < E; e += kBigThreads / 64) {
+    int pos = s_base[e];
+#pragma unroll
+    for (int hb = 0; hb < 2; ++hb) {
+      int j = -1;
+#pragma unroll
+      for (int jj = MOE_MAX_TOPK - 1; jj >= 0; --jj) if (sel[hb][jj] == e) j = jj;
+      const unsigned long long b = __ballot(j >= 0);
+      if (j >= 0) {
+        const int tl = hb * 64 + lane;
+        const int p = pos + __popcll(b & lanemask_lt(lane));
+        sorted_token[p] = t0 + tl;
+        sorted_rank[p] = j;
+        inv_pos[(size_t)(t0 + tl) * K + j] = p;
+      }
+      pos += __popcll(b);
+    }
+  }
+  // positions beyond P are not pairs
+  const int n = T * K;
+  for (int i = P + chunk * kBigThreads + tid; i < n; i += n_chunks * kBigThreads) { sorted_token[i] = -1; sorted_rank[i] = -1; }
 }
 
 // T == 0: only the offsets exist
@@ -192,6 +219,8 @@ __global__ void dispatch_empty_kernel(int E, int32_t* offsets) {
 }
 
 }  // namespace
+
+int dispatch_chunks(int T) { return (T + kChunk - 1) / kChunk; }
 
 int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int32_t* offsets,
                     int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos, int32_t* counts,
@@ -202,10 +231,11 @@ int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t,
     hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kSmallThreads), 0, s, idx, k_t, c.T, c.E,
                        c.k_big, offsets, sorted_token, sorted_rank, inv_pos);
   } else {
-    hipLaunchKernelGGL(dispatch_count_kernel, dim3((unsigned)c.E), dim3(kBigThreads), 0, s, idx, k_t,
-                       c.T, c.k_big, counts);
-    hipLaunchKernelGGL(dispatch_scatter_kernel, dim3((unsigned)c.E), dim3(kBigThreads), 0, s, idx, k_t,
-                       c.T, c.E, c.k_big, counts, offsets, sorted_token, sorted_rank, inv_pos);
+    const int n_chunks = dispatch_chunks(c.T);
+    hipLaunchKernelGGL(dispatch_count_kernel, dim3((unsigned)n_chunks), dim3(kBigThreads), 0, s, idx, k_t,
+                       c.T, c.E, c.k_big, counts);
+    hipLaunchKernelGGL(dispatch_scatter_kernel, dim3((unsigned)n_chunks), dim3(kBigThreads), 0, s, idx, k_t,
+                       c.T, c.E, c.k_big, counts, n_chunks, offsets, sorted_token, sorted_rank, inv_pos);
   }
   return hip_fail(hipGetLastError(), "dispatch launch");
 }

@@ -14,8 +14,9 @@
 //     weight rows of a tile are half rows of W_gate plus the same rows of W_up, arranged so
 //     that a wave holds gate and up of the same outputs and applies SwiGLU in registers.
 //   * global -> LDS goes through registers with raw buffer loads (token gather and all ragged
-//     edges are offsets beyond the buffer: zeros, no branches); the loads of chunk k+1 are in
-//     flight while chunk k is multiplied (two LDS stages, one barrier per chunk).
+//     edges are offsets beyond the buffer: zeros, no branches); two register sets and two LDS
+//     stages form a software pipeline in which requests, LDS writes and fragment reads are
+//     spread between the MFMAs of a chunk (one barrier per chunk).
 //   * LDS rows are padded by 16 bytes so that the rows a b128 fragment read touches fall
 //     into different banks.
 //   * tiles are enumerated on the device from expert_offsets (the host never sees the counts);
@@ -152,68 +153,90 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // The chunk after the one being multiplied is on its way from global memory in registers.
-    // Chunks past the end have offsets beyond the buffers and fetch nothing.
-    i32x4 ga[kLoadsA], gb[kLoadsB];
-    auto gload = [&](int kt) {
+    // Software pipeline of one wave.  Two register sets hold chunks on their way from global
+    // memory: while chunk k is multiplied out of LDS stage k%2, chunk k+1 (requested one chunk
+    // earlier) is written to the other stage and chunk k+2 is requested.  The requests are issued
+    // during the first two of the four 16-wide k steps of a chunk, the LDS writes during the last
+    // two, and the fragments of k step j+1 are read while step j is multiplied, so memory
+    // instructions sit between the MFMAs instead of in phases of their own.  Chunks past the end
+    // have offsets beyond the buffers and fetch nothing.
+    i32x4 ga[2][kLoadsA], gb[2][kLoadsB];
+    auto gload_a = [&](int set, int kt) {
       const int k0 = kt * BK + ld_kc * 8;
       const bool kval = k0 < K;
 #pragma unroll
       for (int p = 0; p < kLoadsA; ++p)
-        ga[p] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(kval ? aoff[p] + (unsigned)k0 * 2u : kOob), 0, 0);
+        ga[set][p] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(kval ? aoff[p] + (unsigned)k0 * 2u : kOob), 0, 0);
+    };
+    auto gload_b = [&](int set, int kt) {
+      const int k0 = kt * BK + ld_kc * 8;
+      const bool kval = k0 < K;
 #pragma unroll
       for (int p = 0; p < kLoadsB; ++p)
-        gb[p] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(kval ? boff[p] + (unsigned)k0 * 2u : kOob), 0, 0);
+        gb[set][p] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(kval ? boff[p] + (unsigned)k0 * 2u : kOob), 0, 0);
     };
-    auto lstore = [&](int st) {
+    auto lstore_a = [&](int set, int st) {
 #pragma unroll
       for (int p = 0; p < kLoadsA; ++p)
-        *reinterpret_cast<i32x4*>(&As[st * BM * LDK + (ld_row + kRowsPerPass * p) * LDK + ld_kc * 8]) = ga[p];
+        *reinterpret_cast<i32x4*>(&As[st * BM * LDK + (ld_row + kRowsPerPass * p) * LDK + ld_kc * 8]) = ga[set][p];
+    };
+    auto lstore_b = [&](int set, int st) {
 #pragma unroll
       for (int p = 0; p < kLoadsB; ++p)
-        *reinterpret_cast<i32x4*>(&Bs[st * BNR * LDK + (ld_row + kRowsPerPass * p) * LDK + ld_kc * 8]) = gb[p];
+        *reinterpret_cast<i32x4*>(&Bs[st * BNR * LDK + (ld_row + kRowsPerPass * p) * LDK + ld_kc * 8]) = gb[set][p];
     };
-    auto compute = [&](int st) {
+    auto read_frags = [&](int st, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
       const S* Ast = As + st * BM * LDK;
       const S* Bst = Bs + st * BNR * LDK;
+      const int kcol = kk * 16 + (lane >> 5) * 8;
 #pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 fa[TM], fb[TN];
-        const int kcol = kk * 16 + (lane >> 5) * 8;
+      for (int i = 0; i < TM; ++i)
+        fa[i] = *reinterpret_cast<const bf16x8*>(&Ast[(wm * TM * 32 + i * 32 + (lane & 31)) * LDK + kcol]);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          fa[i] = *reinterpret_cast<const bf16x8*>(&Ast[(wm * TM * 32 + i * 32 + (lane & 31)) * LDK + kcol]);
+      for (int j = 0; j < TN; ++j) {
+        // gate/up: j < TN/2 gate rows, j >= TN/2 the matching up rows; down: TN column blocks
+        const int brow = (MODE == kGateUp)
+                             ? (j / (TN / 2)) * (BNR / 2) + wn * (TN / 2) * 32 + (j % (TN / 2)) * 32 + (lane & 31)
+                             : wn * TN * 32 + j * 32 + (lane & 31);
+        fb[j] = *reinterpret_cast<const bf16x8*>(&Bst[brow * LDK + kcol]);
+      }
+    };
+    // one chunk: multiply LDS stage st, write register set set_st to the other stage, request
+    // chunk kt_ld into register set set_ld
+    auto half = [&](int st, int set_st, int set_ld, int kt_ld) {
+      constexpr int KK = BK / 16;
+      bf16x8 fa[2][TM], fb[2][TN];
+      read_frags(st, 0, fa[0], fb[0]);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          // gate/up: j < TN/2 gate rows, j >= TN/2 the matching up rows; down: TN column blocks
-          const int brow = (MODE == kGateUp)
-                               ? (j / (TN / 2)) * (BNR / 2) + wn * (TN / 2) * 32 + (j % (TN / 2)) * 32 + (lane & 31)
-                               : wn * TN * 32 + j * 32 + (lane & 31);
-          fb[j] = *reinterpret_cast<const bf16x8*>(&Bst[brow * LDK + kcol]);
-        }
+      for (int kk = 0; kk < KK; ++kk) {
+        if (kk + 1 < KK) read_frags(st, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+#ifndef MOE_TDBG_NOLOAD
+        if (kk == 0) gload_a(set_ld, kt_ld);
+        if (kk == 1 || KK == 1) gload_b(set_ld, kt_ld);
+#endif
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+#ifndef MOE_TDBG_NOSTORE
+        if (kk == KK - 2 || KK == 1) lstore_a(set_st, st ^ 1);
+        if (kk == KK - 1) lstore_b(set_st, st ^ 1);
+#endif
+        __builtin_amdgcn_sched_barrier(0);                 // keep the steps apart; free order inside a step
       }
     };
 
     const int nk = (K + BK - 1) / BK;
-    gload(0);
-    lstore(0);
+    gload_a(0, 0); gload_b(0, 0);
+    gload_a(1, 1); gload_b(1, 1);
+    lstore_a(0, 0); lstore_b(0, 0);                        // waits for chunk 0 only
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-#ifndef MOE_TDBG_NOLOAD
-      gload(kt + 1);
-#endif
-      compute(kt & 1);
-#ifndef MOE_TDBG_NOSTORE
-      lstore((kt + 1) & 1);
-#endif
-#ifndef MOE_TDBG_NOSYNC
+    for (int kt = 0; kt < nk; kt += 2) {
+      half(0, 1, 0, kt + 2);
       __syncthreads();
-#endif
+      half(1, 0, 1, kt + 3);                               // multiplies zeros when nk is odd
+      __syncthreads();
     }
 
     // ---- epilogue: accumulator v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 ----

@@ -84,6 +84,7 @@ int launch_route(const moe_config& c, const float* conf, const float* logits, in
 int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,
                      hipStream_t s);
 int launch_confidence(const float* z, int T, int V, float* conf, hipStream_t s);
+int dispatch_chunks(int T);          // workgroups (token chunks) of the large-T dispatch
 int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int32_t* offsets,
                     int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos, int32_t* counts,
                     hipStream_t s);

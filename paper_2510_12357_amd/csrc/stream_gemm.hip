@@ -99,6 +99,11 @@ struct FP32 {
 
 template <int MODE>
 __device__ __forceinline__ int rows_per_item() { return MODE == kGateUp ? 16 : 16 * kRT; }
+// tokens per work item: the router uses single token tiles (its weight matrix is tiny and stays
+// in L2, so more and smaller items only add parallelism); the expert GEMMs reuse the streamed
+// weights for up to kNT tiles
+template <int MODE>
+__device__ __forceinline__ int tokens_per_item() { return MODE == kRouter ? 16 : 16 * kNT; }
 
 // K loop of one work item for one wave: k-steps ks = wave, wave + NW, ...  (32 k each).
 // aoff / boff: byte offsets of this lane's rows at k = 0 (kOob for rows that do not exist).
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
   for (int g = tid; g < n_groups; g += kThreads) {
     const Group G = resolve_group<typename ET::storage, MODE>(a, g);
     const int rows = (G.N + rows_per_item<MODE>() - 1) / rows_per_item<MODE>();
-    const int tgs = (G.m + 16 * kNT - 1) / (16 * kNT);
+    const int tgs = (G.m + tokens_per_item<MODE>() - 1) / tokens_per_item<MODE>();
     s_group[g] = G;
     s_cnt[g] = rows * tgs;
   }
@@ -193,11 +198,11 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
     const int g = lo;
     const Group G = s_group[g];
     const int local = item - s_prefix[g];
-    const int tgs = (G.m + 16 * kNT - 1) / (16 * kNT);
+    const int tgs = (G.m + tokens_per_item<MODE>() - 1) / tokens_per_item<MODE>();
     const int row_item = local / tgs;
-    const int r0 = (local - row_item * tgs) * (16 * kNT);
+    const int r0 = (local - row_item * tgs) * tokens_per_item<MODE>();
     const int n0 = row_item * rows_per_item<MODE>();
-    const int ntn = min(kNT, (G.m - r0 + 15) >> 4);       // token tiles in use (wave-uniform)
+    const int ntn = (MODE == kRouter) ? 1 : min(kNT, (G.m - r0 + 15) >> 4);   // token tiles in use (wave-uniform)
 
     // ---- operand buffers and this lane's row offsets ----
     const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(G.w0, G.wbytes);
@@ -295,7 +300,7 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
   long items = 0;
   auto row_items = [](int n, int per) { return (long)((n + per - 1) / per); };
   if (MODE == kRouter) {
-    items = row_items(a.E, 32) * tg_all;
+    items = row_items(a.E, 32) * ((a.T + 15) / 16);
   } else {
     const int per = (MODE == kGateUp) ? 16 : 32;
     // a routed expert holds at most T pairs, and all experts together at most T*k_big

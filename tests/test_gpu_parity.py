@@ -275,3 +275,34 @@ def test_fine64_prefill_full_size_sampled():
     ref = run_oracle_layer(layer, logits=logits, tokens=tokens)
     e = rel_err(out_to_f64(b.out)[tokens], ref["out"])
     assert e <= TOL_OUT, e
+
+
+def test_coarse8_full_size_sampled_prefill_and_single_token():
+    """The 8-expert layer with 14336-wide experts at full size: a 4096-token prefill step (tiled MFMA
+    kernels) checked on sampled tokens, and a one-token decode step (streaming kernels)."""
+    cfg = wl.CONFIGS["coarse8"]
+    layer = wl.make_layer(cfg, seed=0)
+    dl = DeviceLayer(layer)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    b = run_gpu_layer(dl, logits=logits)
+    idx, w, imp, kt = oracle.route(logits, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, cfg.renorm)
+    off, st, sr, inv = oracle.dispatch(idx, kt, cfg.E)
+    assert np.array_equal(i32(b.topk_idx), idx) and np.array_equal(b.important.cpu().numpy(), imp)
+    assert np.array_equal(i32(b.expert_offsets), off) and np.array_equal(i32(b.sorted_token), st)
+    assert np.array_equal(i32(b.sorted_rank), sr) and np.array_equal(i32(b.inv_pos), inv)
+    tokens = np.sort(np.random.default_rng(1).choice(cfg.T, size=6, replace=False))
+    ref = run_oracle_layer(layer, logits=logits, tokens=tokens)
+    e = rel_err(out_to_f64(b.out)[tokens], ref["out"])
+    assert e <= TOL_OUT, e
+    # decode: the first token alone, once little (confident) and once big (not confident)
+    one = wl.Layer(cfg.with_(T=1), layer.x[:1], layer.Wg, layer.gate_bias, layer.expert_w, layer.shared_w,
+                   layer.conf[:1])
+    dl1 = DeviceLayer.__new__(DeviceLayer)
+    dl1.__dict__.update(dl.__dict__)
+    dl1.cfg, dl1.x = one.cfg, dl.x[:1].contiguous()
+    for conf in (np.array([0.99], np.float32), np.array([0.1], np.float32)):
+        b1 = run_gpu_layer(dl1, conf=torch.from_numpy(conf).cuda(), logits=logits[:1], T=1)
+        r1 = oracle.moe_layer(one.x, one.Wg, one.gate_bias, one.expert_w, cfg.I, [], (), conf, cfg.gamma,
+                              cfg.k_big, cfg.k_little, cfg.renorm, logits=logits[:1])
+        assert np.array_equal(i32(b1.topk_idx), r1["topk_idx"])
+        assert rel_err(out_to_f64(b1.out), r1["out"]) <= TOL_OUT
