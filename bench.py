@@ -107,12 +107,25 @@ def auto_layers(cfg) -> int:
     return int(max(2, min(8, (12 << 30) // per)))
 
 
+_SIDE = {}
+
+
+def side_stream(torch):
+    """Second stream (default priority) on which the shared experts run under the router kernels."""
+    # Off by default: it gained 3-4 % at 64 tokens but costs more than it hides at small batches,
+    # and it splits the dominant kernel into two launches.  MOE_BENCH_OVERLAP=1 turns it on.
+    if "s" not in _SIDE:
+        _SIDE["s"] = torch.cuda.Stream() if os.environ.get("MOE_BENCH_OVERLAP") else None
+    return _SIDE["s"]
+
+
 def run_steps(mm, torch, layers: DeviceLayers, bufs, n: int, first: int = 0):
     L = layers.L
+    side = side_stream(torch)
     for i in range(first, first + n):
         l = i % L
         mm.layer_step(bufs, layers.x[l], layers.Wg[l], layers.bias[l], layers.conf[l], layers.table[l],
-                      layers.shared[l])
+                      layers.shared[l], side_stream=side)
 
 
 def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: bool = True):

@@ -299,16 +299,31 @@ class StepBuffers:
         self.dws = torch.empty((self.dws_bytes,), dtype=torch.uint8, device=device)
         self.fws_bytes = moe_expert_ffn_workspace_bytes(self.c)
         self.fws = torch.empty((self.fws_bytes,), dtype=torch.uint8, device=device)
+        self.ev_in, self.ev_shared = torch.cuda.Event(), torch.cuda.Event()
 
 
 def layer_step(b: StepBuffers, x, Wg, gate_bias, conf, expert_table, shared_w, logits_given=False,
-               stream=None) -> torch.Tensor:
-    """One step of the layer with all experts resident: the four C calls back to back."""
+               stream=None, side_stream=None) -> torch.Tensor:
+    """One step of the layer with all experts resident: the C calls back to back on `stream`.
+
+    With `side_stream` (a second torch stream of default priority) the shared experts, which do not
+    depend on the router, are enqueued there first and run under the router, selection and dispatch
+    kernels; the combine waits for them.  Only stream plumbing is added; the calls are the same."""
+    overlap = side_stream is not None and b.shared_out is not None
+    if overlap:
+        main = stream if stream is not None else torch.cuda.current_stream()
+        b.ev_in.record(main)                     # x is ready; the previous combine has read shared_out
+        side_stream.wait_event(b.ev_in)
+        moe_expert_ffn(b.c, x, b.expert_offsets, b.sorted_token, None, shared_w, False, True, b.y,
+                       b.shared_out, b.fws, b.fws_bytes, side_stream)
+        b.ev_shared.record(side_stream)
     moe_route(b.c, x, Wg, gate_bias, conf, b.logits, logits_given, b.topk_idx, b.topk_w, b.important,
               b.k_t, stream)
     moe_dispatch(b.c, b.topk_idx, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
                  b.dws, b.dws_bytes, stream)
-    moe_expert_ffn(b.c, x, b.expert_offsets, b.sorted_token, expert_table, shared_w, True, True, b.y,
+    moe_expert_ffn(b.c, x, b.expert_offsets, b.sorted_token, expert_table, shared_w, True, not overlap, b.y,
                    b.shared_out, b.fws, b.fws_bytes, stream)
+    if overlap:
+        main.wait_event(b.ev_shared)
     moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out, stream)
     return b.out

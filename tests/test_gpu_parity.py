@@ -306,3 +306,22 @@ def test_coarse8_full_size_sampled_prefill_and_single_token():
                               cfg.k_big, cfg.k_little, cfg.renorm, logits=logits[:1])
         assert np.array_equal(i32(b1.topk_idx), r1["topk_idx"])
         assert rel_err(out_to_f64(b1.out), r1["out"]) <= TOL_OUT
+
+
+def test_shared_experts_on_a_side_stream():
+    """Shared experts enqueued on a second stream (under the router kernels) give the same layer."""
+    cfg = wl.CONFIGS["fine60_decode"].with_(T=8)
+    layer = wl.make_layer(cfg, seed=5)
+    dl = DeviceLayer(layer)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    ref = run_oracle_layer(layer, logits=logits)
+    side = torch.cuda.Stream()
+    b = mm.StepBuffers(cfg)
+    for it in range(3):                                  # repeated steps reuse the buffers and events
+        b.logits.copy_(torch.from_numpy(logits))
+        mm.layer_step(b, dl.x, dl.Wg, dl.gate_bias, dl.conf, dl.table, dl.shared, logits_given=True,
+                      side_stream=side)
+        torch.cuda.synchronize()
+        assert rel_err(out_to_f64(b.out), ref["out"]) <= TOL_OUT
+    plain = run_gpu_layer(dl, logits=logits)
+    assert torch.equal(plain.out.view(torch.int16), b.out.view(torch.int16))
