@@ -21,6 +21,18 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsig
   return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)n, 0x00020000);
 }
 
+// Values that are the same in all lanes of a wave but come out of LDS or vector arithmetic:
+// moving them to scalar registers frees vector registers.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ unsigned uniform(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+template <typename P>
+__device__ __forceinline__ P* uniform(P* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint64_t lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+  const uint64_t hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+  return (P*)((hi << 32) | lo);
+}
+
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 // One group of the grouped GEMM, fully resolved on the device (kept in LDS).
@@ -38,14 +50,44 @@ struct Group {
   void* out;        // h rows / y rows / slab base, already advanced to row0 where it applies
 };
 
+// What resolving a group has to read from memory; the rest of a Group follows from the kernel
+// arguments alone.  A kernel that must not touch global memory while it walks its items (its
+// loads are counted) keeps these three words per group and expands them on demand.
+struct GroupSrc {
+  int m;            // token rows (0 for a routed expert without weights)
+  int row0;         // first dispatch position (routed), 0 otherwise
+  const void* blob; // expert weights [W_gate | W_up | W_down]
+};
+
 // Group order: shared experts (many tokens => heaviest items) first, then the routed experts.
+template <int MODE>
+__device__ __forceinline__ GroupSrc load_group_src(const StreamArgs& a, int g) {
+  GroupSrc s;
+  s.row0 = 0;
+  if (MODE == kRouter) { s.m = a.T; s.blob = a.Wg; return s; }
+  const int n_sh_groups = (MODE == kDown) ? a.n_slabs : a.n_shared;
+  if (g < n_sh_groups) {
+    s.m = a.T;
+    s.blob = a.shared_w[MODE == kDown ? a.slab_shared[g] : g];
+    return s;
+  }
+  const int e = g - n_sh_groups;
+  const int b0 = clampi(a.offsets[e], 0, a.max_pairs);
+  const int b1 = clampi(a.offsets[e + 1], b0, a.max_pairs);
+  s.blob = a.expert_w[e];
+  s.m = s.blob ? min(b1 - b0, a.T) : 0;
+  s.row0 = b0;
+  return s;
+}
+
 template <typename S, int MODE>
-__device__ __forceinline__ Group resolve_group(const StreamArgs& a, int g) {
+__device__ __forceinline__ Group make_group(const StreamArgs& a, int g, const GroupSrc& src) {
   constexpr unsigned esz = sizeof(S);
   Group G;
-  G.gather = 0; G.row0 = 0;
+  G.gather = 0; G.row0 = src.row0; G.m = src.m;
+  const S* blob = static_cast<const S*>(src.blob);
   if (MODE == kRouter) {
-    G.m = a.T; G.N = a.E; G.K = a.H; G.ldw = a.H;
+    G.N = a.E; G.K = a.H; G.ldw = a.H;
     G.w0 = a.Wg; G.b = a.x; G.out = a.logits;
     G.wbytes = (unsigned)a.E * a.H * esz; G.bbytes = (unsigned)a.T * a.H * esz;
     return G;
@@ -55,8 +97,6 @@ __device__ __forceinline__ Group resolve_group(const StreamArgs& a, int g) {
     int s = g, chunk = 0;
     if (MODE == kDown) { s = a.slab_shared[g]; chunk = a.slab_chunk[g]; }
     const int Is = a.shared_I[s];
-    const S* blob = static_cast<const S*>(a.shared_w[s]);
-    G.m = a.T;
     if (MODE == kGateUp) {
       G.N = Is; G.K = a.H; G.ldw = a.H;
       G.w0 = blob; G.b = a.x; G.out = a.h_shared[s];
@@ -71,12 +111,7 @@ __device__ __forceinline__ Group resolve_group(const StreamArgs& a, int g) {
     }
     return G;
   }
-  const int e = g - n_sh_groups;
-  const int b0 = clampi(a.offsets[e], 0, a.max_pairs);
-  const int b1 = clampi(a.offsets[e + 1], b0, a.max_pairs);
-  const S* blob = static_cast<const S*>(a.expert_w[e]);
-  G.m = blob ? min(b1 - b0, a.T) : 0;
-  G.row0 = b0;
+  const int b0 = src.row0;
   if (MODE == kGateUp) {
     G.N = a.I; G.K = a.H; G.ldw = a.H; G.gather = 1;
     G.w0 = blob; G.b = a.x;
@@ -92,6 +127,29 @@ __device__ __forceinline__ Group resolve_group(const StreamArgs& a, int g) {
   return G;
 }
 
+template <typename S, int MODE>
+__device__ __forceinline__ Group resolve_group(const StreamArgs& a, int g) {
+  return make_group<S, MODE>(a, g, load_group_src<MODE>(a, g));
+}
+
+// Host side: upper bound of the number of work items of one grouped GEMM (the device computes
+// the exact list); row_items rows per item, tok tokens per item.
+inline long item_upper_bound(StreamMode mode, const StreamArgs& a, int tok) {
+  auto row_items = [](int n, int per) { return (long)((n + per - 1) / per); };
+  const long tg_all = (a.T + tok - 1) / tok;
+  if (mode == kRouter) return row_items(a.E, 32) * ((a.T + 15) / 16);
+  const int per = (mode == kGateUp) ? 16 : 32;
+  long items = 0;
+  // a routed expert holds at most T pairs, and all experts together at most T*k_big
+  const long routed_rows = row_items(mode == kGateUp ? a.I : a.H, per);
+  const long pairs_blocks = (a.max_pairs + tok - 1) / tok + a.n_routed;
+  items += a.n_routed ? routed_rows * (pairs_blocks < a.n_routed * tg_all ? pairs_blocks : a.n_routed * tg_all) : 0;
+  if (mode == kGateUp)
+    for (int sidx = 0; sidx < a.n_shared; ++sidx) items += row_items(a.shared_I[sidx], per) * tg_all;
+  else
+    items += (long)a.n_slabs * row_items(a.H, per) * tg_all;
+  return items;
+}
 
 }  // namespace
 }  // namespace mm

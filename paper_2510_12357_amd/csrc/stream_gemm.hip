@@ -56,6 +56,7 @@ constexpr int kNT = MOE_STREAM_NT; // token tiles (16 tokens each) per work item
 struct BF16 {
   typedef uint16_t storage;
   typedef bf16x8 frag;                       // 8 consecutive k
+  static constexpr int kWavesPerSimd = 3;        // register budget: three workgroups per CU
   static constexpr int kDepth1 = MOE_STREAM_D1;  // k-steps in flight with 1 token tile
   static constexpr int kDepth4 = MOE_STREAM_D4;  // ... with up to 4 token tiles
   static __device__ __forceinline__ frag load(__amdgpu_buffer_rsrc_t r, unsigned off) {
@@ -75,6 +76,7 @@ struct BF16 {
 struct FP32 {
   typedef float storage;
   struct frag { f32x4 lo, hi; };             // 8 consecutive k
+  static constexpr int kWavesPerSimd = 2;
   static constexpr int kDepth1 = 4;
   static constexpr int kDepth4 = 2;
   static __device__ __forceinline__ frag load(__amdgpu_buffer_rsrc_t r, unsigned off) {
@@ -105,47 +107,93 @@ __device__ __forceinline__ int rows_per_item() { return MODE == kGateUp ? 16 : 1
 template <int MODE>
 __device__ __forceinline__ int tokens_per_item() { return MODE == kRouter ? 16 : 16 * kNT; }
 
-// K loop of one work item for one wave: k-steps ks = wave, wave + NW, ...  (32 k each).
-// aoff / boff: byte offsets of this lane's rows at k = 0 (kOob for rows that do not exist).
-template <typename ET, int NTI, int DEPTH, int NW>
-__device__ __forceinline__ void k_loop(f32x4 (&acc)[kRT][kNT], __amdgpu_buffer_rsrc_t ra_rsrc,
-                                       __amdgpu_buffer_rsrc_t rb_rsrc, const unsigned (&aoff)[kRT],
-                                       const unsigned (&boff)[kNT], int K, int wave, int q) {
-  typedef typename ET::frag Frag;
+// What a wave needs of a work item to run its K loop.
+struct Operands {
+  const void* w; const void* b;       // buffers of the weight rows / token rows
+  unsigned wbytes, bbytes;
+  unsigned aoff[kRT], boff[kNT];      // byte offsets of this lane's rows at k = 0 (kOob: no such row);
+                                      // boff[1..] only for the k loop with several token tiles
+  int K;
+};
+
+// The ring of k-steps in flight is one pool of fragments, laid out per k-loop shape: entry d
+// holds kRT weight fragments and NTI token fragments.  One pool serves both shapes, so that the
+// ring that persists across items and the ring of the many-token items share registers.
+template <int NTI, int DEPTH>
+struct RingLayout {
+  static constexpr int kSize = DEPTH * (kRT + NTI);
+  static __device__ __forceinline__ constexpr int a(int d, int rt) { return d * kRT + rt; }
+  static __device__ __forceinline__ constexpr int b(int d, int nt) { return DEPTH * kRT + d * NTI + nt; }
+};
+
+// Loads of k-step (wave + step * NW) of an item into ring entry d.
+template <typename ET, int NTI, int DEPTH, int NW, typename POOL>
+__device__ __forceinline__ void fill_step(POOL& pool, int d, const Operands& o, __amdgpu_buffer_rsrc_t ra_rsrc,
+                                          __amdgpu_buffer_rsrc_t rb_rsrc, int step, int wave, int q) {
+  typedef RingLayout<NTI, DEPTH> L;
   constexpr unsigned esz = sizeof(typename ET::storage);
-  Frag ra[DEPTH][kRT], rb[DEPTH][NTI];
-  const int nks = (K + 31) >> 5;
+  const int k0 = (wave + step * NW) * 32 + q * 8;
+  const bool kval = k0 < o.K;
+  const unsigned koff = (unsigned)k0 * esz;                 // kOob + koff stays out of range
+#pragma unroll
+  for (int rt = 0; rt < kRT; ++rt) pool[L::a(d, rt)] = ET::load(ra_rsrc, kval ? o.aoff[rt] + koff : kOob);
+#pragma unroll
+  for (int nt = 0; nt < NTI; ++nt) pool[L::b(d, nt)] = ET::load(rb_rsrc, kval ? o.boff[nt] + koff : kOob);
+}
+
+// K loop of one work item for one wave: k-steps ks = wave, wave + NW, ...  (32 k each).
+// The ring (ra, rb) lives outside: when `primed`, it already holds the first DEPTH k-steps of this
+// item, loaded while the previous item was finishing; when `chain`, the last DEPTH refills fetch
+// the first k-steps of the next item instead of nothing, so that the loads never pause at an
+// item boundary (epilogue, reduction and item set-up run under them).
+template <typename ET, int NTI, int DEPTH, int NW, typename POOL>
+__device__ __forceinline__ void k_loop(f32x4 (&acc)[kRT][kNT], POOL& pool, const Operands& cur,
+                                       const Operands& nxt, bool primed, bool chain, int wave, int q) {
+  typedef RingLayout<NTI, DEPTH> L;
+  const __amdgpu_buffer_rsrc_t ca = make_rsrc(cur.w, cur.wbytes), cb = make_rsrc(cur.b, cur.bbytes);
+  const int nks = (cur.K + 31) >> 5;
   const int nsteps = (nks + NW - 1) / NW;                   // same for every wave of the workgroup
-  auto fill = [&](int d, int step) {
-    const int k0 = (wave + step * NW) * 32 + q * 8;
-    const bool kval = k0 < K;
-    const unsigned koff = (unsigned)k0 * esz;               // kOob + koff stays out of range
+  if (!primed) {
 #pragma unroll
-    for (int rt = 0; rt < kRT; ++rt) ra[d][rt] = ET::load(ra_rsrc, kval ? aoff[rt] + koff : kOob);
+    for (int d = 0; d < DEPTH; ++d) fill_step<ET, NTI, DEPTH, NW>(pool, d, cur, ca, cb, d, wave, q);
+  }
+  auto consume = [&](int d) {
 #pragma unroll
-    for (int nt = 0; nt < NTI; ++nt) rb[d][nt] = ET::load(rb_rsrc, kval ? boff[nt] + koff : kOob);
+    for (int nt = 0; nt < NTI; ++nt)
+#pragma unroll
+      for (int rt = 0; rt < kRT; ++rt) acc[rt][nt] = ET::mma(pool[L::a(d, rt)], pool[L::b(d, nt)], acc[rt][nt]);
   };
-#pragma unroll
-  for (int d = 0; d < DEPTH; ++d) fill(d, d);
-  for (int i = 0; i < nsteps; i += DEPTH) {
+  int i = 0;
+  for (; i + DEPTH < nsteps; i += DEPTH) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-#pragma unroll
-      for (int nt = 0; nt < NTI; ++nt)
-#pragma unroll
-        for (int rt = 0; rt < kRT; ++rt) acc[rt][nt] = ET::mma(ra[d][rt], rb[d][nt], acc[rt][nt]);
-      fill(d, i + d + DEPTH);                               // k-steps past the end fetch nothing
+      consume(d);
+      fill_step<ET, NTI, DEPTH, NW>(pool, d, cur, ca, cb, i + d + DEPTH, wave, q);   // k-steps past the end fetch nothing
       // keep the per-step order (consume oldest, refill it): without this the scheduler hoists
       // all MFMAs above all loads and the ring degenerates into load-all / wait-all / compute-all
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  // last DEPTH k-steps of this item
+  if (chain) {
+    const __amdgpu_buffer_rsrc_t na = make_rsrc(nxt.w, nxt.wbytes), nb = make_rsrc(nxt.b, nxt.bbytes);
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      consume(d);
+      fill_step<ET, NTI, DEPTH, NW>(pool, d, nxt, na, nb, d, wave, q);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) consume(d);
+  }
 }
 
 // NW = waves of a workgroup that split the K dimension of one work item.
 template <typename ET, int MODE, int NW>
-__global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(ET::kWavesPerSimd, ET::kWavesPerSimd))) void stream_kernel(const StreamArgs a) {
   typedef typename ET::storage S;
+  typedef typename ET::frag Frag;
   constexpr int kThreads = NW * 64;
   constexpr unsigned esz = sizeof(S);
 
@@ -185,44 +233,80 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
   __syncthreads();
   const int total = s_prefix[n_groups];
 
-  // Workgroups stride over the list: at any time the resident workgroups read neighbouring
-  // row tiles, i.e. one window of a few dozen MB that sweeps through the weights (measured
-  // faster than giving each workgroup its own contiguous range).
-  for (int item = blockIdx.x; item < total; item += gridDim.x) {
+  // One work item, resolved for this lane.
+  struct Item {
+    int valid, g, r0, n0, ntn, K;
+    const void* w; const void* b;
+    unsigned wbytes, bbytes, aoff[kRT], boff0;
+  };
+  // byte offset of token row (r0 + nt * 16 + c16) of group G, kOob if this lane has no such row
+  auto token_offset = [&](const Group& G, int valid, int r0, int ntn, int nt) -> unsigned {
+    const int r = r0 + nt * 16 + c16;
+    const bool val = valid && nt < ntn && r < G.m;
+    int row = r;
+    if (G.gather) row = val ? clampi(a.sorted_token[G.row0 + r], 0, a.T - 1) : 0;
+    return val ? (unsigned)row * (unsigned)G.ldw * esz : kOob;
+  };
+  auto operands = [&](const Item& it) -> Operands {
+    Operands o;
+    o.w = it.w; o.b = it.b; o.wbytes = it.wbytes; o.bbytes = it.bbytes; o.K = it.K;
+#pragma unroll
+    for (int rt = 0; rt < kRT; ++rt) o.aoff[rt] = it.aoff[rt];
+    o.boff[0] = it.boff0;
+#pragma unroll
+    for (int nt = 1; nt < kNT; ++nt) o.boff[nt] = kOob;
+    return o;
+  };
+  auto decode = [&](int item) -> Item {
+    Item it;
+    it.valid = item < total;
     // group of this item: largest g with prefix[g] <= item < prefix[g+1]
     int lo = 0, hi = n_groups;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
       if (s_prefix[mid] <= item) lo = mid; else hi = mid;
     }
-    const int g = lo;
-    const Group G = s_group[g];
-    const int local = item - s_prefix[g];
-    const int tgs = (G.m + tokens_per_item<MODE>() - 1) / tokens_per_item<MODE>();
+    it.g = uniform(it.valid ? lo : 0);
+    Group G = s_group[it.g];
+    G.m = uniform(G.m); G.N = uniform(G.N); G.K = uniform(G.K); G.ldw = uniform(G.ldw); G.row0 = uniform(G.row0);
+    G.gather = uniform(G.gather); G.wbytes = uniform(G.wbytes); G.bbytes = uniform(G.bbytes);
+    G.w0 = uniform(G.w0); G.b = uniform(G.b);
+    const int local = item - uniform(s_prefix[it.g]);
+    const int tgs = max(1, (G.m + tokens_per_item<MODE>() - 1) / tokens_per_item<MODE>());
     const int row_item = local / tgs;
-    const int r0 = (local - row_item * tgs) * tokens_per_item<MODE>();
-    const int n0 = row_item * rows_per_item<MODE>();
-    const int ntn = (MODE == kRouter) ? 1 : min(kNT, (G.m - r0 + 15) >> 4);   // token tiles in use (wave-uniform)
-
-    // ---- operand buffers and this lane's row offsets ----
-    const __amdgpu_buffer_rsrc_t ra_rsrc = make_rsrc(G.w0, G.wbytes);
-    const __amdgpu_buffer_rsrc_t rb_rsrc = make_rsrc(G.b, G.bbytes);
-    unsigned aoff[kRT], boff[kNT];
+    it.r0 = (local - row_item * tgs) * tokens_per_item<MODE>();
+    it.n0 = row_item * rows_per_item<MODE>();
+    it.ntn = (MODE == kRouter) ? 1 : clampi((G.m - it.r0 + 15) >> 4, 1, kNT);   // token tiles in use (wave-uniform)
+    // an item past the end of the list keeps valid pointers and empty buffers
+    it.w = it.valid ? G.w0 : a.x; it.b = it.valid ? G.b : a.x;
+    it.wbytes = it.valid ? G.wbytes : 0u; it.bbytes = it.valid ? G.bbytes : 0u;
+    it.K = it.valid ? G.K : 0;
 #pragma unroll
     for (int rt = 0; rt < kRT; ++rt) {
-      const int n = (MODE == kGateUp) ? n0 + c16 : n0 + rt * 16 + c16;
+      const int n = (MODE == kGateUp) ? it.n0 + c16 : it.n0 + rt * 16 + c16;
       unsigned off = (unsigned)n * (unsigned)G.ldw * esz;
       if (MODE == kGateUp && rt == 1) off += (unsigned)G.N * (unsigned)G.ldw * esz;   // W_up follows W_gate
-      aoff[rt] = n < G.N ? off : kOob;
+      it.aoff[rt] = (it.valid && n < G.N) ? off : kOob;
     }
-#pragma unroll
-    for (int nt = 0; nt < kNT; ++nt) {
-      const int r = r0 + nt * 16 + c16;
-      const bool val = nt < ntn && r < G.m;
-      int row = r;
-      if (G.gather) row = val ? clampi(a.sorted_token[G.row0 + r], 0, a.T - 1) : 0;
-      boff[nt] = val ? (unsigned)row * (unsigned)G.ldw * esz : kOob;
-    }
+    it.boff0 = token_offset(G, it.valid, it.r0, it.ntn, 0);
+    return it;
+  };
+
+  // the ring; for items with one token tile it persists across items (see k_loop)
+  constexpr int kPool1 = RingLayout<1, ET::kDepth1>::kSize, kPool4 = RingLayout<kNT, ET::kDepth4>::kSize;
+  Frag pool[kPool1 > kPool4 ? kPool1 : kPool4];
+  bool primed = false;
+
+  // Workgroups stride over the list: at any time the resident workgroups read neighbouring
+  // row tiles, i.e. one window of a few dozen MB that sweeps through the weights (measured
+  // faster than giving each workgroup its own contiguous range).
+  Item cur = decode(blockIdx.x);
+  for (int item = blockIdx.x; item < total; item += gridDim.x) {
+    const Item nxt = decode(item + gridDim.x);
+    Group G = s_group[cur.g];
+    G.m = uniform(G.m); G.N = uniform(G.N); G.ldw = uniform(G.ldw); G.row0 = uniform(G.row0);
+    G.gather = uniform(G.gather); G.out = uniform(G.out);
+    const int r0 = cur.r0, n0 = cur.n0, ntn = cur.ntn;
 
     f32x4 acc[kRT][kNT];
 #pragma unroll
@@ -230,8 +314,17 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
 #pragma unroll
       for (int nt = 0; nt < kNT; ++nt) acc[rt][nt] = f32x4{0, 0, 0, 0};
 
-    if (ntn == 1 || kNT == 1) k_loop<ET, 1, ET::kDepth1, NW>(acc, ra_rsrc, rb_rsrc, aoff, boff, G.K, wave, q);
-    else                      k_loop<ET, kNT, ET::kDepth4, NW>(acc, ra_rsrc, rb_rsrc, aoff, boff, G.K, wave, q);
+    if (ntn == 1 || kNT == 1) {
+      const bool chain = nxt.valid && (nxt.ntn == 1 || kNT == 1);
+      k_loop<ET, 1, ET::kDepth1, NW>(acc, pool, operands(cur), operands(nxt), primed, chain, wave, q);
+      primed = chain;
+    } else {
+      Operands o = operands(cur);
+#pragma unroll
+      for (int nt = 1; nt < kNT; ++nt) o.boff[nt] = token_offset(G, 1, r0, ntn, nt);
+      k_loop<ET, kNT, ET::kDepth4, NW>(acc, pool, o, o, false, false, wave, q);
+      primed = false;
+    }
 
     // ---- reduce the K split through LDS ----
 #pragma unroll
@@ -289,29 +382,14 @@ __global__ __launch_bounds__(NW * 64) void stream_kernel(const StreamArgs a) {
       }
     }
     __syncthreads();
+    cur = nxt;
   }
 }
 
 template <typename ET, int MODE, int NW>
 int launch_typed(const StreamArgs& a, hipStream_t s) {
   constexpr int kThreads = NW * 64;
-  // upper bound of the item count (the device computes the exact list)
-  const long tg_all = (a.T + 16 * kNT - 1) / (16 * kNT);
-  long items = 0;
-  auto row_items = [](int n, int per) { return (long)((n + per - 1) / per); };
-  if (MODE == kRouter) {
-    items = row_items(a.E, 32) * ((a.T + 15) / 16);
-  } else {
-    const int per = (MODE == kGateUp) ? 16 : 32;
-    // a routed expert holds at most T pairs, and all experts together at most T*k_big
-    const long routed_rows = row_items(MODE == kGateUp ? a.I : a.H, per);
-    const long pairs_blocks = (a.max_pairs + 16 * kNT - 1) / (16 * kNT) + a.n_routed;
-    items += a.n_routed ? routed_rows * (pairs_blocks < a.n_routed * tg_all ? pairs_blocks : a.n_routed * tg_all) : 0;
-    if (MODE == kGateUp)
-      for (int sidx = 0; sidx < a.n_shared; ++sidx) items += row_items(a.shared_I[sidx], per) * tg_all;
-    else
-      items += (long)a.n_slabs * row_items(a.H, per) * tg_all;
-  }
+  const long items = item_upper_bound((StreamMode)MODE, a, MODE == kRouter ? 16 : 16 * kNT);
   if (items <= 0) return MOE_OK;
   // persistent workgroups: exactly as many as are resident at once, so that the static striding
   // over the item list never leaves a second, partially filled round of workgroups
