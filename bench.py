@@ -262,7 +262,7 @@ def main():
         ach = work["gate_up_bytes"] / (gu["avg_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
                         traffic=stored_traffic(args.workload))
-    roofline["kernel"] = "stream_kernel<BF16,kGateUp> (ffn_gate_up)"
+    roofline["kernel"] = ("tiled_kernel<kGateUp>" if cfg.T >= 256 else "stream_lds_kernel<kGateUp>") + " (ffn_gate_up)"
     roofline["avg_us"] = gu["avg_us"]
     roofline["algorithmic_bytes"] = work["gate_up_bytes"]
 

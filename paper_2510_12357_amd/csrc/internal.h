@@ -74,6 +74,8 @@ struct StreamArgs {
 };
 
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s);
+// bf16 kGateUp / kDown with the weights streamed through an LDS ring (stream_lds.hip)
+int launch_stream_lds(StreamMode mode, const StreamArgs& a, hipStream_t s);
 
 // ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime, bf16) -------------------------
 int launch_tiled(StreamMode mode, const StreamArgs& a, hipStream_t s);

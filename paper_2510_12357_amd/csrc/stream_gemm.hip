@@ -409,6 +409,11 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
 }  // namespace
 
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s) {
+  if (dtype == MOE_BF16 && mode != kRouter) {
+    static int use_lds = -1;
+    if (use_lds < 0) { const char* env = getenv("MOE_STREAM_LDS"); use_lds = env ? atoi(env) : 1; }
+    if (use_lds) return launch_stream_lds(mode, a, s);
+  }
   if (dtype == MOE_BF16) {
     switch (mode) {
       case kRouter: return launch_typed<BF16, kRouter, 4>(a, s);

@@ -1,0 +1,415 @@
+// Skinny grouped GEMM for the decode regime with the weights streamed from HBM directly into
+// LDS (bf16 only; same operation, groups and work items as stream_gemm.hip).
+//
+//   kGateUp  h = silu(W_gate x) * (W_up x)     (execution stage of Sec. II-A, SwiGLU)
+//   kDown    y = W_down h
+//
+// Why: a kernel that loads the weights straight into registers (MFMA "A" operand layout) touches
+// 16 rows x 64 bytes per load instruction and is limited, by its registers, in the bytes it
+// keeps in flight.  Here a load instruction moves two rows x 512 contiguous bytes into LDS
+// without passing through registers, and a workgroup keeps a 64 KB ring (4 stages) in flight.
+//
+// A workgroup has two kinds of waves:
+//   * waves 0..3, loaders: issue the global->LDS loads of the weight chunks and nothing else.  A
+//     work item is 32 weight rows (16 gate + 16 up rows, or 32 down rows) x all of K for up to 32
+//     token rows, cut into chunks of 256 k; one chunk = 32 rows x 512 B = one 16 KB stage = 4 load
+//     instructions per loader.  The chunks of all items of the workgroup form one stream, so the
+//     ring never drains at an item boundary.  A loader issues exactly 4 loads per iteration (a
+//     slot without a chunk issues 4 loads with out-of-range offsets, which the hardware turns
+//     into zero fills without memory traffic), so its hand-counted s_waitcnt vmcnt(12) means:
+//     the chunk issued three iterations ago has landed.  It decodes its next item while its
+//     loads fly.
+//   * waves 4..7, computers: read MFMA fragments from the stage that landed, load the token rows
+//     (MFMA "B" operand, from L2) one chunk ahead into registers with ordinary loads (issued
+//     right behind the MFMAs, so that they arrive during the barrier waits), run the
+//     MFMAs, reduce the K split through LDS, apply the epilogue (SwiGLU) and store.  Computer c
+//     owns token tile c & 1 (16 token rows) and the k-steps of parity c >> 1.
+//   * Two workgroup barriers per iteration: "landed" (the chunk issued three iterations ago is in
+//     LDS for every wave) and "free" (the stage just consumed may be refilled; partial sums of an
+//     item that ended are complete).  Loaders and computers execute the same number of iterations: the number of
+//     chunks of the workgroup's items, which both derive from blockIdx and the item table, plus
+//     the three iterations that the computers lag behind.
+//   * Inside a stage, the 16-byte column c of row r sits at column c ^ (r & 15): the
+//     ds_read_b128 of a fragment (16 rows x the same logical column) is bank-conflict free.
+//   * Groups with more than 32 token rows become several items that read the same weights; the
+//     item order places them 8 items apart, i.e. on workgroups of the same XCD at the same time,
+//     so that the repeats hit in that XCD's L2.
+#include <stdio.h>
+#include <stdlib.h>
+
+#include <type_traits>
+
+#include "internal.h"
+#include "groups.h"
+
+namespace mm {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((address_space(3))) void lds_void;
+
+constexpr int kKC = 256;                     // k per chunk
+constexpr int kRowBytes = kKC * 2;           // 512 B of one weight row per chunk
+constexpr int kRows = 32;                    // weight rows per item
+constexpr int kStageBytes = kRows * kRowBytes;
+constexpr int kStages = 4;
+constexpr int kWorkers = 4;                  // loader waves = computer waves
+constexpr int kThreadsL = 2 * kWorkers * 64;
+constexpr int kTok = 32;                     // token rows per item, at most (two tiles of 16)
+constexpr int kKParts = 2;                   // worker waves that split the k-steps of one token tile
+constexpr int kBLoads = kKC / 32 / kKParts;  // token-row loads per worker and chunk (k-steps of 32)
+
+// vmcnt(n): bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima (no wait)
+#define MM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
+
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also fences global memory,
+// which makes the compiler wait for every outstanding load, i.e. it would drain the ring.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ unsigned uni(unsigned v) { return (unsigned)__builtin_amdgcn_readfirstlane((int)v); }
+template <typename P>
+__device__ __forceinline__ P* uni(P* p) {
+  const uint64_t v = (uint64_t)p;
+  const uint64_t lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)v);
+  const uint64_t hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(v >> 32));
+  return (P*)((hi << 32) | lo);
+}
+
+struct Item {
+  // ---- same value in all lanes of the workgroup ----
+  int valid;
+  int nch;          // chunks
+  int K, N, m;
+  int r0, n0;       // first token row / first weight row of the item
+  int ntn;          // token tiles in use (1..2)
+  int gather, row0;
+  unsigned ldwb;    // bytes between rows of W and of B
+  unsigned wbytes, bbytes;
+  const void* w0;
+  const void* b;
+  void* out;
+  // ---- per lane ----
+  unsigned a_row[4];    // loaders: byte offset of the weight row behind each of the wave's 4 load instructions
+  unsigned boff;        // computers: byte offset of this lane's token row (kOob: none)
+};
+
+template <int MODE>
+__device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int total, int n_groups,
+                                            const int* s_prefix, const GroupSrc* s_src, int wave, int lane) {
+  Item it;
+  const int item = blockIdx.x + j * gridDim.x;
+  it.valid = item < total;
+  // group of the item = number of prefix entries 1..n_groups that are <= item (the prefix is
+  // nondecreasing); every lane counts a slice, the wave adds up
+  const int C = (n_groups + 63) / 64;
+  int cnt = 0;
+  for (int c = 0; c < C; ++c) {
+    const int g = lane * C + c + 1;
+    if (g <= n_groups && s_prefix[g] <= item) ++cnt;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
+  const int g = it.valid ? __builtin_amdgcn_readfirstlane(cnt) : 0;
+  GroupSrc src = s_src[g];
+  src.m = uni(src.m); src.row0 = uni(src.row0); src.blob = uni(src.blob);
+  const Group G = make_group<uint16_t, MODE>(a, g, src);
+  // Items of a group, in blocks of 8 row tiles: all token blocks of row tile (8 b + i) are
+  // 8 items apart, i.e. they run at the same time on workgroups of the same XCD.
+  const int local = item - uni(s_prefix[g]);
+  const int per = MODE == kGateUp ? 16 : 32;
+  const int rows = (G.N + per - 1) / per;
+  const int tgs = max(1, (G.m + kTok - 1) / kTok);
+  int tg = 0, row_item = local;     // one token block (the usual case at decode): nothing to divide
+  if (tgs > 1) {
+    const int block = local / (8 * tgs);
+    const int rem = local - block * 8 * tgs;
+    const int nb = max(1, min(8, rows - 8 * block));
+    tg = rem / nb;
+    row_item = block * 8 + (rem - tg * nb);
+  }
+  it.r0 = tg * kTok;
+  it.n0 = row_item * per;
+  it.K = it.valid ? G.K : 0;
+  it.N = G.N; it.m = it.valid ? G.m : 0;
+  it.nch = (it.K + kKC - 1) / kKC;
+  it.ntn = clampi((it.m - it.r0 + 15) >> 4, 1, kTok / 16);
+  it.gather = G.gather; it.row0 = G.row0;
+  it.ldwb = (unsigned)G.ldw * 2u;
+  // an item that does not exist keeps valid pointers and empty buffers: every load is out of range
+  it.wbytes = it.valid ? G.wbytes : 0u; it.bbytes = it.valid ? G.bbytes : 0u;
+  it.w0 = it.valid ? G.w0 : a.x; it.b = it.valid ? G.b : a.x; it.out = G.out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row_local = 2 * ((wave % kWorkers) * 4 + i) + (lane >> 5);
+    unsigned off;
+    int n;
+    if (MODE == kGateUp) {
+      n = it.n0 + (row_local & 15);
+      off = (unsigned)n * it.ldwb + ((row_local >> 4) ? (unsigned)G.N * it.ldwb : 0u);   // W_up follows W_gate
+    } else {
+      n = it.n0 + row_local;
+      off = (unsigned)n * it.ldwb;
+    }
+    it.a_row[i] = (it.valid && n < G.N) ? off : kOob;
+  }
+  {
+    const int r = it.r0 + (wave & 1) * 16 + (lane & 15);
+    const bool val = it.valid && r < it.m;
+    int row = r;
+    if (it.gather) row = val ? clampi(a.sorted_token[it.row0 + r], 0, a.T - 1) : 0;
+    it.boff = val ? (unsigned)row * it.ldwb : kOob;
+  }
+  return it;
+}
+
+
+struct Smem {
+  char ring[kStages * kStageBytes];
+  float red[kWorkers][2][4][64];       // K-split partial sums; the item counts during set-up
+  GroupSrc src[kMaxGroups];
+  int prefix[kMaxGroups + 1];
+};
+
+template <int MODE>
+__global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4))) void stream_lds_kernel(const StreamArgs a) {
+  // One LDS object with the ring first: the ring starts at LDS address 0 and ends below 64 KB,
+  // so the base that a load-to-LDS instruction takes from M0 stays within 16 bits.
+  __shared__ __attribute__((aligned(1024))) Smem sm;
+  char* const s_ring = sm.ring;
+  float (&s_red)[kWorkers][2][4][64] = sm.red;
+  GroupSrc* const s_src = sm.src;
+  int* const s_prefix = sm.prefix;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
+  const int q = lane >> 4, c16 = lane & 15;
+  const int n_groups = a.n_routed + (MODE == kDown ? a.n_slabs : a.n_shared);
+  int* s_cnt = reinterpret_cast<int*>(&s_red[0][0][0][0]);           // kMaxGroups ints fit easily
+
+  // ---- group table and item list ----
+  for (int g = tid; g < n_groups; g += kThreadsL) {
+    const GroupSrc src = load_group_src<MODE>(a, g);
+    const Group G = make_group<uint16_t, MODE>(a, g, src);
+    const int rows = (G.N + (MODE == kGateUp ? 16 : 32) - 1) / (MODE == kGateUp ? 16 : 32);
+    const int tgs = (G.m + kTok - 1) / kTok;
+    s_src[g] = src;
+    s_cnt[g] = rows * tgs;
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int C = (n_groups + 63) / 64;
+    const int base = lane * C;
+    int sum = 0;
+    for (int c = 0; c < C; ++c) if (base + c < n_groups) sum += s_cnt[base + c];
+    int incl = sum;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_up(incl, d);
+      if (lane >= d) incl += v;
+    }
+    int run = incl - sum;
+    if (lane == 0) s_prefix[0] = 0;
+    for (int c = 0; c < C; ++c) if (base + c < n_groups) { run += s_cnt[base + c]; s_prefix[base + c + 1] = run; }
+  }
+  __syncthreads();
+  const int total = s_prefix[n_groups];
+  __syncthreads();                  // s_cnt (aliases the partial sums) is dead from here on
+
+  if (wave < kWorkers) {
+    // =================================== loader ===================================
+    Item it = decode_item<MODE>(a, 0, total, n_groups, s_prefix, s_src, wave, lane);
+    Item nx = it;
+    int j = 0, k = 0, drain = 0, s = 0;
+    unsigned a_col[4], addr[4];     // logical 16-byte column per load instruction; running offsets
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row_local = 2 * (wave * 4 + i) + (lane >> 5);
+      a_col[i] = (unsigned)((lane & 31) ^ (row_local & 15));
+      addr[i] = it.a_row[i] + a_col[i] * 16u;               // kOob + small stays out of range
+    }
+    __amdgpu_buffer_rsrc_t rs = make_rsrc(it.w0, it.wbytes);
+    MM_WAIT_VMCNT(0);
+    for (;;) {
+      const bool real = k < it.nch;                         // an item that does not exist has no chunks
+      char* stage = s_ring + (s & (kStages - 1)) * kStageBytes + wave * 4096;
+      if (real && (k + 1) * kKC <= it.K) {                  // whole chunk inside K
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16, (int)addr[i], 0, 0, 0);
+      } else {
+        // last, partial chunk, or no chunk: lanes out of range fill their part of the stage with zeros
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int kk = k * kKC + (int)a_col[i] * 8;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16,
+                                                   (int)((real && kk < it.K) ? addr[i] : kOob), 0, 0, 0);
+        }
+      }
+      if (real) {
+        ++k;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) addr[i] += kRowBytes;
+        if (k == 1) nx = decode_item<MODE>(a, j + 1, total, n_groups, s_prefix, s_src, wave, lane);   // under the loads
+        if (k == it.nch) {
+          it = nx; ++j; k = 0;
+          rs = make_rsrc(it.w0, it.wbytes);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) addr[i] = it.a_row[i] + a_col[i] * 16u;
+        }
+      }
+      MM_WAIT_VMCNT(12);                                    // the chunk issued three iterations ago has landed
+      lds_barrier();                                        // "landed"
+      lds_barrier();                                        // "free": stage (s + 1) & 3 was consumed
+      ++s;
+      if (!real && ++drain == 3) break;                     // the computers lag three iterations
+    }
+    MM_WAIT_VMCNT(0);
+    return;
+  }
+
+  // =================================== computer ===================================
+  const int c = wave - kWorkers, tw = c & 1, kp = c >> 1;
+  Item cur = decode_item<MODE>(a, 0, total, n_groups, s_prefix, s_src, c, lane);
+  Item nx = decode_item<MODE>(a, 1, total, n_groups, s_prefix, s_src, c, lane);
+  int j = 0, k = 0;                 // item ordinal and chunk being consumed
+  int pending = 0;                  // the previous item's partial sums wait for their epilogue
+  int f_r0 = 0, f_n0 = 0, f_m = 0, f_N = 0, f_ntn = 0;
+  void* f_out = nullptr;
+  const unsigned ring_base = (unsigned)(size_t)s_ring;
+  const unsigned b_lane = (unsigned)(kp * 64 + q * 16);     // this lane's bytes into a chunk of a token row
+  unsigned rd_off[kBLoads];         // LDS offsets of this lane's fragments inside a stage (row tile 0)
+#pragma unroll
+  for (int t = 0; t < kBLoads; ++t)
+    rd_off[t] = ring_base + (unsigned)c16 * kRowBytes + (unsigned)((((kp + t * kKParts) * 4 + q) ^ c16) * 16);
+  i32x4 bbuf[kBLoads];
+#pragma unroll
+  for (int t = 0; t < kBLoads; ++t) bbuf[t] = i32x4{0, 0, 0, 0};
+  f32x4 acc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
+
+  auto epilogue = [&]() {
+    // computers 0 and 1 finish token tiles 0 and 1: add the two k parts, activate, store
+    if (kp == 0 && tw < f_ntn) {
+      float val[2][4];
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) val[rt][v] = s_red[tw][rt][v][lane] + s_red[tw + 2][rt][v][lane];
+      const int r = f_r0 + tw * 16 + c16;
+      if (r < f_m) {
+        if (MODE == kGateUp) {
+          const int i = f_n0 + 4 * q;
+          if (i < f_N) {
+            float hv[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const float gte = val[0][v];
+              hv[v] = gte / (1.f + __expf(-gte)) * val[1][v];
+            }
+            bf16x4 o = {(__bf16)hv[0], (__bf16)hv[1], (__bf16)hv[2], (__bf16)hv[3]};
+            *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(f_out) + (size_t)r * f_N + i) = o;
+          }
+        } else {
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt) {
+            const int col = f_n0 + rt * 16 + 4 * q;
+            if (col < f_N)
+              *reinterpret_cast<f32x4*>(static_cast<float*>(f_out) + (size_t)r * a.H + col) =
+                  f32x4{val[rt][0], val[rt][1], val[rt][2], val[rt][3]};
+          }
+        }
+      }
+    }
+  };
+
+  // One iteration.
+  auto step = [&](int s) -> bool {
+    lds_barrier();                                          // "landed": the chunk issued three iterations ago
+    if (s >= 3 && cur.valid) {
+      if (tw < cur.ntn) {
+        const unsigned st = (unsigned)(((s + 1) & (kStages - 1)) * kStageBytes);
+#pragma unroll
+        for (int p = 0; p < kBLoads / 2; ++p) {
+          bf16x8 f00, f10, f01, f11;                         // row tile 0 / 1 of two k-steps
+          asm volatile(
+              "ds_read_b128 %0, %4\n ds_read_b128 %1, %4 offset:8192\n"
+              "ds_read_b128 %2, %5\n ds_read_b128 %3, %5 offset:8192\n"
+              "s_waitcnt lgkmcnt(0)"
+              : "=&v"(f00), "=&v"(f10), "=&v"(f01), "=&v"(f11)
+              : "v"(rd_off[2 * p] + st), "v"(rd_off[2 * p + 1] + st)
+              : "memory");
+          const bf16x8 b0 = __builtin_bit_cast(bf16x8, bbuf[2 * p]);
+          const bf16x8 b1 = __builtin_bit_cast(bf16x8, bbuf[2 * p + 1]);
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f00, b0, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f10, b0, acc[1], 0, 0, 0);
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f01, b1, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f11, b1, acc[1], 0, 0, 0);
+        }
+      }
+      if (++k == cur.nch) {         // item done: hand the partial sums over, move on
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) s_red[c][rt][v][lane] = acc[rt][v];
+        acc[0] = f32x4{0, 0, 0, 0}; acc[1] = f32x4{0, 0, 0, 0};
+        f_r0 = cur.r0; f_n0 = cur.n0; f_m = cur.m; f_N = cur.N; f_ntn = cur.ntn; f_out = cur.out;
+        pending = 1;
+        cur = nx; ++j; k = 0;
+        nx = decode_item<MODE>(a, j + 1, total, n_groups, s_prefix, s_src, c, lane);
+      }
+    }
+    // Token rows of the chunk consumed in the next iteration: issued here, behind the MFMAs that
+    // read the previous ones, they arrive while this wave waits at the two barriers.
+    if (s >= 2) {                   // that chunk is (cur, k): the one after the chunk just consumed
+      // Nothing of this wave is in flight any more (the previous token rows were consumed or
+      // belong to a tile this wave skips).  Saying so keeps the compiler from guarding every one
+      // of the loads below against a load of the previous iteration into the same registers.
+      MM_WAIT_VMCNT(0);
+      const __amdgpu_buffer_rsrc_t rb = make_rsrc(cur.b, cur.bbytes);
+#pragma unroll
+      for (int t = 0; t < kBLoads; ++t) {
+        const int kk = k * kKC + (kp + t * kKParts) * 32 + q * 8;
+        const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
+        bbuf[t] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
+      }
+    }
+    lds_barrier();                                          // "free"; partial sums of an item that ended are complete
+    if (pending) { pending = 0; epilogue(); }
+    return cur.valid || s < 2;
+  };
+
+  for (int s = 0; step(s); ++s) {}
+}
+
+template <int MODE>
+int launch_lds_typed(const StreamArgs& a, hipStream_t s) {
+  const long items = item_upper_bound((StreamMode)MODE, a, kTok);
+  if (items <= 0) return MOE_OK;
+  // persistent workgroups: exactly as many as are resident at once
+  static int per_cu = 0;
+  if (per_cu == 0) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, stream_lds_kernel<MODE>, kThreadsL, 0) != hipSuccess || n < 1) n = 1;
+    if (const char* env = getenv("MOE_STREAM_WG_PER_CU")) { const int v = atoi(env); if (v > 0) n = v; }
+    per_cu = n;
+  }
+  long grid = (long)device_cu_count() * per_cu;
+  if (grid > items) grid = items;
+  hipLaunchKernelGGL((stream_lds_kernel<MODE>), dim3((unsigned)grid), dim3(kThreadsL), 0, s, a);
+  return hip_fail(hipGetLastError(), "stream_lds_kernel launch");
+}
+
+}  // namespace
+
+int launch_stream_lds(StreamMode mode, const StreamArgs& a, hipStream_t s) {
+  switch (mode) {
+    case kGateUp: return launch_lds_typed<kGateUp>(a, s);
+    case kDown: return launch_lds_typed<kDown>(a, s);
+    default: break;
+  }
+  return fail(MOE_E_BADARG, "bad stream mode");
+}
+
+}  // namespace mm
