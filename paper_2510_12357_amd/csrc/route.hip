@@ -126,19 +126,29 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void route_kernel(const float*
 }
 
 // ---- fused router for decode sizes ----------------------------------------------------------
-__device__ __forceinline__ void load8(const uint16_t* p, float (&f)[8]) {
-  const uint4 u = *reinterpret_cast<const uint4*>(p);
-  const unsigned w[4] = {u.x, u.y, u.z, u.w};
+// Eight consecutive elements as loaded (16 or 32 bytes), converted to fp32 on demand.
+template <typename S> struct Raw8;
+template <> struct Raw8<uint16_t> {
+  uint4 u;
+  __device__ __forceinline__ void load(const uint16_t* p) { u = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void get(float (&f)[8]) const {
+    const unsigned w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    f[2 * i] = __uint_as_float(w[i] << 16);            // bf16 -> fp32 is a 16-bit shift
-    f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    for (int i = 0; i < 4; ++i) {
+      f[2 * i] = __uint_as_float(w[i] << 16);            // bf16 -> fp32 is a 16-bit shift
+      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
   }
-}
-__device__ __forceinline__ void load8(const float* p, float (&f)[8]) {
-  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-  f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
-}
+};
+template <> struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = *reinterpret_cast<const float4*>(p); b = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void get(float (&f)[8]) const {
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+  }
+};
 
 // One wave per block of TE experts x TT tokens: the lanes split the hidden dimension, every
 // operand chunk is a 16/32-byte load, and the block's sums are reduced with shuffles.  Decode
@@ -162,18 +172,36 @@ __global__ __launch_bounds__(kGemvWaves * 64) void gate_gemv_kernel(const S* __r
 #pragma unroll
     for (int b = 0; b < TT; ++b) acc[a][b] = 0.f;
   const int nchunk = H >> 3;                           // 8 elements per chunk
-  for (int c = lane; c < nchunk; c += 64) {
-    float xv[TT][8];
+  // U chunks per trip with all loads issued before the first FMA: a lane has only H/512 chunks,
+  // so with one chunk per trip the kernel would be a chain of exposed load latencies.  The FMA
+  // order per accumulator (chunks ascending) is the same for every U.
+  constexpr int U = sizeof(S) == 2 ? 4 : 2;
+  for (int c0 = lane; c0 < nchunk; c0 += 64 * U) {
+    Raw8<S> xr[U][TT], wr[U][TE];
 #pragma unroll
-    for (int b = 0; b < TT; ++b) load8(x + (size_t)min(t0 + b, T - 1) * H + c * 8, xv[b]);
+    for (int u = 0; u < U; ++u) {
+      const int c = min(c0 + 64 * u, nchunk - 1);      // a chunk past the end is loaded again and skipped
 #pragma unroll
-    for (int a = 0; a < TE; ++a) {
-      float wv[8];
-      load8(Wg + (size_t)min(e0 + a, E - 1) * H + c * 8, wv);   // clamped rows are discarded below
+      for (int b = 0; b < TT; ++b) xr[u][b].load(x + (size_t)min(t0 + b, T - 1) * H + c * 8);
 #pragma unroll
-      for (int b = 0; b < TT; ++b)
+      for (int a = 0; a < TE; ++a) wr[u][a].load(Wg + (size_t)min(e0 + a, E - 1) * H + c * 8);   // clamped rows are discarded below
+    }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[a][b] = fmaf(xv[b][i], wv[i], acc[a][b]);
+    for (int u = 0; u < U; ++u) {
+      if (c0 + 64 * u < nchunk) {
+        float xv[TT][8];
+#pragma unroll
+        for (int b = 0; b < TT; ++b) xr[u][b].get(xv[b]);
+#pragma unroll
+        for (int a = 0; a < TE; ++a) {
+          float wv[8];
+          wr[u][a].get(wv);
+#pragma unroll
+          for (int b = 0; b < TT; ++b)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[a][b] = fmaf(xv[b][i], wv[i], acc[a][b]);
+        }
+      }
     }
   }
 #pragma unroll
