@@ -210,19 +210,15 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         if (kk + 1 < KK) read_frags(st, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-#ifndef MOE_TDBG_NOLOAD
         if (kk == 0) gload_a(set_ld, kt_ld);
         if (kk == 1 || KK == 1) gload_b(set_ld, kt_ld);
-#endif
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
-#ifndef MOE_TDBG_NOSTORE
         if (kk == KK - 2 || KK == 1) lstore_a(set_st, st ^ 1);
         if (kk == KK - 1) lstore_b(set_st, st ^ 1);
-#endif
         __builtin_amdgcn_sched_barrier(0);                 // keep the steps apart; free order inside a step
       }
     };

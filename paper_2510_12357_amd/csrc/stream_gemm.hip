@@ -410,9 +410,10 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
 
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s) {
   if (dtype == MOE_BF16 && mode != kRouter) {
-    static int use_lds = -1;
-    if (use_lds < 0) { const char* env = getenv("MOE_STREAM_LDS"); use_lds = env ? atoi(env) : 1; }
-    if (use_lds) return launch_stream_lds(mode, a, s);
+    // bf16 expert GEMMs stream through LDS (stream_lds.hip); MOE_STREAM_LDS=0 selects the
+    // register-ring kernel of this file instead (read per call, so a test can flip it)
+    const char* env = getenv("MOE_STREAM_LDS");
+    if (!env || atoi(env) != 0) return launch_stream_lds(mode, a, s);
   }
   if (dtype == MOE_BF16) {
     switch (mode) {

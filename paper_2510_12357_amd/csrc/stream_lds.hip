@@ -276,6 +276,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   Item nx = decode_item<MODE>(a, 1, total, n_groups, s_prefix, s_src, c, lane);
   int j = 0, k = 0;                 // item ordinal and chunk being consumed
   int pending = 0;                  // the previous item's partial sums wait for their epilogue
+  int need_nx = 0;                  // nx is stale (cur just moved on)
   int f_r0 = 0, f_n0 = 0, f_m = 0, f_N = 0, f_ntn = 0;
   void* f_out = nullptr;
   const unsigned ring_base = (unsigned)(size_t)s_ring;
@@ -330,22 +331,22 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     if (s >= 3 && cur.valid) {
       if (tw < cur.ntn) {
         const unsigned st = (unsigned)(((s + 1) & (kStages - 1)) * kStageBytes);
+        bf16x8 f0[kBLoads], f1[kBLoads];                     // row tile 0 / 1, one per k-step
+        static_assert(kBLoads == 4, "the fragment reads below are written for four k-steps per wave");
+        asm volatile(
+            "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:8192\n"
+            "ds_read_b128 %2, %9\n ds_read_b128 %3, %9 offset:8192\n"
+            "ds_read_b128 %4, %10\n ds_read_b128 %5, %10 offset:8192\n"
+            "ds_read_b128 %6, %11\n ds_read_b128 %7, %11 offset:8192\n"
+            "s_waitcnt lgkmcnt(0)"
+            : "=&v"(f0[0]), "=&v"(f1[0]), "=&v"(f0[1]), "=&v"(f1[1]), "=&v"(f0[2]), "=&v"(f1[2]), "=&v"(f0[3]), "=&v"(f1[3])
+            : "v"(rd_off[0] + st), "v"(rd_off[1] + st), "v"(rd_off[2] + st), "v"(rd_off[3] + st)
+            : "memory");
 #pragma unroll
-        for (int p = 0; p < kBLoads / 2; ++p) {
-          bf16x8 f00, f10, f01, f11;                         // row tile 0 / 1 of two k-steps
-          asm volatile(
-              "ds_read_b128 %0, %4\n ds_read_b128 %1, %4 offset:8192\n"
-              "ds_read_b128 %2, %5\n ds_read_b128 %3, %5 offset:8192\n"
-              "s_waitcnt lgkmcnt(0)"
-              : "=&v"(f00), "=&v"(f10), "=&v"(f01), "=&v"(f11)
-              : "v"(rd_off[2 * p] + st), "v"(rd_off[2 * p + 1] + st)
-              : "memory");
-          const bf16x8 b0 = __builtin_bit_cast(bf16x8, bbuf[2 * p]);
-          const bf16x8 b1 = __builtin_bit_cast(bf16x8, bbuf[2 * p + 1]);
-          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f00, b0, acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f10, b0, acc[1], 0, 0, 0);
-          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f01, b1, acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f11, b1, acc[1], 0, 0, 0);
+        for (int t = 0; t < kBLoads; ++t) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t]);
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
         }
       }
       if (++k == cur.nch) {         // item done: hand the partial sums over, move on
@@ -357,7 +358,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
         f_r0 = cur.r0; f_n0 = cur.n0; f_m = cur.m; f_N = cur.N; f_ntn = cur.ntn; f_out = cur.out;
         pending = 1;
         cur = nx; ++j; k = 0;
-        nx = decode_item<MODE>(a, j + 1, total, n_groups, s_prefix, s_src, c, lane);
+        need_nx = 1;
       }
     }
     // Token rows of the chunk consumed in the next iteration: issued here, behind the MFMAs that
@@ -376,7 +377,9 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
       }
     }
     lds_barrier();                                          // "free"; partial sums of an item that ended are complete
+    // what follows runs while the loaders wait for their next chunk
     if (pending) { pending = 0; epilogue(); }
+    if (need_nx) { need_nx = 0; nx = decode_item<MODE>(a, j + 1, total, n_groups, s_prefix, s_src, c, lane); }
     return cur.valid || s < 2;
   };
 

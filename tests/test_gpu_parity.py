@@ -179,6 +179,22 @@ def test_many_tokens_per_expert_and_renorm():
     check_layer(cfg_small(T=300, E=4, k_big=3, k_little=1, renorm=True, shared_I=(40, 24)), seed=4)
 
 
+def test_many_token_blocks_in_the_streaming_kernels():
+    # fewer than 256 tokens (streaming kernels) but several token blocks per expert, row-tile
+    # counts that are not multiples of 8, K with a partial last chunk
+    check_layer(cfg_small(T=200, E=4, k_big=3, k_little=1, shared_I=(40, 24)), seed=5)
+    check_layer(cfg_small(T=97, E=6, k_big=4, k_little=2, shared_I=(72,)), seed=6)
+
+
+def test_register_ring_kernels_in_bf16(monkeypatch):
+    # MOE_STREAM_LDS=0 selects the register-ring streaming kernels for bf16 as well (they are
+    # what fp32 always uses); the library reads the variable on every call
+    monkeypatch.setenv("MOE_STREAM_LDS", "0")
+    check_layer(cfg_small(dtype="bf16", fallback_ratio=0.3, gate_bias_std=0.5), seed=1)
+    check_layer(cfg_small(T=200, E=4, k_big=3, k_little=1, shared_I=(40, 24)), seed=5)
+    check_layer(wl.CONFIGS["fine60_decode"].with_(T=8), seed=0)
+
+
 def test_all_big_and_all_little_and_null_conf():
     cfg = cfg_small()
     b_big, ref_big = check_layer(cfg, conf=None)
