@@ -7,18 +7,20 @@
 // A operand and weight rows the B operand, each read from LDS as 16-byte K chunks.
 //
 // Tiling for gfx950 (64-wide waves, v_mfma_f32_32x32x16_bf16):
-//   * workgroup tile (Shape<WM,WN,TM,TN>): default 128 tokens x 128 weight rows, K chunk 64,
-//     4 waves in a 2x2 grid, each wave 64 x 64 outputs = 2x2 MFMA tiles (64 accumulator
-//     registers), two workgroups per CU.  (256 x 256 with 8 waves measured the same on a
-//     compute-bound layer and worse on layers with ~150 tokens per expert.)  For gate/up the
-//     weight rows of a tile are half rows of W_gate plus the same rows of W_up, arranged so
-//     that a wave holds gate and up of the same outputs and applies SwiGLU in registers.
-//   * global -> LDS goes through registers with raw buffer loads (token gather and all ragged
-//     edges are offsets beyond the buffer: zeros, no branches); two register sets and two LDS
-//     stages form a software pipeline in which requests, LDS writes and fragment reads are
-//     spread between the MFMAs of a chunk (one barrier per chunk).
-//   * LDS rows are padded by 16 bytes so that the rows a b128 fragment read touches fall
-//     into different banks.
+//   * workgroup tile (Shape<WM,WN,TM,TN>): default 128 tokens x 256 weight rows, K chunk 64,
+//     4 waves in a 2x2 grid, each wave 64 x 128 outputs = 2x4 MFMA tiles (128 accumulator
+//     registers, 6 fragment reads per 8 MFMAs), one workgroup per CU.  For gate/up the weight
+//     rows of a tile are half rows of W_gate plus the same rows of W_up, arranged so that a wave
+//     holds gate and up of the same outputs and applies SwiGLU in registers.
+//   * global -> LDS without registers: buffer loads with the LDS destination move 8 tile rows x
+//     128 bytes per instruction (token gather and all ragged edges are offsets beyond the
+//     buffer: zero fill, no branches).  A ring of stages; the loads of the chunk that is
+//     (stages - 1) ahead are issued between the MFMAs of the current chunk, every wave issues the
+//     same number per chunk, so a counted s_waitcnt vmcnt plus one barrier per chunk says "the
+//     current chunk has landed".
+//   * a tile row is 128 bytes in LDS; the 16-byte column c of row r sits at column
+//     c ^ ((r >> 1) & 7), which spreads the 16 rows that a b128 fragment read touches in one
+//     pass over all banks.
 //   * tiles are enumerated on the device from expert_offsets (the host never sees the counts);
 //     persistent workgroups; the tile list is cut into 8 contiguous ranges, one per XCD, and
 //     the token tiles that share a weight panel are adjacent in the list, so a panel is fetched
@@ -34,43 +36,78 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((address_space(3))) void lds_void;
 typedef uint16_t S;
 
 #ifndef MOE_TILED_BK
 #define MOE_TILED_BK 64
 #endif
-constexpr int BK = MOE_TILED_BK;   // K chunk
-constexpr int LDK = BK + 8;        // padded LDS row, elements
-constexpr int kCPR = BK / 8;       // 16-byte chunks per tile row
+#ifndef MOE_TILED_STAGES
+#define MOE_TILED_STAGES 3
+#endif
+constexpr int BK = MOE_TILED_BK;   // K chunk, elements (32 or 64)
+constexpr int kRowB = BK * 2;      // bytes of a tile row in LDS
+constexpr int kStages = MOE_TILED_STAGES;
+constexpr int kCols = BK / 8;                  // 16-byte columns of a tile row
+constexpr int kRowsPerIns = 1024 / kRowB;      // tile rows that one load instruction fills
+constexpr int kKeyShift = BK == 64 ? 1 : 2;    // rows per 256 bytes of LDS = 1 << kKeyShift
+static_assert(BK == 32 || BK == 64, "K chunk of 32 or 64");
+static_assert(MOE_TILED_STAGES >= 3, "the pipeline needs at least three stages");
+// swizzle key of a tile row: rows that share 256 bytes of LDS get the same key, the next ones the next
+__device__ __forceinline__ constexpr int row_key(int row) { return (row >> kKeyShift) & (kCols - 1); }
+
+// vmcnt(n): bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima (no wait)
+#define MM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
+
+// Workgroup barrier that orders LDS accesses only (no global-memory fence: that would make the
+// compiler wait for every outstanding load).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Two fragment reads off one address register.  The compiler does not see them as LDS accesses,
+// so it neither waits for the loads-to-LDS in flight nor for these; frag_wait() does the latter.
+template <int OFF0, int OFF1>
+__device__ __forceinline__ void frag_read2(bf16x8& f0, bf16x8& f1, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
+               : "=&v"(f0), "=&v"(f1) : "v"(addr), "n"(OFF0), "n"(OFF1) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void frag_wait(bf16x8 (&f)[N]) {
+  static_assert(N == 2 || N == 4, "fragment sets of 2 or 4");
+  if constexpr (N == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]) :: "memory");
+  else asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) :: "memory");
+}
+
+#ifndef MOE_TILED_ATTR
+#define MOE_TILED_ATTR
+#endif
 
 // WM x WN waves; each wave TM x TN MFMA tiles of 32 x 32.
 template <int WM_, int WN_, int TM_, int TN_>
 struct Shape {
   static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
-  static constexpr int kThreads = WM * WN * 64;
+  static constexpr int kWaves = WM * WN, kThreads = kWaves * 64;
   static constexpr int BM = WM * TM * 32;            // tokens per tile
   static constexpr int BNR = WN * TN * 32;           // weight rows per tile (gate/up: half + half)
-  static constexpr int kRowsPerPass = kThreads / kCPR;
-  static constexpr int kLoadsA = BM / kRowsPerPass;
-  static constexpr int kLoadsB = BNR / kRowsPerPass;
-  static_assert(BM % kRowsPerPass == 0 && BNR % kRowsPerPass == 0, "tile rows must divide evenly");
-  static_assert(TN % 2 == 0, "gate/up needs an even number of column tiles per wave");
+  static constexpr int kInsA = BM / kRowsPerIns / kWaves;      // load instructions per wave and chunk
+  static constexpr int kInsB = BNR / kRowsPerIns / kWaves;
+  static constexpr int kStageBytes = (BM + BNR) * kRowB;
+  static_assert(BM % (kRowsPerIns * kWaves) == 0 && BNR % (kRowsPerIns * kWaves) == 0, "tile rows must divide evenly");
+  static_assert(TM == 2 && (TN == 2 || TN == 4), "the fragment reads are written for 2 x 2 or 2 x 4 MFMA tiles per wave");
 };
 
 template <int MODE, typename SH>
-__global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a) {
+__global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(const StreamArgs a) {
   constexpr int BM = SH::BM, BNR = SH::BNR, TM = SH::TM, TN = SH::TN;
-  constexpr int kThreads = SH::kThreads, kRowsPerPass = SH::kRowsPerPass;
-  constexpr int kLoadsA = SH::kLoadsA, kLoadsB = SH::kLoadsB;
+  constexpr int kThreads = SH::kThreads, kInsA = SH::kInsA, kInsB = SH::kInsB;
+  constexpr int kPerChunk = kInsA + kInsB;                         // loads of one wave per chunk
   constexpr int kOutCols = (MODE == kGateUp) ? BNR / 2 : BNR;     // output columns per tile
 
   __shared__ int s_cnt[kMaxGroups];
   __shared__ int s_prefix[kMaxGroups + 1];
-  extern __shared__ __attribute__((aligned(16))) S s_tiles[];      // As[2][BM*LDK] | Bs[2][BNR*LDK]
-  S* const As = s_tiles;
-  S* const Bs = s_tiles + 2 * BM * LDK;
+  extern __shared__ __attribute__((aligned(1024))) char s_tiles[];   // kStages x (A rows | B rows)
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / SH::WN, wn = wave % SH::WN;
   const int n_groups = a.n_routed + (MODE == kDown ? a.n_slabs : a.n_shared);
 
@@ -102,8 +139,20 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, nslots = gridDim.x >> 3;
   const int lo_t = (int)((long)total * xcd / 8), hi_t = (int)((long)total * (xcd + 1) / 8);
 
-  // per-thread chunk of the global -> LDS copy: rows tid/kCPR + kRowsPerPass*p, column tid%kCPR
-  const int ld_row = tid / kCPR, ld_kc = tid % kCPR;
+  // ---- per-lane constants of the loads: instruction p of this wave fills tile rows
+  // kRowsPerIns * (wave * kIns + p) + lane / kCols at physical column lane % kCols ----
+  const int ld_sub = lane / kCols, ld_pc = lane % kCols;
+  // ---- per-lane constants of the fragment reads: row (lane & 31) of a 32-row block, logical
+  // column 2 * kk + lane / 32; every block starts at a multiple of 32 rows, so the swizzle key
+  // of the row depends on the lane only ----
+  const unsigned lds0 = (unsigned)(size_t)s_tiles;
+  const unsigned fkey = (unsigned)row_key(lane & 31);
+  const unsigned a_rd = lds0 + (unsigned)((wm * TM * 32 + (lane & 31)) * kRowB);
+  const unsigned b_rd = lds0 + (unsigned)(BM * kRowB) +
+                        (unsigned)(((MODE == kGateUp ? wn * (TN / 2) * 32 : wn * TN * 32) + (lane & 31)) * kRowB);
+  // byte distance between the fragment rows of consecutive column tiles j
+  constexpr int kJ = 32 * kRowB;                                   // next 32 rows
+  constexpr int kUp = (MODE == kGateUp) ? (BNR / 2) * kRowB : (TN / 2) * kJ;   // j >= TN/2: the up rows / the next blocks
 
   for (int tile = lo_t + slot; tile < hi_t; tile += nslots) {
     int lo = 0, hi = n_groups;
@@ -121,19 +170,24 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
 
     const __amdgpu_buffer_rsrc_t ra = make_rsrc(G.b, G.bbytes);      // tokens
     const __amdgpu_buffer_rsrc_t rb = make_rsrc(G.w0, G.wbytes);     // weights
-    unsigned aoff[kLoadsA], boff[kLoadsB];
+    // running byte offsets of this lane's 16 bytes per load instruction (kOob + small stays out
+    // of range), and the logical column (in elements) behind them for the K tail
+    unsigned aoff[kInsA], boff[kInsB];
+    int acol[kInsA], bcol[kInsB];
 #pragma unroll
-    for (int p = 0; p < kLoadsA; ++p) {
-      const int r = m0 + ld_row + kRowsPerPass * p;        // token row of the tile
+    for (int p = 0; p < kInsA; ++p) {
+      const int tr = kRowsPerIns * (wave * kInsA + p) + ld_sub;      // row of the tile
+      const int r = m0 + tr;
       const bool val = r < G.m;
       int row = r;
       if (G.gather) row = val ? clampi(a.sorted_token[G.row0 + r], 0, a.T - 1) : 0;
-      aoff[p] = val ? (unsigned)row * (unsigned)G.ldw * 2u : kOob;
+      acol[p] = (ld_pc ^ row_key(tr)) * 8;
+      aoff[p] = (val ? (unsigned)row * (unsigned)G.ldw * 2u : kOob) + (unsigned)acol[p] * 2u;
     }
 #pragma unroll
-    for (int p = 0; p < kLoadsB; ++p) {
+    for (int p = 0; p < kInsB; ++p) {
       // weight row of the tile: gate/up tiles hold BNR/2 rows of W_gate, then the same rows of W_up
-      const int br = ld_row + kRowsPerPass * p;
+      const int br = kRowsPerIns * (wave * kInsB + p) + ld_sub;
       int n;
       unsigned extra = 0;
       if (MODE == kGateUp) {
@@ -142,7 +196,8 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
       } else {
         n = n0 + br;
       }
-      boff[p] = n < G.N ? (unsigned)n * (unsigned)G.ldw * 2u + extra : kOob;
+      bcol[p] = (ld_pc ^ row_key(br)) * 8;
+      boff[p] = (n < G.N ? (unsigned)n * (unsigned)G.ldw * 2u + extra : kOob) + (unsigned)bcol[p] * 2u;
     }
 
     f32x16 acc[TM][TN];
@@ -153,87 +208,92 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Software pipeline of one wave.  Two register sets hold chunks on their way from global
-    // memory: while chunk k is multiplied out of LDS stage k%2, chunk k+1 (requested one chunk
-    // earlier) is written to the other stage and chunk k+2 is requested.  The requests are issued
-    // during the first two of the four 16-wide k steps of a chunk, the LDS writes during the last
-    // two, and the fragments of k step j+1 are read while step j is multiplied, so memory
-    // instructions sit between the MFMAs instead of in phases of their own.  Chunks past the end
-    // have offsets beyond the buffers and fetch nothing.
-    i32x4 ga[2][kLoadsA], gb[2][kLoadsB];
-    auto gload_a = [&](int set, int kt) {
-      const int k0 = kt * BK + ld_kc * 8;
-      const bool kval = k0 < K;
+    // Loads of one chunk, in kParts portions so that they can sit between the MFMAs.  Portion
+    // `part` of chunk `kt` into stage `st`; chunks past the end only zero-fill.
+    constexpr int kParts = BK / 16;
+    auto issue = [&](int st, int kt, int part) {
+      char* const sa = s_tiles + st * SH::kStageBytes + (wave * kInsA) * 1024;
+      char* const sb = s_tiles + st * SH::kStageBytes + BM * kRowB + (wave * kInsB) * 1024;
+      const bool full = (kt + 1) * BK <= K;
 #pragma unroll
-      for (int p = 0; p < kLoadsA; ++p)
-        ga[set][p] = __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(kval ? aoff[p] + (unsigned)k0 * 2u : kOob), 0, 0);
+      for (int p = 0; p < kInsA; ++p)
+        if (p % kParts == part) {
+          const unsigned off = full ? aoff[p] : ((kt * BK + acol[p] < K) ? aoff[p] : kOob);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void*)(sa + p * 1024), 16, (int)off, 0, 0, 0);
+        }
+#pragma unroll
+      for (int p = 0; p < kInsB; ++p)
+        if ((kInsA + p) % kParts == part) {
+          const unsigned off = full ? boff[p] : ((kt * BK + bcol[p] < K) ? boff[p] : kOob);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void*)(sb + p * 1024), 16, (int)off, 0, 0, 0);
+        }
     };
-    auto gload_b = [&](int set, int kt) {
-      const int k0 = kt * BK + ld_kc * 8;
-      const bool kval = k0 < K;
+    auto advance = [&]() {
 #pragma unroll
-      for (int p = 0; p < kLoadsB; ++p)
-        gb[set][p] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(kval ? boff[p] + (unsigned)k0 * 2u : kOob), 0, 0);
-    };
-    auto lstore_a = [&](int set, int st) {
+      for (int p = 0; p < kInsA; ++p) aoff[p] += kRowB;
 #pragma unroll
-      for (int p = 0; p < kLoadsA; ++p)
-        *reinterpret_cast<i32x4*>(&As[st * BM * LDK + (ld_row + kRowsPerPass * p) * LDK + ld_kc * 8]) = ga[set][p];
-    };
-    auto lstore_b = [&](int set, int st) {
-#pragma unroll
-      for (int p = 0; p < kLoadsB; ++p)
-        *reinterpret_cast<i32x4*>(&Bs[st * BNR * LDK + (ld_row + kRowsPerPass * p) * LDK + ld_kc * 8]) = gb[set][p];
+      for (int p = 0; p < kInsB; ++p) boff[p] += kRowB;
     };
     auto read_frags = [&](int st, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
-      const S* Ast = As + st * BM * LDK;
-      const S* Bst = Bs + st * BNR * LDK;
-      const int kcol = kk * 16 + (lane >> 5) * 8;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-        fa[i] = *reinterpret_cast<const bf16x8*>(&Ast[(wm * TM * 32 + i * 32 + (lane & 31)) * LDK + kcol]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        // gate/up: j < TN/2 gate rows, j >= TN/2 the matching up rows; down: TN column blocks
-        const int brow = (MODE == kGateUp)
-                             ? (j / (TN / 2)) * (BNR / 2) + wn * (TN / 2) * 32 + (j % (TN / 2)) * 32 + (lane & 31)
-                             : wn * TN * 32 + j * 32 + (lane & 31);
-        fb[j] = *reinterpret_cast<const bf16x8*>(&Bst[brow * LDK + kcol]);
-      }
-    };
-    // one chunk: multiply LDS stage st, write register set set_st to the other stage, request
-    // chunk kt_ld into register set set_ld
-    auto half = [&](int st, int set_st, int set_ld, int kt_ld) {
-      constexpr int KK = BK / 16;
-      bf16x8 fa[2][TM], fb[2][TN];
-      read_frags(st, 0, fa[0], fb[0]);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        if (kk + 1 < KK) read_frags(st, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-        if (kk == 0) gload_a(set_ld, kt_ld);
-        if (kk == 1 || KK == 1) gload_b(set_ld, kt_ld);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
-        if (kk == KK - 2 || KK == 1) lstore_a(set_st, st ^ 1);
-        if (kk == KK - 1) lstore_b(set_st, st ^ 1);
-        __builtin_amdgcn_sched_barrier(0);                 // keep the steps apart; free order inside a step
+      const unsigned col = (((unsigned)(kk * 2 + (lane >> 5))) ^ fkey) * 16u + (unsigned)(st * SH::kStageBytes);
+      frag_read2<0, kJ>(fa[0], fa[1], a_rd + col);
+      if constexpr (TN == 2) {
+        frag_read2<0, kUp>(fb[0], fb[1], b_rd + col);
+      } else {
+        frag_read2<0, kJ>(fb[0], fb[1], b_rd + col);
+        frag_read2<kUp, kUp + kJ>(fb[2], fb[3], b_rd + col);
       }
     };
 
     const int nk = (K + BK - 1) / BK;
-    gload_a(0, 0); gload_b(0, 0);
-    gload_a(1, 1); gload_b(1, 1);
-    lstore_a(0, 0); lstore_b(0, 0);                        // waits for chunk 0 only
-    __syncthreads();
-    for (int kt = 0; kt < nk; kt += 2) {
-      half(0, 1, 0, kt + 2);
-      __syncthreads();
-      half(1, 0, 1, kt + 3);                               // multiplies zeros when nk is odd
-      __syncthreads();
+    constexpr int kAhead = kStages - 1;                    // chunks in flight ahead of the one consumed
+    // aoff / boff always point at the chunk that is issued next
+#pragma unroll
+    for (int c = 0; c < kAhead; ++c) {
+#pragma unroll
+      for (int part = 0; part < kParts; ++part) issue(c, c, part);
+      advance();
     }
+    // The fragments of the first k-step of chunk kt are read at the end of chunk kt-1, right after
+    // the barrier that says "chunk kt has landed": that barrier sits in front of the last
+    // k-step's MFMAs, when every wave has already read all fragments of chunk kt-1, so it also
+    // says "the stage of chunk kt-1 is free".
+    static_assert(kPerChunk % kParts == 0, "equal portions of loads per k-step");
+    constexpr int kPortion = kPerChunk / kParts;
+    bf16x8 fa[2][TM], fb[2][TN];
+    MM_WAIT_VMCNT((kAhead - 1) * kPerChunk);               // chunk 0 has landed
+    lds_barrier();
+    read_frags(0, 0, fa[0], fb[0]);
+    frag_wait(fa[0]); frag_wait(fb[0]);
+    int st = 0;                                            // stage of chunk kt
+    for (int kt = 0; kt < nk; ++kt) {
+      const int st_ld = st == 0 ? kStages - 1 : st - 1;    // stage of chunk kt-1 = stage of chunk kt+kAhead
+      const int st_nx = st + 1 == kStages ? 0 : st + 1;    // stage of chunk kt+1
+#pragma unroll
+      for (int kk = 0; kk < kParts; ++kk) {
+        const int cur = kk & 1, nxt = (kk + 1) & 1;        // kParts is even: set 0 again holds k-step 0 of the next chunk
+        if (kk + 1 < kParts) {
+          read_frags(st, kk + 1, fa[nxt], fb[nxt]);
+        } else {
+          // all of chunk kt+1 except the portions of chunk kt+kAhead issued so far in this chunk
+          MM_WAIT_VMCNT((kAhead - 2) * kPerChunk + (kParts - 1) * kPortion);
+          lds_barrier();
+          read_frags(st_nx, 0, fa[nxt], fb[nxt]);          // zeros / stale data past the last chunk; never used
+        }
+        issue(st_ld, kt + kAhead, kk);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+        frag_wait(fa[nxt]); frag_wait(fb[nxt]);
+        __builtin_amdgcn_sched_barrier(0);                 // keep the steps apart; free order inside a step
+      }
+      advance();
+      st = st_nx;
+    }
+    MM_WAIT_VMCNT(0);                                      // the zero fills past the end, before stages are reused
+    lds_barrier();
 
     // ---- epilogue: accumulator v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 ----
 #pragma unroll
@@ -261,12 +321,13 @@ __global__ __launch_bounds__(SH::kThreads) void tiled_kernel(const StreamArgs a)
           }
         }
       }
+    MM_WAIT_VMCNT(0);                                      // stores out of the way of the next tile's counted loads
   }
 }
 
 template <int MODE, typename SH>
 int launch_tiled_shape(const StreamArgs& a, hipStream_t s) {
-  constexpr size_t kLds = 2 * (size_t)(SH::BM + SH::BNR) * LDK * sizeof(S);
+  constexpr size_t kLds = (size_t)kStages * SH::kStageBytes;
   static int per_cu = 0;
   if (per_cu == 0) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_kernel<MODE, SH>),
@@ -285,7 +346,7 @@ int launch_tiled_shape(const StreamArgs& a, hipStream_t s) {
 }
 
 #ifndef MOE_TILED_SHAPE
-#define MOE_TILED_SHAPE 2, 2, 2, 2
+#define MOE_TILED_SHAPE 2, 2, 2, 4
 #endif
 typedef Shape<MOE_TILED_SHAPE> DefaultShape;
 
