@@ -176,8 +176,7 @@ struct Smem {
 
 template <int MODE>
 __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4))) void stream_lds_kernel(const StreamArgs a) {
-  // One LDS object with the ring first: the ring starts at LDS address 0 and ends below 64 KB,
-  // so the base that a load-to-LDS instruction takes from M0 stays within 16 bits.
+  // One LDS object, ring first (1 KB aligned: every load instruction fills one aligned KB).
   __shared__ __attribute__((aligned(1024))) Smem sm;
   char* const s_ring = sm.ring;
   float (&s_red)[kWorkers][2][4][64] = sm.red;
