@@ -38,7 +38,7 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_gate_logits", "oracle_token_confidence", "oracle_route",
-                     "oracle_dispatch", "oracle_swiglu_rows", "oracle_expert_ffn",
+                     "oracle_dispatch", "oracle_dispatch_from", "oracle_combine_add", "oracle_swiglu_rows", "oracle_expert_ffn",
                      "oracle_combine", "oracle_num_threads"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
@@ -167,6 +167,49 @@ def combine(y: np.ndarray, topk_w: np.ndarray, inv_pos: np.ndarray, k_t: np.ndar
     _check(_load().oracle_combine(_p(y), _p(w), _p(inv), _p(kt), _p(sh), ns, T, H, K, _p(out)),
            "combine")
     return out
+
+
+def dispatch_from(topk_idx: np.ndarray, k_t: np.ndarray, j_lo: int, E: int):
+    """Dispatch of the ranks j_lo <= j < k_t[t] only -> same four arrays as dispatch()."""
+    idx = _c(topk_idx, np.int32)
+    kt = _c(k_t, np.int32)
+    T, K = idx.shape
+    off = np.empty((E + 1,), np.int32)
+    st = np.empty((T * K,), np.int32)
+    sr = np.empty((T * K,), np.int32)
+    inv = np.empty((T, K), np.int32)
+    _check(_load().oracle_dispatch_from(_p(idx), _p(kt), int(j_lo), T, E, K, _p(off), _p(st), _p(sr),
+                                        _p(inv)), "dispatch_from")
+    return off, st, sr, inv
+
+
+def combine_add(y: np.ndarray, topk_w: np.ndarray, inv_pos: np.ndarray, k_t: np.ndarray, j_lo: int,
+                out: np.ndarray) -> np.ndarray:
+    """-> out + sum over the ranks j_lo <= j < k_t[t] (float64 [T,H]); `out` is not modified"""
+    y = _c(y, np.float64)
+    w = _c(topk_w, np.float32)
+    inv = _c(inv_pos, np.int32)
+    kt = _c(k_t, np.int32)
+    res = np.array(out, dtype=np.float64, order="C", copy=True)
+    T, H = res.shape
+    _check(_load().oracle_combine_add(_p(y), _p(w), _p(inv), _p(kt), int(j_lo), T, H, w.shape[1], _p(res)),
+           "combine_add")
+    return res
+
+
+def fallback_increment(x: np.ndarray, expert_w: Sequence[np.ndarray], I: int, logits: np.ndarray,
+                       conf: Optional[np.ndarray], gamma: float, k_big: int, k_little: int,
+                       out_little: np.ndarray) -> dict:
+    """Second pass of Alg. 1 at layer level: the tokens whose little result is rejected (conf not above
+    gamma) get the big model's layer output.  With routing weights that are not renormalised the big
+    layer output is the little one plus the experts of ranks k_little .. k_big-1, so only those are
+    computed and added to `out_little` (the little pass's layer output, all tokens at k_little)."""
+    idx, w, imp, kt = route(logits, conf, gamma, k_big, k_little, False)
+    off, st, sr, inv = dispatch_from(idx, kt, k_little, len(expert_w))
+    y = expert_ffn(x, expert_w, I, off, st)
+    out = combine_add(y, w, inv, kt, k_little, out_little)
+    return dict(topk_idx=idx, topk_w=w, important=imp, k_t=kt, expert_offsets=off, sorted_token=st,
+                sorted_rank=sr, inv_pos=inv, y=y, out=out)
 
 
 def moe_layer(x: np.ndarray, Wg: np.ndarray, gate_bias: Optional[np.ndarray],

@@ -153,6 +153,36 @@ int oracle_route(const float* logits, const float* conf, float gamma, int T, int
 //   sorted_token[p]   token of the pair at position p      (-1 for p >= P)
 //   sorted_rank[p]    its rank j in the token's selection  (-1 for p >= P)
 //   inv_pos[t][j]     position of pair (t, j)              (-1 for j >= k_t)
+// Dispatch of the ranks j_lo <= j < k_t[t] only.  j_lo = 0 is the dispatch of a whole step; j_lo =
+// k_little is the re-do of a token whose little result was rejected (Alg. 1, Sec. III-B) when the
+// experts of ranks below k_little have been computed already: the big model's expert set is the
+// little one's plus the ranks k_little .. K-1 (Sec. III-A: same router, K instead of K/2 experts).
+int oracle_dispatch_from(const int32_t* idx, const int32_t* k_t, int j_lo, int T, int E, int K,
+                         int32_t* offsets, int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos) {
+  if (!idx || !k_t || !offsets || !sorted_token || !sorted_rank || !inv_pos || j_lo < 0) return -1;
+  for (size_t i = 0; i < (size_t)T * K; ++i) {
+    sorted_token[i] = -1;
+    sorted_rank[i] = -1;
+    inv_pos[i] = -1;
+  }
+  int pos = 0;
+  for (int e = 0; e < E; ++e) {
+    offsets[e] = pos;
+    for (int t = 0; t < T; ++t) {
+      for (int j = j_lo; j < k_t[t]; ++j) {
+        if (idx[(size_t)t * K + j] == e) {
+          sorted_token[pos] = t;
+          sorted_rank[pos] = j;
+          inv_pos[(size_t)t * K + j] = pos;
+          ++pos;
+        }
+      }
+    }
+  }
+  offsets[E] = pos;
+  return 0;
+}
+
 int oracle_dispatch(const int32_t* idx, const int32_t* k_t, int T, int E, int K, int32_t* offsets,
                     int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos) {
   if (!idx || !k_t || !offsets || !sorted_token || !sorted_rank || !inv_pos) return -1;
@@ -242,6 +272,23 @@ int oracle_combine(const double* y, const float* w, const int32_t* inv_pos, cons
       for (int j = 0; j < k_t[t]; ++j)
         acc += (double)w[(size_t)t * K + j] * y[(size_t)inv_pos[(size_t)t * K + j] * H + c];
       for (int s = 0; s < n_shared; ++s) acc += shared[((size_t)s * T + t) * H + c];
+      out[(size_t)t * H + c] = acc;
+    }
+  }
+  return 0;
+}
+
+// out[t] += sum_{j_lo <= j < k_t[t]} w[t][j] * y[inv_pos[t][j]]: the ranks that the big model adds on
+// top of a little result (routing weights not renormalised, so the ranks below j_lo keep their
+// weights).  Tokens with k_t[t] <= j_lo are left as they are.
+int oracle_combine_add(const double* y, const float* w, const int32_t* inv_pos, const int32_t* k_t,
+                       int j_lo, int T, int H, int K, double* out) {
+  if (!w || !inv_pos || !k_t || !out || j_lo < 0) return -1;
+  for (int t = 0; t < T; ++t) {
+    for (int c = 0; c < H; ++c) {
+      double acc = out[(size_t)t * H + c];
+      for (int j = j_lo; j < k_t[t]; ++j)
+        acc += (double)w[(size_t)t * K + j] * y[(size_t)inv_pos[(size_t)t * K + j] * H + c];
       out[(size_t)t * H + c] = acc;
     }
   }

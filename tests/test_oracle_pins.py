@@ -373,3 +373,84 @@ def test_confidence_generator_hits_fallback_ratio():
     bits = wl.f32_to_bf16_bits(np.array([1.0, 1.00390625, 1.01171875, -2.5], np.float32))
     ref = torch.tensor([1.0, 1.00390625, 1.01171875, -2.5]).bfloat16().view(torch.int16).numpy()
     assert np.array_equal(bits, ref.view(np.uint16))
+
+
+# ------------------------------------------------------------------ second pass of Alg. 1 at layer level
+def test_dispatch_from_equals_stable_sort_of_the_window():
+    g = np.random.default_rng(7)
+    T, E, K = 53, 11, 6
+    kt = g.choice([2, 3, 6], size=T).astype(np.int32)
+    idx = np.full((T, K), -1, np.int32)
+    for t in range(T):
+        idx[t, :kt[t]] = g.permutation(E)[:kt[t]]
+    # j_lo = 0 is the plain dispatch
+    for a, b in zip(oracle.dispatch_from(idx, kt, 0, E), oracle.dispatch(idx, kt, E)):
+        assert np.array_equal(a, b)
+    for j_lo in (1, 2, 3, 6, 9):
+        off, st, sr, inv = oracle.dispatch_from(idx, kt, j_lo, E)
+        pairs = [(t, j) for t in range(T) for j in range(j_lo, kt[t])]
+        P = len(pairs)
+        assert off[-1] == P == np.maximum(kt - j_lo, 0).sum()
+        if P:
+            keys = np.array([idx[t, j] for t, j in pairs])
+            order = np.argsort(keys, kind="stable")
+            assert st[:P].tolist() == [pairs[i][0] for i in order]
+            assert sr[:P].tolist() == [pairs[i][1] for i in order]
+            assert np.array_equal(off, np.concatenate([[0], np.cumsum(np.bincount(keys, minlength=E))]))
+        assert (st[P:] == -1).all() and (sr[P:] == -1).all()
+        want = np.full((T, K), -1)
+        for p in range(P):
+            want[st[p], sr[p]] = p
+        assert np.array_equal(inv, want)               # -1 for every rank outside the window
+
+
+def test_combine_add_is_the_window_of_combine():
+    g = np.random.default_rng(8)
+    T, H, K, E = 9, 12, 4, 5
+    kt = g.choice([2, 4], size=T).astype(np.int32)
+    idx = np.full((T, K), -1, np.int32)
+    for t in range(T):
+        idx[t, :kt[t]] = g.permutation(E)[:kt[t]]
+    w = g.random((T, K)).astype(np.float32)
+    off, st, sr, inv = oracle.dispatch(idx, kt, E)
+    y = g.standard_normal((int(off[-1]), H))
+    full = oracle.combine(y, w, inv, kt, None, T, H)
+    low = oracle.combine(y, w, inv, np.minimum(kt, 2).astype(np.int32), None, T, H)
+    base = g.standard_normal((T, H))
+    got = oracle.combine_add(y, w, inv, kt, 2, base)
+    assert np.allclose(got, base + (full - low), rtol=1e-12, atol=1e-12)
+    # written out by hand for one token
+    t = int(np.argmax(kt))
+    hand = base[t] + sum(float(w[t, j]) * y[inv[t, j]] for j in range(2, kt[t]))
+    assert np.allclose(got[t], hand, rtol=1e-12, atol=1e-14)
+    # tokens whose window is empty are untouched, bit for bit
+    assert np.array_equal(got[kt <= 2], base[kt <= 2])
+    assert np.array_equal(oracle.combine_add(y, w, inv, kt, K, base), base)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("r", [0.0, 0.3, 1.0])
+def test_little_pass_plus_fallback_increment_is_the_mixed_layer(dtype, r):
+    # Alg. 1: little model on every token, big model again for the rejected ones.  Without
+    # renormalisation the two-pass result must be the layer evaluated once with k_t per token,
+    # which in turn is pinned to the brute-force dense evaluation above.
+    cfg = wl.LayerConfig(name="two_pass", T=23, H=40, E=7, I=24, k_big=4, k_little=2, shared_I=(16,),
+                         dtype=dtype, renorm=False, gate_std=0.5, w_std=0.2, fallback_ratio=r)
+    layer = wl.make_layer(cfg, seed=11)
+    args = (layer.x, layer.Wg, layer.gate_bias, layer.expert_w, cfg.I, layer.shared_w, cfg.shared_I)
+    mixed = oracle.moe_layer(*args, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, False)
+    never = np.full(cfg.T, np.inf, np.float32)                       # confidence above gamma: nobody falls back
+    little = oracle.moe_layer(*args, never, cfg.gamma, cfg.k_big, cfg.k_little, False)
+    assert (little["k_t"] == cfg.k_little).all()
+    second = oracle.fallback_increment(layer.x, layer.expert_w, cfg.I, little["logits"], layer.conf,
+                                       cfg.gamma, cfg.k_big, cfg.k_little, little["out"])
+    assert np.array_equal(second["k_t"], mixed["k_t"])
+    assert int(second["expert_offsets"][-1]) == int((mixed["k_t"] - cfg.k_little).sum())
+    scale = np.abs(mixed["out"]).max()
+    assert np.abs(second["out"] - mixed["out"]).max() <= 1e-12 * scale
+    # tokens that keep their little result are not touched at all
+    keep = mixed["important"] == 0
+    assert np.array_equal(second["out"][keep], little["out"][keep])
+    # and against the independent dense evaluation
+    dense, _, _ = brute_force_layer(layer, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, False)
+    assert np.abs(second["out"] - dense).max() <= 1e-9 * scale
