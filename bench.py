@@ -128,6 +128,49 @@ def run_steps(mm, torch, layers: DeviceLayers, bufs, n: int, first: int = 0):
                       layers.shared[l], side_stream=side)
 
 
+def time_two_pass(mm, torch, cfg, steps: int, warmup: int):
+    """Alg. 1 at layer level: little pass on every token, then the fallback pass that adds the ranks
+    k_little .. k_big-1 for the tokens rejected by the layer's confidences (fallback ratio of cfg).
+    -> microseconds per step of the little pass, the fallback pass, and an all-big pass."""
+    L = auto_layers(cfg)
+    layers = DeviceLayers(cfg, L)
+    b = mm.StepBuffers(cfg)
+    never = torch.full((cfg.T,), float("inf"), dtype=torch.float32, device="cuda")
+
+    def little(l):
+        mm.layer_step(b, layers.x[l], layers.Wg[l], layers.bias[l], never, layers.table[l], layers.shared[l])
+
+    def fallback(l):
+        mm.fallback_step(b, layers.x[l], layers.conf[l], layers.table[l])
+
+    def big(l):
+        mm.layer_step(b, layers.x[l], layers.Wg[l], layers.bias[l], None, layers.table[l], layers.shared[l])
+
+    def timed(fn, pre=None):
+        # `pre` (untimed on the device clock: bracketed out with events) prepares what fn consumes
+        ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        ev1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+        for i in range(warmup):
+            if pre: pre(i % L)
+            fn(i % L)
+        for i in range(steps):
+            if pre: pre(i % L)
+            ev0[i].record()
+            fn(i % L)
+            ev1[i].record()
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(c) for a, c in zip(ev0, ev1)) * 1e3 / steps
+
+    t_l = timed(little)
+    t_f = timed(fallback, pre=little)
+    t_b = timed(big)
+    flagged = sum(int((layers.conf[l] <= cfg.gamma).sum()) for l in range(L)) / L
+    del layers, b
+    torch.cuda.empty_cache()
+    return dict(little_us=t_l, fallback_us=t_f, all_big_us=t_b, flagged_tokens_per_step=flagged,
+                speedup_vs_all_big=t_b / (t_l + t_f))
+
+
 def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: bool = True):
     """-> dict with ms_per_step, tokens/s, per-kernel ms, routing statistics"""
     L = L or auto_layers(cfg)
@@ -304,6 +347,9 @@ def main():
                                 speedup_r0_11=T_ / (Tl_ + 0.11 * Tb_), speedup_r0_21=T_ / (Tl_ + 0.21 * Tb_),
                                 note="HBM-resident layer on MI355X; the paper's 1.57-1.72x are end-to-end with "
                                      "PCIe offloading on other hardware (context only)")
+        # the paper's two-pass sequence at layer level (fallback pass = only the ranks above k_little)
+        others["two_pass"] = {name: time_two_pass(mm, torch, workload_config(name, args.ratio), k2, w2)
+                              for name in ("fine60_decode_b1", "fine60_decode_b64")}
         extra["other_workloads"] = others
 
     line = dict(metric="MoE-layer tokens/s (decode b=1..64, prefill 2k) + % HBM/MFMA roofline",

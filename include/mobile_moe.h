@@ -176,6 +176,33 @@ int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,
                 void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Second pass of Alg. 1 at layer level.  Alg. 1 runs the little model (k_little experts per token)
+ * and, for a token whose result is rejected (confidence not above gamma), the big model
+ * (k_big experts, Sec. III-A: same router).  With routing weights that are not renormalised
+ * (cfg->renorm == 0) the big model's layer output is the little one's plus the experts of ranks
+ * k_little .. k_big-1, so the re-do only has to compute those:
+ *
+ *   pass 1  moe_route (conf = NULL is NOT little: pass a confidence above gamma for every token),
+ *           moe_dispatch, moe_expert_ffn, moe_combine                    -> out = little output
+ *   pass 2  moe_route(logits_given = 1, conf = the tokens' confidences)  -> k_t = k_big where rejected
+ *           moe_dispatch_from(j_lo = k_little)    pairs (t, j) with j_lo <= j < k_t[t] only;
+ *                                                 inv_pos = -1 for every other rank
+ *           moe_expert_ffn(run_shared = 0)        the shared experts are part of pass 1
+ *           moe_combine_add(j_lo = k_little)      out[t] += sum_{j_lo <= j < k_t[t]} w[t][j] y[inv_pos[t][j]]
+ *
+ * moe_dispatch_from has the arguments, outputs and workspace of moe_dispatch; moe_dispatch is
+ * j_lo = 0.  moe_combine_add reads and rewrites out [T,H] (storage dtype; fp32 sum in ascending j,
+ * one more rounding) for the tokens with k_t[t] > j_lo and leaves the others untouched; it
+ * returns MOE_E_UNSUPPORTED when cfg->renorm != 0, because then the weights of the ranks below
+ * j_lo differ between the two models.  0 <= j_lo <= k_big, else MOE_E_BADARG.
+ */
+int moe_dispatch_from(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t, int32_t j_lo,
+                      int32_t* expert_offsets, int32_t* sorted_token, int32_t* sorted_rank,
+                      int32_t* inv_pos, void* ws, size_t ws_bytes, void* stream);
+int moe_combine_add(const moe_config* cfg, const float* y, const float* topk_w, const int32_t* inv_pos,
+                    const int32_t* k_t, int32_t j_lo, void* out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Fallback fetch and prefetch of expert weights (Sec. II-B: experts stay in host DRAM and are
  * loaded when the router asks for them; Sec. III-B: for a token that falls back, the router
  * outputs of its discarded little pass name the experts of the big pass ahead of time, for

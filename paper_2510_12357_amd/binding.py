@@ -26,7 +26,8 @@ ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "M
           -5: "MOE_E_CACHE_FULL", -6: "MOE_E_WORKSPACE"}
 
 EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
-           "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_expert_ffn_workspace_bytes",
+           "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_from", "moe_combine_add",
+           "moe_expert_ffn_workspace_bytes",
            "moe_shared_out_slabs", "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync")
 
@@ -74,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_dispatch_workspace_bytes.argtypes = [cfgp]
     lib.moe_dispatch_workspace_bytes.restype = sz
     lib.moe_dispatch.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_dispatch_from.argtypes = [cfgp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.moe_combine_add.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, vp]
     lib.moe_expert_ffn_workspace_bytes.argtypes = [cfgp]
     lib.moe_expert_ffn_workspace_bytes.restype = sz
     lib.moe_shared_out_slabs.argtypes = [cfgp]
@@ -94,6 +97,7 @@ def load_library() -> ctypes.CDLL:
     lib.moe_cache_snapshot.argtypes = [vp, ctypes.POINTER(i32)]
     lib.moe_cache_sync.argtypes = [vp]
     for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence", "moe_dispatch",
+                 "moe_dispatch_from", "moe_combine_add",
                  "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot",
                  "moe_cache_sync"):
         getattr(lib, name).restype = ctypes.c_int
@@ -180,6 +184,18 @@ def moe_dispatch(cfg: moe_config, topk_idx, k_t, expert_offsets, sorted_token, s
     _check(load_library().moe_dispatch(ctypes.byref(cfg), _ptr(topk_idx), _ptr(k_t),
                                        _ptr(expert_offsets), _ptr(sorted_token), _ptr(sorted_rank),
                                        _ptr(inv_pos), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def moe_dispatch_from(cfg: moe_config, topk_idx, k_t, j_lo: int, expert_offsets, sorted_token, sorted_rank,
+                      inv_pos, ws, ws_bytes: int, stream=None) -> None:
+    _check(load_library().moe_dispatch_from(ctypes.byref(cfg), _ptr(topk_idx), _ptr(k_t), int(j_lo),
+                                            _ptr(expert_offsets), _ptr(sorted_token), _ptr(sorted_rank),
+                                            _ptr(inv_pos), _ptr(ws), ws_bytes, _stream(stream)))
+
+
+def moe_combine_add(cfg: moe_config, y, topk_w, inv_pos, k_t, j_lo: int, out, stream=None) -> None:
+    _check(load_library().moe_combine_add(ctypes.byref(cfg), _ptr(y), _ptr(topk_w), _ptr(inv_pos), _ptr(k_t),
+                                          int(j_lo), _ptr(out), _stream(stream)))
 
 
 def moe_expert_ffn_workspace_bytes(cfg: moe_config) -> int:
@@ -326,4 +342,18 @@ def layer_step(b: StepBuffers, x, Wg, gate_bias, conf, expert_table, shared_w, l
     if overlap:
         main.wait_event(b.ev_shared)
     moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out, stream)
+    return b.out
+
+
+def fallback_step(b: StepBuffers, x, conf, expert_table, stream=None) -> torch.Tensor:
+    """Second pass of Alg. 1 on the buffers of a little pass (layer_step with a confidence above gamma
+    for every token, which leaves the router logits in b.logits and the little output in b.out): the
+    tokens rejected by `conf` get the experts of ranks k_little .. k_big-1 added.  Four C calls."""
+    kl = int(b.c.k_little)
+    moe_route(b.c, x, None, None, conf, b.logits, True, b.topk_idx, b.topk_w, b.important, b.k_t, stream)
+    moe_dispatch_from(b.c, b.topk_idx, b.k_t, kl, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                      b.dws, b.dws_bytes, stream)
+    moe_expert_ffn(b.c, x, b.expert_offsets, b.sorted_token, expert_table, (), True, False, b.y,
+                   b.shared_out, b.fws, b.fws_bytes, stream)
+    moe_combine_add(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, kl, b.out, stream)
     return b.out

@@ -214,8 +214,17 @@ extern "C" size_t moe_dispatch_workspace_bytes(const moe_config* cfg) {
 extern "C" int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t,
                             int32_t* expert_offsets, int32_t* sorted_token, int32_t* sorted_rank,
                             int32_t* inv_pos, void* ws, size_t ws_bytes, void* stream) {
+  return moe_dispatch_from(cfg, topk_idx, k_t, 0, expert_offsets, sorted_token, sorted_rank, inv_pos, ws, ws_bytes,
+                           stream);
+}
+
+extern "C" int moe_dispatch_from(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t,
+                                 int32_t j_lo, int32_t* expert_offsets, int32_t* sorted_token,
+                                 int32_t* sorted_rank, int32_t* inv_pos, void* ws, size_t ws_bytes,
+                                 void* stream) {
   int rc = validate_config(cfg);
   if (rc) return rc;
+  if (j_lo < 0 || j_lo > cfg->k_big) return fail(MOE_E_BADARG, "moe_dispatch_from: j_lo=%d outside [0, k_big=%d]", j_lo, cfg->k_big);
   if (!expert_offsets) return fail(MOE_E_BADARG, "moe_dispatch: expert_offsets is NULL");
   if (cfg->T > 0 && (!topk_idx || !k_t || !sorted_token || !sorted_rank || !inv_pos))
     return fail(MOE_E_BADARG, "moe_dispatch: null tensor");
@@ -223,7 +232,7 @@ extern "C" int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, cons
     return fail(MOE_E_WORKSPACE, "moe_dispatch: workspace %p of %zu bytes (need %zu, 256-byte aligned)", ws,
                 ws_bytes, moe_dispatch_workspace_bytes(cfg));
   ProfScope ps(kProfDispatch, static_cast<hipStream_t>(stream));
-  return launch_dispatch(*cfg, topk_idx, k_t, expert_offsets, sorted_token, sorted_rank, inv_pos,
+  return launch_dispatch(*cfg, topk_idx, k_t, j_lo, expert_offsets, sorted_token, sorted_rank, inv_pos,
                          static_cast<int32_t*>(ws), static_cast<hipStream_t>(stream));
 }
 
@@ -305,4 +314,19 @@ extern "C" int moe_combine(const moe_config* cfg, const float* y, const float* t
   if (cfg->n_shared > 0 && !shared_out) return fail(MOE_E_BADARG, "moe_combine: shared_out is NULL but n_shared=%d", cfg->n_shared);
   ProfScope ps(kProfCombine, static_cast<hipStream_t>(stream));
   return launch_combine(*cfg, y, topk_w, inv_pos, k_t, shared_out, out, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_combine_add(const moe_config* cfg, const float* y, const float* topk_w,
+                               const int32_t* inv_pos, const int32_t* k_t, int32_t j_lo, void* out,
+                               void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (cfg->renorm)
+    return fail(MOE_E_UNSUPPORTED, "moe_combine_add: with renormalised routing weights the ranks below j_lo "
+                                   "change their weights too; recompute the token with moe_combine");
+  if (j_lo < 0 || j_lo > cfg->k_big) return fail(MOE_E_BADARG, "moe_combine_add: j_lo=%d outside [0, k_big=%d]", j_lo, cfg->k_big);
+  if (cfg->T == 0) return MOE_OK;
+  if (!y || !topk_w || !inv_pos || !k_t || !out) return fail(MOE_E_BADARG, "moe_combine_add: null tensor");
+  ProfScope ps(kProfCombine, static_cast<hipStream_t>(stream));
+  return launch_combine_add(*cfg, y, topk_w, inv_pos, k_t, j_lo, out, static_cast<hipStream_t>(stream));
 }

@@ -33,7 +33,7 @@ __device__ __forceinline__ int match_rank_lds(const int* s_idx, int t, int T, in
 }
 
 __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
-    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int E, int K,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int j_lo, int T, int E, int K,
     int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_token,
     int32_t* __restrict__ sorted_rank, int32_t* __restrict__ inv_pos) {
   __shared__ int s_idx[kSmallT * MOE_MAX_TOPK];
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
     int kt = k_t[t];
     kt = kt < 0 ? 0 : (kt > K ? K : kt);
     const int e = idx[i];
-    const bool pair = j < kt && (unsigned)e < (unsigned)E;
+    const bool pair = j >= j_lo && j < kt && (unsigned)e < (unsigned)E;
     s_idx[i] = pair ? e : -1;
     if (!pair) inv_pos[i] = -1;
   }
@@ -103,7 +103,7 @@ constexpr int kChunk = 128;
 constexpr int kCountSlab = 32 * MOE_MAX_EXPERTS;        // ints of the count table held in LDS at a time
 
 __device__ __forceinline__ void stage_chunk(const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t,
-                                            int t0, int T, int E, int K, int* s_idx,
+                                            int j_lo, int t0, int T, int E, int K, int* s_idx,
                                             int32_t* __restrict__ inv_pos) {
   const int n = min(kChunk, T - t0) * K;
   for (int i = threadIdx.x; i < n; i += kBigThreads) {
@@ -111,20 +111,20 @@ __device__ __forceinline__ void stage_chunk(const int32_t* __restrict__ idx, con
     int kt = k_t[t0 + tl];
     kt = kt < 0 ? 0 : (kt > K ? K : kt);
     const int e = idx[(size_t)t0 * K + i];
-    const bool pair = j < kt && (unsigned)e < (unsigned)E;
+    const bool pair = j >= j_lo && j < kt && (unsigned)e < (unsigned)E;
     s_idx[i] = pair ? e : -1;
     if (inv_pos && !pair) inv_pos[(size_t)t0 * K + i] = -1;
   }
 }
 
 __global__ __launch_bounds__(kBigThreads) void dispatch_count_kernel(
-    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int E, int K,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int j_lo, int T, int E, int K,
     int32_t* __restrict__ counts /* [chunks][E] */) {
   __shared__ int s_idx[kChunk * MOE_MAX_TOPK];
   __shared__ int s_hist[MOE_MAX_EXPERTS];
   const int t0 = blockIdx.x * kChunk;
   for (int e = threadIdx.x; e < E; e += kBigThreads) s_hist[e] = 0;
-  stage_chunk(idx, k_t, t0, T, E, K, s_idx, nullptr);
+  stage_chunk(idx, k_t, j_lo, t0, T, E, K, s_idx, nullptr);
   __syncthreads();
   const int n = min(kChunk, T - t0) * K;
   for (int i = threadIdx.x; i < n; i += kBigThreads)
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kBigThreads) void dispatch_count_kernel(
 }
 
 __global__ __launch_bounds__(kBigThreads) void dispatch_scatter_kernel(
-    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int T, int E, int K,
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int j_lo, int T, int E, int K,
     const int32_t* __restrict__ counts, int n_chunks, int32_t* __restrict__ offsets,
     int32_t* __restrict__ sorted_token, int32_t* __restrict__ sorted_rank,
     int32_t* __restrict__ inv_pos) {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kBigThreads) void dispatch_scatter_kernel(
   __shared__ int s_wsum[kBigThreads / 64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = blockIdx.x, t0 = chunk * kChunk;
-  stage_chunk(idx, k_t, t0, T, E, K, s_idx, inv_pos);
+  stage_chunk(idx, k_t, j_lo, t0, T, E, K, s_idx, inv_pos);
   // per expert (one thread each, E <= 256 = kBigThreads): pairs in earlier chunks, pairs in all
   // chunks.  The count table goes through LDS in slabs with coalesced, independent loads (a
   // per-thread loop over global memory would pay one memory latency per chunk).
@@ -222,20 +222,20 @@ __global__ void dispatch_empty_kernel(int E, int32_t* offsets) {
 
 int dispatch_chunks(int T) { return (T + kChunk - 1) / kChunk; }
 
-int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int32_t* offsets,
+int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int j_lo, int32_t* offsets,
                     int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos, int32_t* counts,
                     hipStream_t s) {
   if (c.T == 0) {
     hipLaunchKernelGGL(dispatch_empty_kernel, dim3(1), dim3(256), 0, s, c.E, offsets);
   } else if (c.T <= kSmallT) {
-    hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kSmallThreads), 0, s, idx, k_t, c.T, c.E,
+    hipLaunchKernelGGL(dispatch_small_kernel, dim3(1), dim3(kSmallThreads), 0, s, idx, k_t, j_lo, c.T, c.E,
                        c.k_big, offsets, sorted_token, sorted_rank, inv_pos);
   } else {
     const int n_chunks = dispatch_chunks(c.T);
     hipLaunchKernelGGL(dispatch_count_kernel, dim3((unsigned)n_chunks), dim3(kBigThreads), 0, s, idx, k_t,
-                       c.T, c.E, c.k_big, counts);
+                       j_lo, c.T, c.E, c.k_big, counts);
     hipLaunchKernelGGL(dispatch_scatter_kernel, dim3((unsigned)n_chunks), dim3(kBigThreads), 0, s, idx, k_t,
-                       c.T, c.E, c.k_big, counts, n_chunks, offsets, sorted_token, sorted_rank, inv_pos);
+                       j_lo, c.T, c.E, c.k_big, counts, n_chunks, offsets, sorted_token, sorted_rank, inv_pos);
   }
   return hip_fail(hipGetLastError(), "dispatch launch");
 }

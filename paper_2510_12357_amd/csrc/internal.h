@@ -87,10 +87,14 @@ int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const f
                      hipStream_t s);
 int launch_confidence(const float* z, int T, int V, float* conf, hipStream_t s);
 int dispatch_chunks(int T);          // workgroups (token chunks) of the large-T dispatch
-int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int32_t* offsets,
+// pairs (t, j) with j_lo <= j < k_t[t]
+int launch_dispatch(const moe_config& c, const int32_t* idx, const int32_t* k_t, int j_lo, int32_t* offsets,
                     int32_t* sorted_token, int32_t* sorted_rank, int32_t* inv_pos, int32_t* counts,
                     hipStream_t s);
 int launch_combine(const moe_config& c, const float* y, const float* w, const int32_t* inv_pos,
                    const int32_t* k_t, const float* shared_out, void* out, hipStream_t s);
+// out[t] += sum over the ranks j_lo <= j < k_t[t]; tokens without such ranks are not written
+int launch_combine_add(const moe_config& c, const float* y, const float* w, const int32_t* inv_pos,
+                       const int32_t* k_t, int j_lo, void* out, hipStream_t s);
 
 }  // namespace mm

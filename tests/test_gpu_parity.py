@@ -341,3 +341,92 @@ def test_shared_experts_on_a_side_stream():
         assert rel_err(out_to_f64(b.out), ref["out"]) <= TOL_OUT
     plain = run_gpu_layer(dl, logits=logits)
     assert torch.equal(plain.out.view(torch.int16), b.out.view(torch.int16))
+
+
+# ------------------------------------------------------------------ second pass of Alg. 1 at layer level
+@pytest.mark.parametrize("T,E,K,j_lo", [(1, 8, 2, 1), (64, 60, 4, 2), (64, 60, 4, 0), (64, 60, 4, 4), (257, 64, 8, 4),
+                                        (2048, 64, 8, 4), (1000, 7, 3, 1), (40, 256, 16, 8)])
+def test_dispatch_from_bit_exact(T, E, K, j_lo):
+    g = np.random.default_rng(T + E + K + j_lo)
+    kl = max(1, K // 2)
+    kt = g.choice([kl, K], size=T).astype(np.int32)
+    idx = np.full((T, K), -1, np.int32)
+    for t in range(T):
+        idx[t, :kt[t]] = g.choice(E, size=kt[t], replace=False)
+    cfg = wl.LayerConfig("d", T=T, H=8, E=E, I=8, k_big=K, k_little=kl)
+    b = mm.StepBuffers(cfg)
+    b.topk_idx.copy_(torch.from_numpy(idx))
+    b.k_t.copy_(torch.from_numpy(kt))
+    for buf in (b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos):
+        buf.fill_(-7)
+    mm.moe_dispatch_from(b.c, b.topk_idx, b.k_t, j_lo, b.expert_offsets, b.sorted_token, b.sorted_rank,
+                         b.inv_pos, b.dws, b.dws_bytes)
+    torch.cuda.synchronize()
+    off, st, sr, inv = oracle.dispatch_from(idx, kt, j_lo, E)
+    assert np.array_equal(i32(b.expert_offsets), off)
+    assert np.array_equal(i32(b.sorted_token), st)
+    assert np.array_equal(i32(b.sorted_rank), sr)
+    assert np.array_equal(i32(b.inv_pos), inv)
+
+
+@pytest.mark.parametrize("cfg", [
+    cfg_small(fallback_ratio=0.3, gate_bias_std=0.5),                          # streaming kernels, ragged sizes
+    cfg_small(T=300, E=4, k_big=3, k_little=1, shared_I=(40, 24)),             # tiled kernels
+    wl.CONFIGS["fine60_decode"].with_(T=64),                                   # the decode layer at full size
+    cfg_small(dtype="fp32", fallback_ratio=0.5),
+], ids=["small", "tiled", "fine60_b64", "fp32"])
+def test_little_pass_then_fallback_pass(cfg):
+    tol = TOL_OUT if cfg.dtype == "bf16" else 1e-4
+    layer = wl.make_layer(cfg, seed=3)
+    dl = DeviceLayer(layer)
+    never = torch.full((cfg.T,), float("inf"), dtype=torch.float32, device="cuda")
+    b = mm.StepBuffers(cfg)
+    # pass 1: the little model on every token
+    mm.layer_step(b, dl.x, dl.Wg, dl.gate_bias, never, dl.table, dl.shared)
+    torch.cuda.synchronize()
+    logits = b.logits.cpu().numpy()                                            # selection is compared on the GPU's logits
+    args = (layer.x, layer.Wg, layer.gate_bias, layer.expert_w, cfg.I, layer.shared_w, cfg.shared_I)
+    little = oracle.moe_layer(*args, never.cpu().numpy(), cfg.gamma, cfg.k_big, cfg.k_little, cfg.renorm,
+                              logits=logits)
+    assert np.array_equal(i32(b.k_t), little["k_t"]) and (little["k_t"] == cfg.k_little).all()
+    assert np.array_equal(i32(b.topk_idx), little["topk_idx"])
+    out_little = out_to_f64(b.out)
+    assert rel_err(out_little, little["out"]) <= tol
+    # pass 2: the rejected tokens get the ranks k_little .. k_big-1 on top
+    mm.fallback_step(b, dl.x, dl.conf, dl.table)
+    torch.cuda.synchronize()
+    ref = oracle.fallback_increment(layer.x, layer.expert_w, cfg.I, logits, layer.conf, cfg.gamma,
+                                    cfg.k_big, cfg.k_little, little["out"])
+    for name in ("topk_idx", "k_t", "expert_offsets", "sorted_token", "sorted_rank", "inv_pos"):
+        assert np.array_equal(i32(getattr(b, name)), ref[name]), name
+    assert np.array_equal(b.important.cpu().numpy(), ref["important"])
+    P2 = int(ref["expert_offsets"][-1])
+    assert P2 == int((ref["k_t"] - cfg.k_little).sum())
+    if P2:
+        assert rel_err(b.y[:P2].cpu().numpy(), ref["y"]) <= tol
+    out2 = out_to_f64(b.out)
+    assert rel_err(out2, ref["out"]) <= tol
+    keep = ref["important"] == 0
+    assert np.array_equal(out2[keep], out_little[keep])                        # kept tokens are not rewritten
+    # the two passes give the one-pass layer with k_t per token
+    one = mm.StepBuffers(cfg)
+    one.logits.copy_(b.logits)
+    mm.layer_step(one, dl.x, dl.Wg, dl.gate_bias, dl.conf, dl.table, dl.shared, logits_given=True)
+    torch.cuda.synchronize()
+    assert rel_err(out2, out_to_f64(one.out)) <= tol
+
+
+def test_fallback_pass_argument_checks():
+    b = mm.StepBuffers(cfg_small(renorm=True))
+    with pytest.raises(mm.MoeError) as ei:
+        mm.moe_combine_add(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, 2, b.out)
+    assert ei.value.code == -3                                                 # renormalised weights: not additive
+    ok = mm.StepBuffers(cfg_small())
+    for j_lo in (-1, 5):
+        with pytest.raises(mm.MoeError) as ei:
+            mm.moe_dispatch_from(ok.c, ok.topk_idx, ok.k_t, j_lo, ok.expert_offsets, ok.sorted_token,
+                                 ok.sorted_rank, ok.inv_pos, ok.dws, ok.dws_bytes)
+        assert ei.value.code == -1
+        with pytest.raises(mm.MoeError) as ei:
+            mm.moe_combine_add(ok.c, ok.y, ok.topk_w, ok.inv_pos, ok.k_t, j_lo, ok.out)
+        assert ei.value.code == -1
