@@ -171,6 +171,78 @@ def time_two_pass(mm, torch, cfg, steps: int, warmup: int):
                 speedup_vs_all_big=t_b / (t_l + t_f))
 
 
+def time_offload(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16, prefetch: bool = False):
+    """The layer with its routed experts in pinned host memory behind a cache of n_slots HBM slots
+    (fallback fetch path): steps over different token batches of one layer.  With `prefetch`, the
+    experts the next batch will select are requested while the current step runs (a router output
+    known one step ahead, as for a token whose little pass was discarded).
+    -> step time, hits / misses per step, achieved host-to-device rate."""
+    DEMAND, PREFETCH = 0, 1
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    blob = 3 * cfg.H * cfg.I
+
+    def randn(shape, std):
+        return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+
+    host = torch.empty((cfg.E, blob), dtype=dt).pin_memory()
+    for e in range(cfg.E):
+        host[e].copy_(randn((blob,), cfg.w_std))
+    Wg = randn((cfg.E, cfg.H), cfg.gate_std)
+    shared = [randn((3 * cfg.H * Is,), cfg.w_std) for Is in cfg.shared_I]
+    nb = 8
+    xs = [randn((cfg.T, cfg.H), 1.0) for _ in range(nb)]
+    from paper_2510_12357_amd import workloads as wl
+    confs = [torch.from_numpy(wl.make_confidence(100 + i, cfg.T, cfg.gamma, cfg.fallback_ratio)).cuda() for i in range(nb)]
+    slots = torch.zeros((n_slots, blob), dtype=dt, device="cuda")
+    h = mm.moe_cache_create(cfg.E, blob * host.element_size(), n_slots, host, slots)
+    bufs = [mm.StepBuffers(cfg) for _ in range(2)]
+    wanted = {}
+    if prefetch:                                    # the distinct experts of every batch, in dispatch order
+        for i in range(nb):
+            b = bufs[0]
+            mm.moe_route(b.c, xs[i], Wg, None, confs[i], b.logits, False, b.topk_idx, b.topk_w, b.important, b.k_t)
+            torch.cuda.synchronize()
+            idx = b.topk_idx.cpu().numpy().ravel()
+            seen = []
+            for e in idx[idx >= 0].tolist():
+                if e not in seen:
+                    seen.append(e)
+            wanted[i] = seen
+    hits = misses = nbytes = waves = 0
+    t0 = 0.0
+    try:
+        for it in range(warmup + steps):
+            if it == warmup:
+                torch.cuda.synchronize()
+                hits = misses = nbytes = waves = 0
+                t0 = time.perf_counter()
+            i = it % nb
+            b = bufs[it & 1]
+            mm.moe_route(b.c, xs[i], Wg, None, confs[i], b.logits, False, b.topk_idx, b.topk_w, b.important, b.k_t)
+            mm.moe_dispatch(b.c, b.topk_idx, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                            b.dws, b.dws_bytes)
+            st, nw = mm.moe_expert_ffn_cached(b.c, h, xs[i], b.expert_offsets, b.sorted_token, shared, b.y,
+                                              b.shared_out, b.fws, b.fws_bytes)
+            mm.moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out)
+            if prefetch:
+                _, ps = mm.expert_cache_fetch(h, wanted[(it + 1) % nb], PREFETCH)
+                nbytes += ps.bytes_h2d
+            hits += st.hits; misses += st.misses; nbytes += st.bytes_h2d; waves += nw
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+    finally:
+        mm.moe_cache_sync(h)
+        mm.moe_cache_destroy(h)
+    del host, slots
+    torch.cuda.empty_cache()
+    return dict(us_per_step=dt_s * 1e6 / steps, tokens_per_s=cfg.T * steps / dt_s, slots=n_slots,
+                experts_needed_per_step=(hits + misses) / steps, demand_hit_rate=hits / max(1, hits + misses),
+                waves_per_step=waves / steps, h2d_gb_per_s=nbytes / dt_s / 1e9,
+                h2d_mb_per_step=nbytes / steps / 1e6, prefetch=prefetch)
+
+
 def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: bool = True):
     """-> dict with ms_per_step, tokens/s, per-kernel ms, routing statistics"""
     L = L or auto_layers(cfg)
@@ -350,6 +422,12 @@ def main():
         # the paper's two-pass sequence at layer level (fallback pass = only the ranks above k_little)
         others["two_pass"] = {name: time_two_pass(mm, torch, workload_config(name, args.ratio), k2, w2)
                               for name in ("fine60_decode_b1", "fine60_decode_b64")}
+        # fallback fetch path: routed experts in pinned host memory, 16 HBM slots (host-link bound)
+        from paper_2510_12357_amd import workloads as wl
+        oc = wl.CONFIGS["shared2_offload"].with_(fallback_ratio=args.ratio)
+        # (prefetching the next batch's experts cannot help a single layer whose demand misses already
+        # saturate the link: there is no other layer's compute to hide the copies under)
+        others["shared2_offload_b16"] = dict(demand_only=time_offload(mm, torch, oc, 24, 8))
         extra["other_workloads"] = others
 
     line = dict(metric="MoE-layer tokens/s (decode b=1..64, prefill 2k) + % HBM/MFMA roofline",
