@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="distinct layers cycled (0 = auto)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: throughput over fallback ratio and little-model size "
+                         "(one JSON line per point; the shapes of the paper's Tables 4 and 5)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (scale for the rocprofv3 HBM counters)")
     return ap.parse_args()
@@ -352,6 +355,27 @@ def main():
         raise SystemExit("no GPU visible")
     torch.cuda.set_device(0)
 
+    if args.sweep:
+        import torch
+        from paper_2510_12357_amd import binding as mm
+        from paper_2510_12357_amd import workloads as wl
+        steps, warm = max(20, args.steps // 4), max(5, args.warmup // 2)
+        points = []
+        for T in (1, 64):
+            for r in (0.0, 0.11, 0.21, 0.5, 1.0):                      # Table 4: the threshold acts through r
+                points.append(("fallback_ratio", wl.CONFIGS["fine60_decode"].with_(T=T, fallback_ratio=r)))
+        for T in (1, 64):
+            for kl in (2, 4, 6, 8):                                    # Table 5: experts of the little model, of 8
+                points.append(("k_little", wl.CONFIGS["fine64_prefill"].with_(T=T, k_little=kl, fallback_ratio=args.ratio)))
+        for what, c in points:
+            r = time_workload(mm, torch, c, steps, warm, profile=False)
+            print(json.dumps(dict(sweep=what, layer=c.name, tokens=c.T, k_big=c.k_big, k_little=c.k_little,
+                                  fallback_ratio=c.fallback_ratio, us_per_step=r["ms_per_step"] * 1e3,
+                                  tokens_per_s=r["tokens_per_s"], pairs_per_step=r["P_mean"],
+                                  experts_touched_per_step=r["D_mean"])), flush=True)
+            del r
+            torch.cuda.empty_cache()
+        return
     if args.calibrate_copy:
         n = 1 << 30
         src = torch.full((n,), 3, dtype=torch.uint8, device="cuda")
