@@ -430,3 +430,16 @@ def test_fallback_pass_argument_checks():
         with pytest.raises(mm.MoeError) as ei:
             mm.moe_combine_add(ok.c, ok.y, ok.topk_w, ok.inv_pos, ok.k_t, j_lo, ok.out)
         assert ei.value.code == -1
+
+
+# ------------------------------------------------------------------ kernel switch points and table limits
+@pytest.mark.parametrize("T", [255, 256])
+def test_layer_on_both_sides_of_the_streaming_tiled_switch(T):
+    # 255 tokens run the streaming kernels (8 token blocks per expert), 256 the tiled ones
+    check_layer(cfg_small(T=T, E=5, k_big=3, k_little=1, shared_I=(40,)), seed=7)
+
+
+def test_many_experts_and_largest_top_k():
+    # group tables near their limits: 200 routed experts + 4 shared experts, top-16 of them
+    check_layer(cfg_small(T=33, E=200, k_big=16, k_little=8, shared_I=(24, 40, 8, 16), I=72), seed=8)
+    check_layer(cfg_small(T=3, E=256, k_big=16, k_little=8, shared_I=(), I=40), seed=9)
