@@ -104,15 +104,12 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   const int item = blockIdx.x + j * gridDim.x;
   it.valid = item < total;
   // group of the item = number of prefix entries 1..n_groups that are <= item (the prefix is
-  // nondecreasing); every lane counts a slice, the wave adds up
-  const int C = (n_groups + 63) / 64;
+  // nondecreasing): 64 entries per ballot
   int cnt = 0;
-  for (int c = 0; c < C; ++c) {
-    const int g = lane * C + c + 1;
-    if (g <= n_groups && s_prefix[g] <= item) ++cnt;
+  for (int g0 = 1; g0 <= n_groups; g0 += 64) {
+    const int gg = g0 + lane;
+    cnt += __popcll(__ballot(gg <= n_groups && s_prefix[gg] <= item));
   }
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_xor(cnt, d);
   const int g = it.valid ? __builtin_amdgcn_readfirstlane(cnt) : 0;
   GroupSrc src = s_src[g];
   src.m = uni(src.m); src.row0 = uni(src.row0); src.blob = uni(src.blob);
