@@ -102,6 +102,11 @@ class DeviceLayers:
         return eb * (c.E * 3 * c.H * c.I + sum(3 * c.H * i for i in c.shared_I) + c.E * c.H)
 
 
+def eq1(T: float, T_l: float, T_b: float, r: float) -> float:
+    """Eq. 1 of the paper: speedup = T / (T_l + r * T_b)."""
+    return T / (T_l + r * T_b)
+
+
 def auto_layers(cfg) -> int:
     eb = 2 if cfg.dtype == "bf16" else 4
     per = eb * (cfg.E * 3 * cfg.H * cfg.I + sum(3 * cfg.H * i for i in cfg.shared_I))
@@ -440,7 +445,7 @@ def main():
         tb = time_workload(mm, torch, workload_config("fine60_decode_b1", 1.0), k2, w2, profile=False)
         T_, Tl_, Tb_ = tb["ms_per_step"], tl["ms_per_step"], tb["ms_per_step"]
         others["eq1_b1"] = dict(T_us=T_ * 1e3, T_little_us=Tl_ * 1e3, T_big_us=Tb_ * 1e3,
-                                speedup_r0_11=T_ / (Tl_ + 0.11 * Tb_), speedup_r0_21=T_ / (Tl_ + 0.21 * Tb_),
+                                speedup_r0_11=eq1(T_, Tl_, Tb_, 0.11), speedup_r0_21=eq1(T_, Tl_, Tb_, 0.21),
                                 note="HBM-resident layer on MI355X; the paper's 1.57-1.72x are end-to-end with "
                                      "PCIe offloading on other hardware (context only)")
         # the paper's two-pass sequence at layer level (fallback pass = only the ranks above k_little)

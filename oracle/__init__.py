@@ -231,3 +231,10 @@ def moe_layer(x: np.ndarray, Wg: np.ndarray, gate_bias: Optional[np.ndarray],
     out = combine(y, w, inv, kt, shared, T, H)
     return dict(logits=logits, topk_idx=idx, topk_w=w, important=imp, k_t=kt, expert_offsets=off,
                 sorted_token=st, sorted_rank=sr, inv_pos=inv, y=y, shared=shared, out=out)
+
+
+def eq1_speedup(T: float, T_l: float, T_b: float, r: float) -> float:
+    """Estimated speedup of Eq. 1 (Sec. III-B): a token costs the little model's latency T_l, and with
+    probability r (the fallback ratio) the big model's latency T_b on top; T is the latency of the
+    full model without the method."""
+    return T / (T_l + r * T_b)

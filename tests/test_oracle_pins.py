@@ -454,3 +454,48 @@ def test_little_pass_plus_fallback_increment_is_the_mixed_layer(dtype, r):
     # and against the independent dense evaluation
     dense, _, _ = brute_force_layer(layer, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, False)
     assert np.abs(second["out"] - dense).max() <= 1e-9 * scale
+
+
+# ------------------------------------------------------------------ Eq. 1 against the numbers the paper prints
+def _golden(name):
+    import os
+    rows = []
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append(line.split())
+    return rows
+
+
+def test_eq1_against_the_papers_threshold_sweep():
+    # Table IV gives (r, speedup) pairs of one model.  Eq. 1 fixes their relation: at r = 0 the
+    # speedup is T / T_l; every further row then implies a big-model latency T_b / T, which must be
+    # positive and below 1 (Sec. III-B: the big pass hides its expert loads behind prefetching, so it
+    # is faster than full offloading), and the speedup must fall as r grows.
+    rows = [(float(g), float(r), float(s)) for g, r, s in _golden("table4_threshold_sweep.txt")]
+    assert rows[0][1] == 0.0
+    Tl_over_T = 1.0 / rows[0][2]
+    assert abs(oracle.eq1_speedup(1.0, Tl_over_T, 0.7, 0.0) - rows[0][2]) < 1e-12      # r = 0: T_b is irrelevant
+    prev = rows[0][2]
+    for g, r, s in rows[1:]:
+        Tb_over_T = (1.0 / s - Tl_over_T) / r                                            # Eq. 1 solved for T_b / T
+        assert 0.0 < Tb_over_T < 1.0, (g, Tb_over_T)
+        assert abs(oracle.eq1_speedup(1.0, Tl_over_T, Tb_over_T, r) - s) < 1e-9
+        assert s < prev
+        prev = s
+    # the formula itself, written out once by hand: T = 10, T_l = 5, T_b = 4, r = 0.25 -> 10 / 6
+    assert abs(oracle.eq1_speedup(10.0, 5.0, 4.0, 0.25) - 10.0 / 6.0) < 1e-15
+
+
+def test_eq1_against_the_papers_main_results_and_bench_helper():
+    import bench
+    for model, task, kl, kb, r, s_little, s_mobile in _golden("table3_main_results.txt"):
+        r, s_little, s_mobile = float(r), float(s_little), float(s_mobile)
+        assert int(kl) * 2 == int(kb)                                                    # Sec. III-A: the little model uses K/2 experts
+        Tl_over_T = 1.0 / s_little
+        Tb_over_T = (1.0 / s_mobile - Tl_over_T) / r
+        assert 0.0 < Tb_over_T < 1.0, (model, task, Tb_over_T)
+        for f in (oracle.eq1_speedup, bench.eq1):                                        # the benchmark's own helper agrees
+            assert abs(f(1.0, Tl_over_T, Tb_over_T, r) - s_mobile) < 1e-9
+            assert abs(f(1.0, Tl_over_T, Tb_over_T, 0.0) - s_little) < 1e-9
