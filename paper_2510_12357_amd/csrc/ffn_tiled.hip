@@ -8,16 +8,17 @@
 //
 // Tiling for gfx950 (64-wide waves, v_mfma_f32_32x32x16_bf16):
 //   * workgroup tile (Shape<WM,WN,TM,TN>): default 128 tokens x 256 weight rows, K chunk 64,
-//     4 waves in a 2x2 grid, each wave 64 x 128 outputs = 2x4 MFMA tiles (128 accumulator
-//     registers, 6 fragment reads per 8 MFMAs), one workgroup per CU.  For gate/up the weight
-//     rows of a tile are half rows of W_gate plus the same rows of W_up, arranged so that a wave
-//     holds gate and up of the same outputs and applies SwiGLU in registers.
+//     one workgroup per CU.  Waves 0..3 compute, in a 2x2 grid, each 64 x 128 outputs = 2x4 MFMA
+//     tiles (128 accumulator registers, 6 fragment reads per 8 MFMAs); waves 4..7 only load, so a
+//     full vector-memory queue never stops the MFMA issue.  For gate/up the weight rows of a
+//     tile are half rows of W_gate plus the same rows of W_up, arranged so that a wave holds
+//     gate and up of the same outputs and applies SwiGLU in registers.
 //   * global -> LDS without registers: buffer loads with the LDS destination move 8 tile rows x
 //     128 bytes per instruction (token gather and all ragged edges are offsets beyond the
-//     buffer: zero fill, no branches).  A ring of stages; the loads of the chunk that is
-//     (stages - 1) ahead are issued between the MFMAs of the current chunk, every wave issues the
-//     same number per chunk, so a counted s_waitcnt vmcnt plus one barrier per chunk says "the
-//     current chunk has landed".
+//     buffer: zero fill, no branches).  A ring of stages; a loader issues the chunk that is
+//     (stages - 1) ahead, waits with a counted s_waitcnt vmcnt until its share of the next chunk
+//     has landed, and joins the one barrier per chunk.  The loaders start the next tile while
+//     the computing waves store the epilogue.
 //   * a tile row is 128 bytes in LDS; the 16-byte column c of row r sits at column
 //     c ^ ((r >> 1) & 7), which spreads the 16 rows that a b128 fragment read touches in one
 //     pass over all banks.
@@ -85,14 +86,15 @@ __device__ __forceinline__ void frag_wait(bf16x8 (&f)[N]) {
 template <int WM_, int WN_, int TM_, int TN_>
 struct Shape {
   static constexpr int WM = WM_, WN = WN_, TM = TM_, TN = TN_;
-  static constexpr int kWaves = WM * WN, kThreads = kWaves * 64;
+  static constexpr int kWaves = WM * WN;              // computing waves, and as many loader waves
+  static constexpr int kThreads = 2 * kWaves * 64;
   static constexpr int BM = WM * TM * 32;            // tokens per tile
   static constexpr int BNR = WN * TN * 32;           // weight rows per tile (gate/up: half + half)
   static constexpr int kInsA = BM / kRowsPerIns / kWaves;      // load instructions per wave and chunk
   static constexpr int kInsB = BNR / kRowsPerIns / kWaves;
   static constexpr int kStageBytes = (BM + BNR) * kRowB;
   static_assert(BM % (kRowsPerIns * kWaves) == 0 && BNR % (kRowsPerIns * kWaves) == 0, "tile rows must divide evenly");
-  static_assert(TM == 2 && (TN == 2 || TN == 4), "the fragment reads are written for 2 x 2 or 2 x 4 MFMA tiles per wave");
+  static_assert((TM == 2 || TM == 4) && (TN == 2 || TN == 4), "the fragment reads are written for 2 or 4 MFMA tiles per wave and side");
 };
 
 template <int MODE, typename SH>
@@ -108,7 +110,10 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / SH::WN, wn = wave % SH::WN;
+  const bool loader = wave >= SH::kWaves;                          // waves kWaves.. only move data
+  const int lw = wave - SH::kWaves;                                // index among the loaders
+  const int wm = (wave % SH::kWaves) / SH::WN, wn = wave % SH::WN;
+  constexpr int kAhead = kStages - 1;                              // chunks in flight ahead of the one consumed
   const int n_groups = a.n_routed + (MODE == kDown ? a.n_slabs : a.n_shared);
 
   // ---- tile list: tiles per group, exclusive prefix ----
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
   const int lo_t = (int)((long)total * xcd / 8), hi_t = (int)((long)total * (xcd + 1) / 8);
 
   // ---- per-lane constants of the loads: instruction p of this wave fills tile rows
-  // kRowsPerIns * (wave * kIns + p) + lane / kCols at physical column lane % kCols ----
+  // kRowsPerIns * (lw * kIns + p) + lane / kCols at physical column lane % kCols ----
   const int ld_sub = lane / kCols, ld_pc = lane % kCols;
   // ---- per-lane constants of the fragment reads: row (lane & 31) of a 32-row block, logical
   // column 2 * kk + lane / 32; every block starts at a multiple of 32 rows, so the swizzle key
@@ -168,38 +173,81 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
     const int n0 = n_tile * kOutCols;
     const int K = G.K;
 
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(G.b, G.bbytes);      // tokens
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(G.w0, G.wbytes);     // weights
-    // running byte offsets of this lane's 16 bytes per load instruction (kOob + small stays out
-    // of range), and the logical column (in elements) behind them for the K tail
-    unsigned aoff[kInsA], boff[kInsB];
-    int acol[kInsA], bcol[kInsB];
+    const int nk = (K + BK - 1) / BK;
+
+    if (loader) {
+      // ================= loader waves: nothing but loads into LDS, waits and barriers =================
+      const __amdgpu_buffer_rsrc_t ra = make_rsrc(G.b, G.bbytes);      // tokens
+      const __amdgpu_buffer_rsrc_t rb = make_rsrc(G.w0, G.wbytes);     // weights
+      // running byte offsets of this lane's 16 bytes per load instruction (kOob + small stays out
+      // of range), and the logical column (in elements) behind them for the K tail
+      unsigned aoff[kInsA], boff[kInsB];
+      int acol[kInsA], bcol[kInsB];
 #pragma unroll
-    for (int p = 0; p < kInsA; ++p) {
-      const int tr = kRowsPerIns * (wave * kInsA + p) + ld_sub;      // row of the tile
-      const int r = m0 + tr;
-      const bool val = r < G.m;
-      int row = r;
-      if (G.gather) row = val ? clampi(a.sorted_token[G.row0 + r], 0, a.T - 1) : 0;
-      acol[p] = (ld_pc ^ row_key(tr)) * 8;
-      aoff[p] = (val ? (unsigned)row * (unsigned)G.ldw * 2u : kOob) + (unsigned)acol[p] * 2u;
-    }
-#pragma unroll
-    for (int p = 0; p < kInsB; ++p) {
-      // weight row of the tile: gate/up tiles hold BNR/2 rows of W_gate, then the same rows of W_up
-      const int br = kRowsPerIns * (wave * kInsB + p) + ld_sub;
-      int n;
-      unsigned extra = 0;
-      if (MODE == kGateUp) {
-        n = n0 + (br % (BNR / 2));
-        if (br >= BNR / 2) extra = (unsigned)G.N * (unsigned)G.ldw * 2u;
-      } else {
-        n = n0 + br;
+      for (int p = 0; p < kInsA; ++p) {
+        const int tr = kRowsPerIns * (lw * kInsA + p) + ld_sub;        // row of the tile
+        const int r = m0 + tr;
+        const bool val = r < G.m;
+        int row = r;
+        if (G.gather) row = val ? clampi(a.sorted_token[G.row0 + r], 0, a.T - 1) : 0;
+        acol[p] = (ld_pc ^ row_key(tr)) * 8;
+        aoff[p] = (val ? (unsigned)row * (unsigned)G.ldw * 2u : kOob) + (unsigned)acol[p] * 2u;
       }
-      bcol[p] = (ld_pc ^ row_key(br)) * 8;
-      boff[p] = (n < G.N ? (unsigned)n * (unsigned)G.ldw * 2u + extra : kOob) + (unsigned)bcol[p] * 2u;
+#pragma unroll
+      for (int p = 0; p < kInsB; ++p) {
+        // weight row of the tile: gate/up tiles hold BNR/2 rows of W_gate, then the same rows of W_up
+        const int br = kRowsPerIns * (lw * kInsB + p) + ld_sub;
+        int n;
+        unsigned extra = 0;
+        if (MODE == kGateUp) {
+          n = n0 + (br % (BNR / 2));
+          if (br >= BNR / 2) extra = (unsigned)G.N * (unsigned)G.ldw * 2u;
+        } else {
+          n = n0 + br;
+        }
+        bcol[p] = (ld_pc ^ row_key(br)) * 8;
+        boff[p] = (n < G.N ? (unsigned)n * (unsigned)G.ldw * 2u + extra : kOob) + (unsigned)bcol[p] * 2u;
+      }
+      // chunk `kt` into stage `st`, then step the offsets to the next chunk
+      auto issue = [&](int st, int kt) {
+        char* const sa = s_tiles + st * SH::kStageBytes + (lw * kInsA) * 1024;
+        char* const sb = s_tiles + st * SH::kStageBytes + BM * kRowB + (lw * kInsB) * 1024;
+        const bool full = (kt + 1) * BK <= K;
+#pragma unroll
+        for (int p = 0; p < kInsA; ++p) {
+          const unsigned off = full ? aoff[p] : ((kt * BK + acol[p] < K) ? aoff[p] : kOob);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void*)(sa + p * 1024), 16, (int)off, 0, 0, 0);
+          aoff[p] += kRowB;
+        }
+#pragma unroll
+        for (int p = 0; p < kInsB; ++p) {
+          const unsigned off = full ? boff[p] : ((kt * BK + bcol[p] < K) ? boff[p] : kOob);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void*)(sb + p * 1024), 16, (int)off, 0, 0, 0);
+          boff[p] += kRowB;
+        }
+      };
+      // wait until at most `pending` whole chunks of this wave's loads are still in flight
+      auto wait_chunks = [&](int pending) {
+        static_assert(kStages <= 4, "wait_chunks covers up to two chunks in flight behind the awaited one");
+        if (pending <= 0) MM_WAIT_VMCNT(0);
+        else if (pending == 1) MM_WAIT_VMCNT(kPerChunk);
+        else MM_WAIT_VMCNT(2 * kPerChunk);
+      };
+      int issued = 0, st_is = 0;                             // chunks issued; stage of the next one
+      for (; issued < kAhead && issued < nk; ++issued) { issue(st_is, issued); st_is = st_is + 1 == kStages ? 0 : st_is + 1; }
+      wait_chunks(issued - 1);                               // chunk 0 has landed
+      lds_barrier();                                         // barrier 0
+      for (int kt = 0; kt < nk; ++kt) {
+        // barrier kt was passed: every computing wave is done reading chunk kt-1, whose stage
+        // is the one that chunk kt+kAhead goes to
+        if (issued < nk) { issue(st_is, issued); st_is = st_is + 1 == kStages ? 0 : st_is + 1; ++issued; }
+        wait_chunks(issued - (kt + 2));                      // chunk kt+1 has landed (or nothing is left)
+        lds_barrier();                                       // barrier kt+1
+      }
+      continue;
     }
 
+    // ================= computing waves: fragment reads, MFMAs, barriers, epilogue =================
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -208,35 +256,10 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Loads of one chunk, in kParts portions so that they can sit between the MFMAs.  Portion
-    // `part` of chunk `kt` into stage `st`; chunks past the end only zero-fill.
-    constexpr int kParts = BK / 16;
-    auto issue = [&](int st, int kt, int part) {
-      char* const sa = s_tiles + st * SH::kStageBytes + (wave * kInsA) * 1024;
-      char* const sb = s_tiles + st * SH::kStageBytes + BM * kRowB + (wave * kInsB) * 1024;
-      const bool full = (kt + 1) * BK <= K;
-#pragma unroll
-      for (int p = 0; p < kInsA; ++p)
-        if (p % kParts == part) {
-          const unsigned off = full ? aoff[p] : ((kt * BK + acol[p] < K) ? aoff[p] : kOob);
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_void*)(sa + p * 1024), 16, (int)off, 0, 0, 0);
-        }
-#pragma unroll
-      for (int p = 0; p < kInsB; ++p)
-        if ((kInsA + p) % kParts == part) {
-          const unsigned off = full ? boff[p] : ((kt * BK + bcol[p] < K) ? boff[p] : kOob);
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void*)(sb + p * 1024), 16, (int)off, 0, 0, 0);
-        }
-    };
-    auto advance = [&]() {
-#pragma unroll
-      for (int p = 0; p < kInsA; ++p) aoff[p] += kRowB;
-#pragma unroll
-      for (int p = 0; p < kInsB; ++p) boff[p] += kRowB;
-    };
     auto read_frags = [&](int st, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
       const unsigned col = (((unsigned)(kk * 2 + (lane >> 5))) ^ fkey) * 16u + (unsigned)(st * SH::kStageBytes);
       frag_read2<0, kJ>(fa[0], fa[1], a_rd + col);
+      if constexpr (TM == 4) frag_read2<2 * kJ, 3 * kJ>(fa[2], fa[3], a_rd + col);
       if constexpr (TN == 2) {
         frag_read2<0, kUp>(fb[0], fb[1], b_rd + col);
       } else {
@@ -245,29 +268,17 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
       }
     };
 
-    const int nk = (K + BK - 1) / BK;
-    constexpr int kAhead = kStages - 1;                    // chunks in flight ahead of the one consumed
-    // aoff / boff always point at the chunk that is issued next
-#pragma unroll
-    for (int c = 0; c < kAhead; ++c) {
-#pragma unroll
-      for (int part = 0; part < kParts; ++part) issue(c, c, part);
-      advance();
-    }
-    // The fragments of the first k-step of chunk kt are read at the end of chunk kt-1, right after
-    // the barrier that says "chunk kt has landed": that barrier sits in front of the last
-    // k-step's MFMAs, when every wave has already read all fragments of chunk kt-1, so it also
-    // says "the stage of chunk kt-1 is free".
-    static_assert(kPerChunk % kParts == 0, "equal portions of loads per k-step");
-    constexpr int kPortion = kPerChunk / kParts;
+    // Barrier kt says "chunk kt has landed" (the loaders waited for it) and "chunk kt-1 has been
+    // read" (it sits in front of the last k-step's MFMAs of chunk kt-1, whose fragments were read
+    // one k-step earlier).  The fragments of the first k-step of chunk kt are read right behind
+    // it, under those MFMAs.
+    constexpr int kParts = BK / 16;
     bf16x8 fa[2][TM], fb[2][TN];
-    MM_WAIT_VMCNT((kAhead - 1) * kPerChunk);               // chunk 0 has landed
-    lds_barrier();
+    lds_barrier();                                         // barrier 0
     read_frags(0, 0, fa[0], fb[0]);
     frag_wait(fa[0]); frag_wait(fb[0]);
     int st = 0;                                            // stage of chunk kt
     for (int kt = 0; kt < nk; ++kt) {
-      const int st_ld = st == 0 ? kStages - 1 : st - 1;    // stage of chunk kt-1 = stage of chunk kt+kAhead
       const int st_nx = st + 1 == kStages ? 0 : st + 1;    // stage of chunk kt+1
 #pragma unroll
       for (int kk = 0; kk < kParts; ++kk) {
@@ -275,12 +286,9 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
         if (kk + 1 < kParts) {
           read_frags(st, kk + 1, fa[nxt], fb[nxt]);
         } else {
-          // all of chunk kt+1 except the portions of chunk kt+kAhead issued so far in this chunk
-          MM_WAIT_VMCNT((kAhead - 2) * kPerChunk + (kParts - 1) * kPortion);
-          lds_barrier();
-          read_frags(st_nx, 0, fa[nxt], fb[nxt]);          // zeros / stale data past the last chunk; never used
+          lds_barrier();                                   // barrier kt+1
+          read_frags(st_nx, 0, fa[nxt], fb[nxt]);          // stale data behind the last chunk; never used
         }
-        issue(st_ld, kt + kAhead, kk);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -289,11 +297,8 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
         frag_wait(fa[nxt]); frag_wait(fb[nxt]);
         __builtin_amdgcn_sched_barrier(0);                 // keep the steps apart; free order inside a step
       }
-      advance();
       st = st_nx;
     }
-    MM_WAIT_VMCNT(0);                                      // the zero fills past the end, before stages are reused
-    lds_barrier();
 
     // ---- epilogue: accumulator v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 ----
 #pragma unroll
@@ -321,7 +326,6 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
           }
         }
       }
-    MM_WAIT_VMCNT(0);                                      // stores out of the way of the next tile's counted loads
   }
 }
 
