@@ -238,3 +238,66 @@ def eq1_speedup(T: float, T_l: float, T_b: float, r: float) -> float:
     probability r (the fallback ratio) the big model's latency T_b on top; T is the latency of the
     full model without the method."""
     return T / (T_l + r * T_b)
+
+
+# ----------------------------------------------------------------------------- Alg. 1 as a loop
+def alg1_generate(little_model, big_model, prompt: Sequence[int], gamma: float, eos: int,
+                  max_new: int):
+    """The inference loop of Alg. 1 (Sec. III-A) for one sequence.
+
+    little_model(y) -> (p, h): distribution over the next token after the tokens y, and the router
+    states h of that pass; big_model(y, h) -> p.  While the last token is not <eos>: run the little
+    model; if its largest probability exceeds gamma keep its token, otherwise drop it and take the
+    big model's.  Readings where the paper is silent: "sample" is the most probable token (lowest id
+    among equals), and at most max_new tokens are generated.
+    Returns (y, from_big) with one flag per generated token."""
+    y = [int(t) for t in prompt]
+    from_big = []
+    while y[-1] != eos and len(from_big) < max_new:
+        p_s, h_s = little_model(y)
+        p_s = np.asarray(p_s, np.float64)
+        if float(p_s.max()) > gamma:
+            y.append(int(np.argmax(p_s)))
+            from_big.append(False)
+        else:
+            p_l = np.asarray(big_model(y, h_s), np.float64)
+            y.append(int(np.argmax(p_l)))
+            from_big.append(True)
+    return y, from_big
+
+
+def _round_to_storage(a: np.ndarray, like: np.ndarray) -> np.ndarray:
+    """Rounds double values to the storage type of `like` (float32, or bf16 bits in uint16, both
+    round-to-nearest-even): activations between two layers are stored in the layer's dtype."""
+    f = np.asarray(a, np.float64).astype(np.float32)
+    if like.dtype == np.float32:
+        return f
+    bits = f.view(np.uint32).astype(np.uint64)
+    bits = bits + 0x7FFF + ((bits >> 16) & 1)
+    return (bits >> 16).astype(np.uint16)
+
+
+def toy_lm_next(embed: np.ndarray, layers: Sequence[dict], head: np.ndarray, tokens: np.ndarray,
+                big: np.ndarray, gamma: float, k_big: int, k_little: int, renorm: bool) -> dict:
+    """One decoding step of a tiny attention-free language model built from MoE layers: embedding
+    row of each token, the layers one after the other (a layer's output, rounded to the storage
+    type, is the next layer's input), output head, softmax.  big[t] says whether token t runs the
+    big model (k_big experts in every layer) or the little one (k_little), Sec. III-A.
+    Each entry of `layers` holds Wg, gate_bias, expert_w, I, shared_w, shared_I.
+    Returns p [T,V] (double), lm_logits [T,V] (float32), conf [T], router logits per layer."""
+    tokens = np.asarray(tokens, np.int64)
+    big = np.asarray(big, bool)
+    # Alg. 1 sends a token to the big model when its confidence does not exceed gamma
+    conf = np.where(big, np.float32(-np.inf), np.float32(np.inf)).astype(np.float32)
+    x = np.ascontiguousarray(embed[tokens])
+    h = []
+    for ly in layers:
+        r = moe_layer(x, ly["Wg"], ly["gate_bias"], ly["expert_w"], ly["I"], ly["shared_w"], ly["shared_I"],
+                      conf, gamma, k_big, k_little, renorm)
+        h.append(r["logits"])
+        x = _round_to_storage(r["out"], embed)
+    z = gate_logits(x, head, None)
+    zz = z.astype(np.float64)
+    e = np.exp(zz - zz.max(axis=1, keepdims=True))
+    p = e / e.sum(axis=1, keepdims=True)
+    return dict(p=p, lm_logits=z, conf=token_confidence(z), router_logits=h, x_last=x)

@@ -155,3 +155,33 @@ def make_layer(cfg: LayerConfig, seed: int = 0, experts: bool = True) -> Layer:
         if experts else []
     conf = make_confidence(seed, cfg.T, cfg.gamma, cfg.fallback_ratio)
     return Layer(cfg, x, Wg, bias, ew, sw, conf)
+
+
+# ----------------------------------------------------------------------------- toy language model
+_ID_EMBED, _ID_HEAD, _ID_PROMPT = 7, 8, 9
+
+
+@dataclasses.dataclass
+class ToyLM:
+    """Random weights of a tiny attention-free "language model": token embedding, L MoE layers
+    applied one after the other (the output of a layer is the input of the next), and an output
+    head.  It only exists to drive Alg. 1 (little pass, confidence test, fallback pass) over many
+    decoding steps; the next token depends on the current one alone."""
+    cfg: LayerConfig                    # shape of every layer (cfg.T is not used)
+    V: int                              # vocabulary; token 0 is <eos>
+    embed: np.ndarray                   # [V,H] stored dtype
+    layers: List[Layer]                 # x / conf of these are not used
+    head: np.ndarray                    # [V,H] stored dtype
+
+
+def make_toy_lm(cfg: LayerConfig, V: int, L: int, seed: int = 0, head_std: float = 1.0) -> ToyLM:
+    embed = _store(_normal(seed, _ID_EMBED, (V, cfg.H), 1.0), cfg.dtype)
+    head = _store(_normal(seed, _ID_HEAD, (V, cfg.H), head_std), cfg.dtype)
+    small = cfg.with_(T=1)
+    layers = [make_layer(small, seed=seed * 1009 + 17 * (l + 1)) for l in range(L)]
+    return ToyLM(cfg, V, embed, layers, head)
+
+
+def make_prompt_tokens(seed: int, n: int, V: int) -> np.ndarray:
+    """First tokens of n sequences, never <eos>."""
+    return _rng(seed, _ID_PROMPT).integers(1, V, size=n).astype(np.int64)
