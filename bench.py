@@ -45,6 +45,8 @@ def parse_args():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: throughput over fallback ratio and little-model size "
                          "(one JSON line per point; the shapes of the paper's Tables 4 and 5)")
+    ap.add_argument("--alg1-toy", action="store_true",
+                    help="only the Alg. 1 loop on a toy language model made of the workload's layer; one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (scale for the rocprofv3 HBM counters)")
     return ap.parse_args()
@@ -251,6 +253,74 @@ def time_offload(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16, pre
                 h2d_mb_per_step=nbytes / steps / 1e6, prefetch=prefetch)
 
 
+def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 256, ratio: float = 0.2):
+    """Alg. 1 over many decoding steps on a toy language model of L layers of shape `cfg` (continuous
+    batching, cfg.T slots): accepted tokens per second and the realised fallback ratio, against the
+    same model without the method (every pass a big pass) and against Eq. 1's estimate."""
+    import numpy as np
+    from paper_2510_12357_amd import workloads as wl
+    from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
+    B = cfg.T
+    dl = DeviceLayers(cfg, L, seed=7)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    embed = torch.randn((V, cfg.H), generator=g, device="cuda").to(dt)
+    head32 = torch.randn((V, cfg.H), generator=g, device="cuda")
+    layers = [dict(Wg=dl.Wg[l], gate_bias=dl.bias[l], table=dl.table[l], shared=dl.shared[l]) for l in range(L)]
+    prompts = wl.make_prompt_tokens(3, 1 << 16, V)
+
+    # input calibration: scale the random head so that a fraction `ratio` of the little model's
+    # confidences (over the whole vocabulary as input) does not exceed gamma
+    probe = Alg1Batch(ToyLMDevice(cfg, V, embed, head32.to(dt), layers), B, prompts, max_new=32)
+    zs = []
+    for t0 in range(0, V, B):
+        for b in range(B):
+            probe.tokens[b] = [(t0 + b) % V]
+        probe.big[:] = False
+        probe.step()
+        zs.append(probe.hb.logits.cpu().numpy().astype(np.float64))
+    z = np.concatenate(zs)[:V]
+
+    def frac_below(tau):
+        zz = tau * z
+        c = 1.0 / np.exp(zz - zz.max(axis=1, keepdims=True)).sum(axis=1)
+        return float((c <= cfg.gamma).mean())
+    lo, hi = 1e-3, 1e3
+    for _ in range(60):
+        mid = (lo * hi) ** 0.5
+        lo, hi = (mid, hi) if frac_below(mid) > ratio else (lo, mid)
+    tau = hi
+    dev = ToyLMDevice(cfg, V, embed, (head32 * tau).to(dt), layers)
+    del probe
+
+    def timed(always_big):
+        run = Alg1Batch(dev, B, prompts, max_new=32, always_big=always_big)
+        for _ in range(warmup):
+            run.step()
+        a0, f0, n0 = run.n_accepted, run.n_fallbacks, run.n_steps
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run.step()
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        acc, fall = run.n_accepted - a0, run.n_fallbacks - f0
+        return dict(tokens_per_s=acc / dt_s, us_per_step=dt_s / (run.n_steps - n0) * 1e6, accepted_tokens=acc,
+                    fallback_ratio=fall / max(acc, 1))
+    method, plain = timed(False), timed(True)
+    # Eq. 1 with per-slot pass times: a step costs about the same in either mode here (weights
+    # resident), so T = T_b = the all-big step and T_l = a step of little passes only
+    r = method["fallback_ratio"]
+    return dict(layers=L, slots=B, vocabulary=V, steps=steps, head_scale=tau, calibrated_for_ratio=ratio,
+                realised_fallback_ratio=r, tokens_per_s=method["tokens_per_s"],
+                us_per_step=method["us_per_step"], all_big_tokens_per_s=plain["tokens_per_s"],
+                all_big_us_per_step=plain["us_per_step"],
+                speedup_vs_all_big=method["tokens_per_s"] / plain["tokens_per_s"],
+                note="accepted tokens per second incl. the host round trip per step that takes Alg. 1's decisions; "
+                     "a rejected token costs its slot a second step")
+
+
 def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: bool = True):
     """-> dict with ms_per_step, tokens/s, per-kernel ms, routing statistics"""
     L = L or auto_layers(cfg)
@@ -360,6 +430,14 @@ def main():
         raise SystemExit("no GPU visible")
     torch.cuda.set_device(0)
 
+    if args.alg1_toy:
+        L = args.layers if args.layers > 0 else 4
+        res = time_alg1_toy(mm, torch, workload_config(args.workload, args.ratio), args.steps, args.warmup, L=L,
+                            ratio=args.ratio)
+        print(json.dumps(dict(metric="Alg. 1 on a toy MoE language model: accepted tokens/s", workload=args.workload,
+                              **res)))
+        return
+
     if args.sweep:
         import torch
         from paper_2510_12357_amd import binding as mm
@@ -457,6 +535,10 @@ def main():
         # (prefetching the next batch's experts cannot help a single layer whose demand misses already
         # saturate the link: there is no other layer's compute to hide the copies under)
         others["shared2_offload_b16"] = dict(demand_only=time_offload(mm, torch, oc, 24, 8))
+        torch.cuda.empty_cache()
+        # Alg. 1 end to end on a toy language model made of this layer (realised fallback ratio)
+        others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 10,
+                                              ratio=args.ratio)
         extra["other_workloads"] = others
 
     line = dict(metric="MoE-layer tokens/s (decode b=1..64, prefill 2k) + % HBM/MFMA roofline",

@@ -1,0 +1,158 @@
+"""Alg. 1 driven over many decoding steps on the GPU (toy MoE language model, continuous
+batching), checked against the oracle: every layer of every step from the layer's own input
+(element by element), the output head, the confidence, and the loop's decisions and bookkeeping
+against the oracle's single-sequence loop of Alg. 1."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_12357_amd import workloads as wl
+from gpu_util import TOL_OUT, out_to_f64, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def layers_of(lm):
+    c = lm.cfg
+    return [dict(Wg=l.Wg, gate_bias=l.gate_bias, expert_w=l.expert_w, I=c.I, shared_w=l.shared_w,
+                 shared_I=c.shared_I) for l in lm.layers]
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    """Stored form of a device activation: float32, or bf16 bit patterns as uint16."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16)
+    return t.numpy()
+
+
+def toy(dtype, V=48, L=3, seed=3, head_std=0.25, **kw):
+    base = dict(name="toy", T=1, H=64, E=8, I=48, k_big=4, k_little=2, shared_I=(32,), dtype=dtype,
+                renorm=False, gate_std=0.3, w_std=0.18, gate_bias_std=0.2)
+    base.update(kw)
+    return wl.make_toy_lm(wl.LayerConfig(**base), V=V, L=L, seed=seed, head_std=head_std)
+
+
+@pytest.mark.parametrize("dtype,renorm", [("bf16", False), ("bf16", True), ("fp32", False)])
+def test_alg1_over_many_steps(dtype, renorm):
+    from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
+    lm = toy(dtype, renorm=renorm)
+    c, ls = lm.cfg, layers_of(lm)
+    B, steps, max_new = 12, 40, 9
+    prompts = wl.make_prompt_tokens(11, 200, lm.V)
+    rec = []
+    run = Alg1Batch(ToyLMDevice.upload(lm), B, prompts, max_new, eos=0, record=rec)
+    for _ in range(steps):
+        run.step()
+    torch.cuda.synchronize()
+    st = run.stats()
+    assert st["steps"] == steps and len(rec) == steps
+
+    gamma32 = np.float32(c.gamma)
+    tol = TOL_OUT if dtype == "bf16" else 1e-4
+    agree_rows = total_rows = 0
+    little_p, big_p, little_h, big_h = {}, {}, {}, {}
+    for s, r in enumerate(rec):
+        tok, big = r["tokens_in"], r["big_in"]
+        # ---- the mixed batch: big-mode slots, and only they, are important in every layer
+        x_prev = lm.embed[tok]
+        same_sel = np.ones(B, bool)
+        for l, (ly, g) in enumerate(zip(ls, r["layers"])):
+            x_in = host_bits(g["x_in"])
+            assert np.array_equal(x_in, x_prev), (s, l)            # bit-identical hand-over
+            assert np.array_equal(g["important"].astype(bool), big), (s, l)
+            assert np.array_equal(g["k_t"], np.where(big, c.k_big, c.k_little)), (s, l)
+            # the layer from its own input; selection on the logits the GPU's router produced
+            ref = oracle.moe_layer(x_in, ly["Wg"], ly["gate_bias"], ly["expert_w"], ly["I"], ly["shared_w"],
+                                   ly["shared_I"], r["conf_in"], c.gamma, c.k_big, c.k_little, c.renorm,
+                                   logits=g["logits"])
+            assert np.array_equal(g["topk_idx"], ref["topk_idx"]), (s, l)
+            e = rel_err(out_to_f64(g["out"]), ref["out"])
+            assert e <= tol, (s, l, e)
+            own = oracle.gate_logits(x_in, ly["Wg"], ly["gate_bias"])
+            assert rel_err(g["logits"], own) <= tol, (s, l)
+            same_sel &= (oracle.route(own, r["conf_in"], c.gamma, c.k_big, c.k_little, c.renorm)[0]
+                         == g["topk_idx"]).all(axis=1)
+            x_prev = host_bits(g["out"])
+        # ---- output head, confidence, most probable token
+        z = r["lm_logits"]
+        assert rel_err(z, oracle.gate_logits(x_prev, lm.head, None)) <= tol, s
+        np.testing.assert_allclose(r["conf"], oracle.token_confidence(z), rtol=2e-6, atol=0)
+        assert np.array_equal(r["top"], np.argmax(z, axis=1)), s
+        # ---- the whole step from the tokens alone, where the oracle's own routing agrees
+        full = oracle.toy_lm_next(lm.embed, ls, lm.head, tok, big, c.gamma, c.k_big, c.k_little, c.renorm)
+        total_rows += B
+        agree_rows += int(same_sel.sum())
+        if same_sel.any():
+            # three layers deep, each hand-over rounded to the storage type on both sides: a
+            # norm-wise bound (the element-wise bar is applied layer by layer above)
+            d = z[same_sel].astype(np.float64) - full["lm_logits"][same_sel]
+            assert np.linalg.norm(d) <= 3 * tol * np.linalg.norm(full["lm_logits"][same_sel]), s
+        # ---- what the replay below needs
+        zz = z.astype(np.float64)
+        p = np.exp(zz - zz.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        for b in range(B):
+            if r["seq_id"][b] < 0:
+                continue
+            key = (r["seq_id"][b], r["pos"][b])
+            pb = p[b].copy()
+            pb[int(np.argmax(z[b]))] = float(r["conf"][b])      # the decision is taken on the fp32 confidence
+            (big_p if big[b] else little_p)[key] = pb
+            (big_h if big[b] else little_h)[key] = r["layers"][0]["logits"][b].copy()
+    assert agree_rows > 0.8 * total_rows
+
+    # ---- decisions and bookkeeping: every sequence is what Alg. 1 generates from the recorded
+    # distributions, run one sequence at a time
+    seqs = list(run.finished) + [(run.seq_id[b], run.tokens[b], run.from_big[b]) for b in range(B)
+                                 if run.seq_id[b] >= 0]
+    assert len(run.finished) >= 3
+    n_tok = n_fall = 0
+    for sid, tokens, from_big in seqs:
+        def little_model(y):
+            return little_p[(sid, len(y))], little_h[(sid, len(y))]
+
+        def big_model(y, h):
+            # the router states of the rejected pass are those the big pass computes itself
+            assert np.array_equal(h, big_h[(sid, len(y))])
+            return big_p[(sid, len(y))]
+
+        n = len(from_big)
+        y, fb = oracle.alg1_generate(little_model, big_model, [tokens[0]], float(gamma32), 0, max_new=n)
+        assert y == tokens and fb == from_big, sid
+        assert tokens[0] == int(prompts[sid])
+        if (sid, tokens, from_big) in run.finished:
+            assert tokens[-1] == 0 or n == max_new
+        n_tok += n
+        n_fall += sum(fb)
+    # a slot that was rejected in the last step has a fallback that is not yet a token
+    pending = int(run.big.sum())
+    assert st["accepted_tokens"] == n_tok and st["fallbacks"] == n_fall + pending
+    assert 0 < n_fall < n_tok
+    assert st["little_passes"] + st["big_passes"] == int(sum(sum(1 for q in r["seq_id"] if q >= 0) for r in rec))
+    assert st["big_passes"] == n_fall
+
+
+def test_gamma_limits_on_the_gpu():
+    """gamma = 1: every token falls back (no probability exceeds 1), two passes per token; a gamma
+    below every confidence: the little model alone."""
+    from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
+    for gamma, expect_all_big in ((1.0, True), (1e-6, False)):
+        lm = toy("bf16", L=2, gamma=gamma)
+        run = Alg1Batch(ToyLMDevice.upload(lm), 8, wl.make_prompt_tokens(5, 64, lm.V), max_new=6)
+        for _ in range(12):
+            run.step()
+        st = run.stats()
+        flags = [f for _, _, fb in run.finished for f in fb]
+        assert len(flags) > 0 and all(f == expect_all_big for f in flags)
+        if expect_all_big:
+            assert st["big_passes"] == st["accepted_tokens"] and st["little_passes"] == st["fallbacks"]
+        else:
+            assert st["fallbacks"] == 0 and st["big_passes"] == 0
+
+
+def test_vocabulary_limit():
+    from paper_2510_12357_amd.alg1_driver import ToyLMDevice
+    lm = toy("bf16", V=300, L=1)
+    with pytest.raises(ValueError):
+        ToyLMDevice.upload(lm)
