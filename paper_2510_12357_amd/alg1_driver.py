@@ -13,6 +13,14 @@ runs all slots together as one mixed batch: the per-token confidence handed to t
 +inf for little-mode slots (not important) and the rejected confidence (<= gamma: important) for
 big-mode slots, so that the layer kernels see exactly the mixed k of the paper's method.  A
 finished sequence (<eos> or the length cap) is replaced by the next prompt at once.
+
+Offloaded experts (Sec. II-B, III-B): with one expert cache per layer the routed experts live in
+pinned host memory and every layer fetches what its router selected.  For a slot in big mode the
+router logits of its rejected little pass are known for ALL layers before the big pass starts, so
+the experts they name (k_big per layer, the selection rule of the layer itself) are prefetched
+`prefetch_distance` layers ahead of the layer that is being computed: before layer l of a step runs,
+the prefetch for layer l + d is issued (layers 0 .. d-1 at the start of the step).  Little-mode slots
+have no prediction; their experts are demand misses.
 """
 from __future__ import annotations
 
@@ -59,6 +67,29 @@ class ToyLMDevice:
         return cls(cfg, lm.V, mm.to_device(lm.embed, cfg, device), mm.to_device(lm.head, cfg, device), layers)
 
 
+class LayerCaches:
+    """One expert cache per layer: `host_experts[l]` is a pinned host tensor [E, blob elements] with
+    the layer's expert blobs, each cache gets n_slots HBM slots of one blob."""
+
+    def __init__(self, host_experts: list, n_slots: int, device="cuda"):
+        self.handles, self.slots, self.host = [], [], host_experts
+        try:
+            for h in host_experts:
+                E, blob = h.shape
+                dev = torch.zeros((n_slots, blob), dtype=h.dtype, device=device)
+                self.slots.append(dev)
+                self.handles.append(mm.moe_cache_create(E, blob * h.element_size(), n_slots, h, dev))
+        except Exception:
+            self.close()
+            raise
+
+    def close(self) -> None:
+        for h in self.handles:
+            mm.moe_cache_sync(h)
+            mm.moe_cache_destroy(h)
+        self.handles = []
+
+
 class Alg1Batch:
     """B sequences advancing together.  `prompts` holds the first token of every sequence that will
     ever be started (the run ends when they are used up and all slots have drained, or after the
@@ -67,8 +98,14 @@ class Alg1Batch:
     token kept): the T of Eq. 1."""
 
     def __init__(self, dev: ToyLMDevice, B: int, prompts: np.ndarray, max_new: int, eos: int = 0,
-                 record: Optional[list] = None, always_big: bool = False):
+                 record: Optional[list] = None, always_big: bool = False, caches: Optional[list] = None,
+                 prefetch_distance: int = 0, fetch_log: Optional[list] = None):
         self.dev, self.B, self.max_new, self.eos, self.record = dev, B, max_new, eos, record
+        if caches is not None and len(caches) != len(dev.layers):
+            raise ValueError("one expert cache per layer")
+        if prefetch_distance < 0:
+            raise ValueError("prefetch_distance must not be negative")
+        self.caches, self.distance, self.fetch_log = caches, prefetch_distance, fetch_log
         self.always_big = always_big        # the model without the method: one big pass per token
         self.gamma = np.float32(dev.cfg.gamma)
         self.prompts, self.next_prompt = np.asarray(prompts, np.int64), 0
@@ -86,6 +123,14 @@ class Alg1Batch:
         self.rejected_conf = np.zeros(B, np.float32)
         self.finished = []                  # (seq_id, tokens, from_big)
         self.n_steps = self.n_accepted = self.n_fallbacks = self.n_little = self.n_big = 0
+        # offloading: router logits of a slot's rejected pass for every layer, the prediction made
+        # from them (experts per layer, most likely first), and the counters
+        L, E = len(dev.layers), dev.cfg.E
+        self.router_states = np.zeros((L, B, E), np.float32)
+        self.predicted: List[List[int]] = [[] for _ in range(L)]
+        self.pb = mm.StepBuffers(dev.cfg, L * B, d) if caches is not None and prefetch_distance > 0 else None
+        self.demand_hits = self.demand_misses = self.prefetch_copies = self.prefetch_dropped = 0
+        self.bytes_h2d = self.waves = 0
         for b in range(B):
             self._refill(b)
 
@@ -118,8 +163,22 @@ class Alg1Batch:
         self.conf_dev.copy_(torch.from_numpy(conf_in))
         x = dev.embed.index_select(0, self.tok_dev)
         xs = [x]
-        for ly, b in zip(dev.layers, self.bufs):
-            x = mm.layer_step(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev, ly["table"], ly["shared"])
+        L = len(dev.layers)
+        if self.caches is not None and self.distance > 0:
+            for l in range(min(self.distance, L)):
+                self._prefetch(l)
+        for l, (ly, b) in enumerate(zip(dev.layers, self.bufs)):
+            if self.caches is None:
+                x = mm.layer_step(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev, ly["table"], ly["shared"])
+            else:
+                if self.distance > 0 and l + self.distance < L:
+                    self._prefetch(l + self.distance)
+                x, st, waves = mm.layer_step_cached(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev,
+                                                    self.caches[l], ly["shared"])
+                self.demand_hits += st.hits
+                self.demand_misses += st.misses
+                self.bytes_h2d += st.bytes_h2d
+                self.waves += waves
             xs.append(x)
         hb = self.hb
         mm.moe_route(hb.c, x, dev.head, None, None, hb.logits, False, hb.topk_idx, hb.topk_w, hb.important,
@@ -137,6 +196,7 @@ class Alg1Batch:
                         for xi, b in zip(xs, self.bufs)],
                 lm_logits=hb.logits.cpu().numpy(), conf=conf.copy(), top=top.copy()))
         self.n_steps += 1
+        rejected: List[int] = []
         for b in range(B):
             if not act[b]:
                 continue
@@ -149,6 +209,7 @@ class Alg1Batch:
                 self.big[b] = True
                 self.rejected_conf[b] = conf[b]
                 self.n_fallbacks += 1
+                rejected.append(b)
                 continue
             self.tokens[b].append(int(top[b]))
             self.from_big[b].append(bool(self.big[b]))
@@ -157,9 +218,50 @@ class Alg1Batch:
             if int(top[b]) == self.eos or len(self.from_big[b]) >= self.max_new:
                 self.finished.append((self.seq_id[b], self.tokens[b], self.from_big[b]))
                 self._refill(b)
+        if self.caches is not None:
+            self._predict(rejected)
+
+    # ---- prefetch from the router states of the rejected passes (Sec. III-B)
+    def _predict(self, rejected: List[int]) -> None:
+        """The experts the big pass of the slots now in big mode will most likely select, per layer:
+        the layer's own selection rule (k_big experts, logit descending, id ascending) on the router
+        logits of the rejected little pass; most likely rank first, each expert once."""
+        L, B, K = len(self.dev.layers), self.B, self.dev.cfg.k_big
+        self.predicted = [[] for _ in range(L)]
+        if self.pb is None or self.always_big or not rejected:
+            return                          # a slot is in big mode only right after its rejection
+        slots = rejected
+        for l, b in enumerate(self.bufs):
+            self.router_states[l, rejected] = b.logits[rejected].cpu().numpy()
+        pb = self.pb
+        pb.logits.copy_(torch.from_numpy(self.router_states.reshape(L * B, -1)))
+        mm.moe_route(pb.c, None, None, None, None, pb.logits, True, pb.topk_idx, pb.topk_w, pb.important,
+                     pb.k_t, None)
+        idx = pb.topk_idx.cpu().numpy().reshape(L, B, K)
+        for l in range(L):
+            seen = []
+            for j in range(K):
+                for b in slots:
+                    e = int(idx[l, b, j])
+                    if e not in seen:
+                        seen.append(e)
+            self.predicted[l] = seen
+
+    def _prefetch(self, l: int) -> None:
+        ids = self.predicted[l]
+        if not ids:
+            return
+        slots, st = mm.expert_cache_fetch(self.caches[l], ids, 1)
+        self.prefetch_copies += st.misses
+        self.prefetch_dropped += st.dropped
+        self.bytes_h2d += st.bytes_h2d
+        if self.fetch_log is not None:
+            self.fetch_log.append((self.n_steps, l, list(ids), slots, (st.hits, st.misses, st.dropped)))
 
     def stats(self) -> dict:
         return dict(steps=self.n_steps, accepted_tokens=self.n_accepted, fallbacks=self.n_fallbacks,
                     little_passes=self.n_little, big_passes=self.n_big,
                     fallback_ratio=self.n_fallbacks / max(self.n_accepted, 1),
-                    finished_sequences=len(self.finished))
+                    finished_sequences=len(self.finished), demand_hits=self.demand_hits,
+                    demand_misses=self.demand_misses, prefetch_copies=self.prefetch_copies,
+                    prefetch_dropped=self.prefetch_dropped, bytes_h2d=self.bytes_h2d, waves=self.waves)

@@ -357,3 +357,16 @@ def fallback_step(b: StepBuffers, x, conf, expert_table, stream=None) -> torch.T
                    b.shared_out, b.fws, b.fws_bytes, stream)
     moe_combine_add(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, kl, b.out, stream)
     return b.out
+
+
+def layer_step_cached(b: StepBuffers, x, Wg, gate_bias, conf, cache: int, shared_w, stream=None):
+    """One step of the layer whose routed experts live in pinned host memory behind `cache`
+    (Sec. II-B): router and dispatch as in layer_step, then the execution stage through the cache
+    (the host waits once for the router's decision).  -> (b.out, summed fetch statistics, waves)."""
+    moe_route(b.c, x, Wg, gate_bias, conf, b.logits, False, b.topk_idx, b.topk_w, b.important, b.k_t, stream)
+    moe_dispatch(b.c, b.topk_idx, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                 b.dws, b.dws_bytes, stream)
+    st, waves = moe_expert_ffn_cached(b.c, cache, x, b.expert_offsets, b.sorted_token, shared_w, b.y,
+                                      b.shared_out, b.fws, b.fws_bytes, stream)
+    moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out, stream)
+    return b.out, st, waves

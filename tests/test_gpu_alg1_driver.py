@@ -156,3 +156,103 @@ def test_vocabulary_limit():
     lm = toy("bf16", V=300, L=1)
     with pytest.raises(ValueError):
         ToyLMDevice.upload(lm)
+
+
+# ------------------------------------------------------------------ experts in host memory, prefetch ahead
+def pinned_experts(lm):
+    from paper_2510_12357_amd import binding as mm
+    return [torch.stack([mm.to_device(b, lm.cfg, "cpu") for b in l.expert_w]).pin_memory() for l in lm.layers]
+
+
+def run_driver(lm, B, steps, max_new, prompts, caches=None, d=0):
+    from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
+    rec, log = [], []
+    run = Alg1Batch(ToyLMDevice.upload(lm), B, prompts, max_new, record=rec,
+                    caches=None if caches is None else caches.handles, prefetch_distance=d, fetch_log=log)
+    for _ in range(steps):
+        run.step()
+    torch.cuda.synchronize()
+    return run, rec, log
+
+
+def test_offloaded_model_equals_resident_model_and_cache_follows_the_policy():
+    """Sec. II-B / III-B over several layers: the experts of every layer live in pinned host memory
+    behind a small cache; the experts of a rejected slot's big pass are prefetched d layers ahead
+    from the router states of the rejected pass.  Nothing of that may change a single bit of the
+    results, every fetch must follow the cache policy (host-only model), the predictions must be
+    the layer's own selection rule on the rejected pass's logits, and prefetching must turn
+    demand misses into hits."""
+    from oracle.cache_model import DEMAND, PREFETCH, CacheModel
+    from paper_2510_12357_amd import binding as mm
+    from paper_2510_12357_amd.alg1_driver import LayerCaches
+    lm = toy("bf16", L=4, E=32, head_std=0.3)
+    c = lm.cfg
+    B, steps, max_new, n_slots = 4, 40, 8, 16
+    prompts = wl.make_prompt_tokens(21, 200, lm.V)
+    base, rec0, _ = run_driver(lm, B, steps, max_new, prompts)
+    assert base.stats()["fallbacks"] >= 5
+    host = pinned_experts(lm)
+    misses = {}
+    for d in (0, 1, 2, 7):
+        caches = LayerCaches(host, n_slots)
+        try:
+            run, rec, log = run_driver(lm, B, steps, max_new, prompts, caches, d)
+            st = run.stats()
+            # ---- bit-identical to the model with all experts resident
+            assert run.finished == base.finished and run.tokens == base.tokens
+            for r, r0 in zip(rec, rec0):
+                assert np.array_equal(r["conf"], r0["conf"]) and np.array_equal(r["top"], r0["top"])
+                for g, g0 in zip(r["layers"], r0["layers"]):
+                    assert np.array_equal(g["topk_idx"], g0["topk_idx"])
+                    assert torch.equal(g["out"], g0["out"])
+            # ---- the predictions: k_big experts of the rejected pass's router logits, most likely rank first
+            by_call = {(s, l): (ids, slots, cnt) for s, l, ids, slots, cnt in log}
+            assert (len(log) > 0) == (d > 0)
+            for (s, l), (ids, _, _) in by_call.items():
+                rej = [b for b in range(B) if rec[s]["big_in"][b] and not rec[s - 1]["big_in"][b]]
+                assert rej == [b for b in range(B) if rec[s]["big_in"][b]]
+                idx = oracle.route(rec[s - 1]["layers"][l]["logits"][rej], None, c.gamma, c.k_big, c.k_little,
+                                   c.renorm)[0]
+                want = []
+                for j in range(c.k_big):
+                    for e in idx[:, j]:
+                        if int(e) not in want:
+                            want.append(int(e))
+                assert ids == want, (s, l)
+            if d > 0:
+                # every layer of every step that has a slot in big mode gets its prefetch, once
+                expect = {(s, l) for s in range(1, steps) if rec[s]["big_in"].any() for l in range(len(lm.layers))}
+                assert set(by_call) == expect
+            # ---- every fetch against the host-only model of the policy
+            hits = miss = 0
+            for l in range(len(lm.layers)):
+                model = CacheModel(c.E, n_slots)
+                for s in range(steps):
+                    if (s, l) in by_call:
+                        ids, slots, cnt = by_call[(s, l)]
+                        ref_slots, h, m, dr = model.fetch(ids, PREFETCH)
+                        assert slots == ref_slots and cnt == (h, m, dr), (d, s, l)
+                    g = rec[s]["layers"][l]
+                    need = sorted({int(e) for e in g["topk_idx"].ravel() if e >= 0})
+                    order = [e for e in need if model.slot_of(e) >= 0] + \
+                            [e for e in need if model.slot_of(e) < 0]
+                    for i in range(0, len(order), n_slots):
+                        _, h, m, _ = model.fetch(order[i:i + n_slots], DEMAND)
+                        hits, miss = hits + h, miss + m
+                assert mm.moe_cache_snapshot(caches.handles[l], n_slots) == model.slot_expert, (d, l)
+            assert (st["demand_hits"], st["demand_misses"]) == (hits, miss)
+            misses[d] = miss
+            assert (st["prefetch_copies"] > 0) == (d > 0)
+        finally:
+            caches.close()
+    assert misses[1] < misses[0] and misses[2] < misses[0] and misses[7] < misses[0]
+
+
+def test_driver_argument_checks():
+    from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
+    lm = toy("bf16", L=2)
+    dev = ToyLMDevice.upload(lm)
+    with pytest.raises(ValueError):
+        Alg1Batch(dev, 4, wl.make_prompt_tokens(1, 8, lm.V), 4, caches=[1])
+    with pytest.raises(ValueError):
+        Alg1Batch(dev, 4, wl.make_prompt_tokens(1, 8, lm.V), 4, prefetch_distance=-1)
