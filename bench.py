@@ -47,6 +47,8 @@ def parse_args():
                          "(one JSON line per point; the shapes of the paper's Tables 4 and 5)")
     ap.add_argument("--alg1-toy", action="store_true",
                     help="only the Alg. 1 loop on a toy language model made of the workload's layer; one JSON line")
+    ap.add_argument("--alg1-offload", action="store_true",
+                    help="only the Alg. 1 loop with the experts in host memory, prefetch distance 0..3; one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of known size (scale for the rocprofv3 HBM counters)")
     return ap.parse_args()
@@ -272,7 +274,7 @@ def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 
 
     # input calibration: scale the random head so that a fraction `ratio` of the little model's
     # confidences (over the whole vocabulary as input) does not exceed gamma
-    probe = Alg1Batch(ToyLMDevice(cfg, V, embed, head32.to(dt), layers), B, prompts, max_new=32)
+    probe = Alg1Batch(ToyLMDevice(cfg, V, embed, head32.to(dt), layers, norm=True), B, prompts, max_new=32)
     zs = []
     for t0 in range(0, V, B):
         for b in range(B):
@@ -291,7 +293,7 @@ def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 
         mid = (lo * hi) ** 0.5
         lo, hi = (mid, hi) if frac_below(mid) > ratio else (lo, mid)
     tau = hi
-    dev = ToyLMDevice(cfg, V, embed, (head32 * tau).to(dt), layers)
+    dev = ToyLMDevice(cfg, V, embed, (head32 * tau).to(dt), layers, norm=True)
     del probe
 
     def timed(always_big):
@@ -319,6 +321,93 @@ def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 
                 speedup_vs_all_big=method["tokens_per_s"] / plain["tokens_per_s"],
                 note="accepted tokens per second incl. the host round trip per step that takes Alg. 1's decisions; "
                      "a rejected token costs its slot a second step")
+
+
+def time_alg1_offload(mm, torch, cfg, steps: int, warmup: int, L: int, n_slots: int, V: int = 256,
+                      ratio: float = 0.2, distances=(0, 1, 2, 3)):
+    """Alg. 1 on a toy language model whose routed experts live in pinned host memory (one cache of
+    n_slots per layer): the same run for several prefetch distances d (Sec. III-B: the experts of a
+    rejected slot's big pass are requested d layers ahead of the layer being computed)."""
+    import numpy as np
+    from paper_2510_12357_amd import workloads as wl
+    from paper_2510_12357_amd.alg1_driver import Alg1Batch, LayerCaches, ToyLMDevice
+    B = cfg.T
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    blob = 3 * cfg.H * cfg.I
+
+    def randn(shape, std):
+        return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+    host, layers = [], []
+    for l in range(L):
+        h = torch.empty((cfg.E, blob), dtype=dt).pin_memory()
+        for e in range(cfg.E):
+            h[e].copy_(randn((blob,), cfg.w_std))
+        host.append(h)
+        layers.append(dict(Wg=randn((cfg.E, cfg.H), cfg.gate_std), gate_bias=None, table=None,
+                           shared=[randn((3 * cfg.H * Is,), cfg.w_std) for Is in cfg.shared_I]))
+    embed = randn((V, cfg.H), 1.0)
+    head32 = torch.randn((V, cfg.H), generator=g, device="cuda")
+    prompts = wl.make_prompt_tokens(5, 1 << 16, V)
+
+    def run(d, head, n, warm):
+        caches = LayerCaches(host, n_slots)
+        try:
+            r = Alg1Batch(ToyLMDevice(cfg, V, embed, head, layers, norm=True), B, prompts, max_new=32, caches=caches.handles,
+                          prefetch_distance=d)
+            for _ in range(warm):
+                r.step()
+            s0 = r.stats()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n):
+                r.step()
+            torch.cuda.synchronize()
+            dt_s = time.perf_counter() - t0
+            s1 = r.stats()
+            return r, {k: s1[k] - s0[k] for k in s1 if k != "fallback_ratio"}, dt_s
+        finally:
+            caches.close()
+
+    # input calibration as in time_alg1_toy: scale the head for the wanted share of rejected passes
+    caches = LayerCaches(host, n_slots)
+    try:
+        probe = Alg1Batch(ToyLMDevice(cfg, V, embed, head32.to(dt), layers, norm=True), B, prompts, max_new=32,
+                          caches=caches.handles)
+        zs = []
+        for t0 in range(0, V, B):
+            for b in range(B):
+                probe.tokens[b] = [(t0 + b) % V]
+            probe.big[:] = False
+            probe.step()
+            zs.append(probe.hb.logits.cpu().numpy().astype(np.float64))
+    finally:
+        caches.close()
+    z = np.concatenate(zs)[:V]
+
+    def frac_below(tau):
+        zz = tau * z
+        c = 1.0 / np.exp(zz - zz.max(axis=1, keepdims=True)).sum(axis=1)
+        return float((c <= cfg.gamma).mean())
+    lo, hi = 1e-3, 1e3
+    for _ in range(60):
+        mid = (lo * hi) ** 0.5
+        lo, hi = (mid, hi) if frac_below(mid) > ratio else (lo, mid)
+    head = (head32 * hi).to(dt)
+
+    out = dict(layers=L, head_scale=hi, slots_per_layer=n_slots, batch_slots=B, vocabulary=V, blob_mb=blob * host[0].element_size() / 1e6,
+               steps=steps, by_distance={})
+    for d in distances:
+        _, s, dt_s = run(d, head, steps, warmup)
+        need = s["demand_hits"] + s["demand_misses"]
+        out["by_distance"][str(d)] = dict(
+            us_per_step=dt_s / steps * 1e6, accepted_tokens_per_s=s["accepted_tokens"] / dt_s,
+            fallback_ratio=s["fallbacks"] / max(1, s["accepted_tokens"]),
+            demand_hit_rate=s["demand_hits"] / max(1, need), experts_needed_per_step=need / steps,
+            prefetch_copies_per_step=s["prefetch_copies"] / steps, prefetch_dropped_per_step=s["prefetch_dropped"] / steps,
+            h2d_gb_per_s=s["bytes_h2d"] / dt_s / 1e9, h2d_mb_per_step=s["bytes_h2d"] / steps / 1e6)
+    return out
 
 
 def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: bool = True):
@@ -436,6 +525,19 @@ def main():
                             ratio=args.ratio)
         print(json.dumps(dict(metric="Alg. 1 on a toy MoE language model: accepted tokens/s", workload=args.workload,
                               **res)))
+        return
+
+    if args.alg1_offload:
+        from paper_2510_12357_amd import workloads as wl
+        L = args.layers if args.layers > 0 else 6
+        real = wl.CONFIGS["shared2_offload"].with_(fallback_ratio=args.ratio)
+        # a layer whose expert is 1.5 MB instead of 17 MB: copy time of a step's experts of the same
+        # order as the step's compute, the regime in which the prefetch distance matters
+        light = real.with_(name="light_offload", H=1024, I=256, shared_I=(256, 256))
+        res = dict(metric="Alg. 1 with offloaded experts: step time by prefetch distance",
+                   shared2_offload=time_alg1_offload(mm, torch, real, args.steps, args.warmup, L, 48, ratio=args.ratio),
+                   light_offload=time_alg1_offload(mm, torch, light, args.steps, args.warmup, L, 48, ratio=args.ratio))
+        print(json.dumps(res))
         return
 
     if args.sweep:

@@ -277,12 +277,26 @@ def _round_to_storage(a: np.ndarray, like: np.ndarray) -> np.ndarray:
     return (bits >> 16).astype(np.uint16)
 
 
+def rms_normalize(x: np.ndarray) -> np.ndarray:
+    """Rows of a stored activation divided by sqrt(mean of squares + 1e-6), stored in the same type."""
+    x = _c(x)
+    if x.dtype == np.uint16:
+        f = (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    else:
+        f = x.astype(np.float64)
+    y = f / np.sqrt((f * f).mean(axis=1, keepdims=True) + 1e-6)
+    return _round_to_storage(y, x)
+
+
 def toy_lm_next(embed: np.ndarray, layers: Sequence[dict], head: np.ndarray, tokens: np.ndarray,
-                big: np.ndarray, gamma: float, k_big: int, k_little: int, renorm: bool) -> dict:
+                big: np.ndarray, gamma: float, k_big: int, k_little: int, renorm: bool,
+                norm: bool = False) -> dict:
     """One decoding step of a tiny attention-free language model built from MoE layers: embedding
     row of each token, the layers one after the other (a layer's output, rounded to the storage
     type, is the next layer's input), output head, softmax.  big[t] says whether token t runs the
-    big model (k_big experts in every layer) or the little one (k_little), Sec. III-A.
+    big model (k_big experts in every layer) or the little one (k_little), Sec. III-A.  With `norm`
+    every layer's stored output row is divided by sqrt(mean of its squares + 1e-6) and stored again
+    (a SwiGLU layer is quadratic in its input, so a deep stack without it collapses or blows up).
     Each entry of `layers` holds Wg, gate_bias, expert_w, I, shared_w, shared_I.
     Returns p [T,V] (double), lm_logits [T,V] (float32), conf [T], router logits per layer."""
     tokens = np.asarray(tokens, np.int64)
@@ -296,6 +310,8 @@ def toy_lm_next(embed: np.ndarray, layers: Sequence[dict], head: np.ndarray, tok
                       conf, gamma, k_big, k_little, renorm)
         h.append(r["logits"])
         x = _round_to_storage(r["out"], embed)
+        if norm:
+            x = rms_normalize(x)
     z = gate_logits(x, head, None)
     zz = z.astype(np.float64)
     e = np.exp(zz - zz.max(axis=1, keepdims=True))

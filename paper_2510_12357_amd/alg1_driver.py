@@ -1,10 +1,12 @@
 """Alg. 1 over a batch of sequences (continuous batching) on a toy MoE language model.
 
-Every arithmetic step runs in the library's kernels: the layers are `layer_step` calls; the output
-head reuses `moe_route` with the vocabulary in the place of the experts (its logits are
+The method's arithmetic runs in the library's kernels: the layers are `layer_step` calls; the
+output head reuses `moe_route` with the vocabulary in the place of the experts (its logits are
 x . head^T and its rank-0 selection is the most probable token, lowest id among equals); the
-confidence is `moe_token_confidence`.  torch only gathers embedding rows and carries a few small
-arrays to the host, where the loop of Alg. 1 takes its decisions.
+confidence is `moe_token_confidence`.  torch gathers embedding rows, optionally rescales a layer's
+output rows to unit RMS (the toy model's glue between layers: a stack of SwiGLU layers is quadratic
+in its input and needs it beyond a few layers) and carries a few small arrays to the host, where the
+loop of Alg. 1 takes its decisions.
 
 Scheduling (Sec. III-A, Alg. 1, batched): each slot of the batch holds one sequence that is either
 in little mode (its next token is tried with k_little experts per layer) or in big mode (the
@@ -38,11 +40,12 @@ class ToyLMDevice:
     and per layer a dict with Wg, gate_bias (or None), table (int64 device pointers of the E expert
     blobs) and shared (list of blobs)."""
 
-    def __init__(self, cfg: wl.LayerConfig, V: int, embed: torch.Tensor, head: torch.Tensor, layers: list):
+    def __init__(self, cfg: wl.LayerConfig, V: int, embed: torch.Tensor, head: torch.Tensor, layers: list,
+                 norm: bool = False):
         if V > 256:
             raise ValueError("the output head runs on the router kernel: at most 256 tokens in the vocabulary")
         self.cfg, self.V, self.device = cfg, V, embed.device
-        self.embed, self.head, self.layers = embed, head, layers
+        self.embed, self.head, self.layers, self.norm = embed, head, layers, norm
         # the head as a "router" over V outputs with one selected entry
         self.head_cfg = wl.LayerConfig("lm_head", T=1, H=cfg.H, E=V, I=8, k_big=1, k_little=1,
                                        dtype=cfg.dtype, gamma=cfg.gamma)
@@ -64,7 +67,16 @@ class ToyLMDevice:
                 gate_bias=None if l.gate_bias is None else torch.from_numpy(l.gate_bias).to(device),
                 experts=experts, table=table,
                 shared=[mm.to_device(b, cfg, device) for b in l.shared_w]))
-        return cls(cfg, lm.V, mm.to_device(lm.embed, cfg, device), mm.to_device(lm.head, cfg, device), layers)
+        return cls(cfg, lm.V, mm.to_device(lm.embed, cfg, device), mm.to_device(lm.head, cfg, device), layers,
+                   lm.norm)
+
+    def between_layers(self, out: torch.Tensor) -> torch.Tensor:
+        """What the next layer (or the head) reads: the layer's stored output, with `norm` its rows
+        divided by sqrt(mean of squares + 1e-6) and stored in the same type."""
+        if not self.norm:
+            return out
+        f = out.float()
+        return (f * torch.rsqrt((f * f).mean(dim=1, keepdim=True) + 1e-6)).to(out.dtype)
 
 
 class LayerCaches:
@@ -123,10 +135,9 @@ class Alg1Batch:
         self.rejected_conf = np.zeros(B, np.float32)
         self.finished = []                  # (seq_id, tokens, from_big)
         self.n_steps = self.n_accepted = self.n_fallbacks = self.n_little = self.n_big = 0
-        # offloading: router logits of a slot's rejected pass for every layer, the prediction made
-        # from them (experts per layer, most likely first), and the counters
-        L, E = len(dev.layers), dev.cfg.E
-        self.router_states = np.zeros((L, B, E), np.float32)
+        # offloading: the prediction made from the router logits of the rejected passes (experts per
+        # layer, most likely first), and the counters
+        L = len(dev.layers)
         self.predicted: List[List[int]] = [[] for _ in range(L)]
         self.pb = mm.StepBuffers(dev.cfg, L * B, d) if caches is not None and prefetch_distance > 0 else None
         self.demand_hits = self.demand_misses = self.prefetch_copies = self.prefetch_dropped = 0
@@ -179,6 +190,7 @@ class Alg1Batch:
                 self.demand_misses += st.misses
                 self.bytes_h2d += st.bytes_h2d
                 self.waves += waves
+            x = dev.between_layers(x)
             xs.append(x)
         hb = self.hb
         mm.moe_route(hb.c, x, dev.head, None, None, hb.logits, False, hb.topk_idx, hb.topk_w, hb.important,
@@ -194,7 +206,7 @@ class Alg1Batch:
                              topk_idx=b.topk_idx.cpu().numpy(), k_t=b.k_t.cpu().numpy(),
                              important=b.important.cpu().numpy(), out=b.out.detach().cpu())
                         for xi, b in zip(xs, self.bufs)],
-                lm_logits=hb.logits.cpu().numpy(), conf=conf.copy(), top=top.copy()))
+                x_head=x.detach().cpu(), lm_logits=hb.logits.cpu().numpy(), conf=conf.copy(), top=top.copy()))
         self.n_steps += 1
         rejected: List[int] = []
         for b in range(B):
@@ -231,10 +243,9 @@ class Alg1Batch:
         if self.pb is None or self.always_big or not rejected:
             return                          # a slot is in big mode only right after its rejection
         slots = rejected
-        for l, b in enumerate(self.bufs):
-            self.router_states[l, rejected] = b.logits[rejected].cpu().numpy()
         pb = self.pb
-        pb.logits.copy_(torch.from_numpy(self.router_states.reshape(L * B, -1)))
+        # all layers' router logits of the step in one [L*B, E] selection; one copy to the host
+        torch.stack([b.logits for b in self.bufs], out=pb.logits.view(L, B, -1))
         mm.moe_route(pb.c, None, None, None, None, pb.logits, True, pb.topk_idx, pb.topk_w, pb.important,
                      pb.k_t, None)
         idx = pb.topk_idx.cpu().numpy().reshape(L, B, K)

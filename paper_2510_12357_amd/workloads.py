@@ -172,14 +172,16 @@ class ToyLM:
     embed: np.ndarray                   # [V,H] stored dtype
     layers: List[Layer]                 # x / conf of these are not used
     head: np.ndarray                    # [V,H] stored dtype
+    norm: bool = False                  # rescale every layer's output rows to unit RMS (deep stacks)
 
 
-def make_toy_lm(cfg: LayerConfig, V: int, L: int, seed: int = 0, head_std: float = 1.0) -> ToyLM:
+def make_toy_lm(cfg: LayerConfig, V: int, L: int, seed: int = 0, head_std: float = 1.0,
+                norm: bool = False) -> ToyLM:
     embed = _store(_normal(seed, _ID_EMBED, (V, cfg.H), 1.0), cfg.dtype)
     head = _store(_normal(seed, _ID_HEAD, (V, cfg.H), head_std), cfg.dtype)
     small = cfg.with_(T=1)
     layers = [make_layer(small, seed=seed * 1009 + 17 * (l + 1)) for l in range(L)]
-    return ToyLM(cfg, V, embed, layers, head)
+    return ToyLM(cfg, V, embed, layers, head, norm)
 
 
 def make_prompt_tokens(seed: int, n: int, V: int) -> np.ndarray:

@@ -26,17 +26,31 @@ def host_bits(t: torch.Tensor) -> np.ndarray:
     return t.numpy()
 
 
-def toy(dtype, V=48, L=3, seed=3, head_std=0.25, **kw):
+def toy(dtype, V=48, L=3, seed=3, head_std=0.25, norm=False, **kw):
     base = dict(name="toy", T=1, H=64, E=8, I=48, k_big=4, k_little=2, shared_I=(32,), dtype=dtype,
                 renorm=False, gate_std=0.3, w_std=0.18, gate_bias_std=0.2)
     base.update(kw)
-    return wl.make_toy_lm(wl.LayerConfig(**base), V=V, L=L, seed=seed, head_std=head_std)
+    return wl.make_toy_lm(wl.LayerConfig(**base), V=V, L=L, seed=seed, head_std=head_std, norm=norm)
 
 
-@pytest.mark.parametrize("dtype,renorm", [("bf16", False), ("bf16", True), ("fp32", False)])
-def test_alg1_over_many_steps(dtype, renorm):
+def handed_over(lm, out_bits, x_in, where):
+    """The next layer's stored input against the layer's stored output: the same bits, or with the
+    model's normalisation the oracle's rescaled rows up to the last stored bit."""
+    if not lm.norm:
+        assert np.array_equal(x_in, out_bits), where
+        return
+    want = wl.as_f32(oracle.rms_normalize(out_bits)).astype(np.float64)
+    got = wl.as_f32(x_in).astype(np.float64)
+    ulp = 2.0 ** -7 if lm.cfg.dtype == "bf16" else 2.0 ** -22
+    assert (np.abs(got - want) <= ulp * np.abs(want) + 1e-30).all(), where
+    assert (got == want).mean() > 0.98, where
+
+
+@pytest.mark.parametrize("dtype,renorm,norm,L", [("bf16", False, False, 3), ("bf16", True, False, 3),
+                                                 ("fp32", False, False, 3), ("bf16", False, True, 6)])
+def test_alg1_over_many_steps(dtype, renorm, norm, L):
     from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
-    lm = toy(dtype, renorm=renorm)
+    lm = toy(dtype, renorm=renorm, norm=norm, L=L, head_std=0.25 if not norm else 0.55)
     c, ls = lm.cfg, layers_of(lm)
     B, steps, max_new = 12, 40, 9
     prompts = wl.make_prompt_tokens(11, 200, lm.V)
@@ -55,11 +69,14 @@ def test_alg1_over_many_steps(dtype, renorm):
     for s, r in enumerate(rec):
         tok, big = r["tokens_in"], r["big_in"]
         # ---- the mixed batch: big-mode slots, and only they, are important in every layer
-        x_prev = lm.embed[tok]
+        x_prev = None
         same_sel = np.ones(B, bool)
         for l, (ly, g) in enumerate(zip(ls, r["layers"])):
             x_in = host_bits(g["x_in"])
-            assert np.array_equal(x_in, x_prev), (s, l)            # bit-identical hand-over
+            if l == 0:
+                assert np.array_equal(x_in, lm.embed[tok]), s      # the embedding rows, bit for bit
+            else:
+                handed_over(lm, x_prev, x_in, (s, l))
             assert np.array_equal(g["important"].astype(bool), big), (s, l)
             assert np.array_equal(g["k_t"], np.where(big, c.k_big, c.k_little)), (s, l)
             # the layer from its own input; selection on the logits the GPU's router produced
@@ -76,16 +93,21 @@ def test_alg1_over_many_steps(dtype, renorm):
             x_prev = host_bits(g["out"])
         # ---- output head, confidence, most probable token
         z = r["lm_logits"]
-        assert rel_err(z, oracle.gate_logits(x_prev, lm.head, None)) <= tol, s
+        x_head = host_bits(r["x_head"])
+        handed_over(lm, x_prev, x_head, (s, "head"))
+        assert rel_err(z, oracle.gate_logits(x_head, lm.head, None)) <= tol, s
         np.testing.assert_allclose(r["conf"], oracle.token_confidence(z), rtol=2e-6, atol=0)
         assert np.array_equal(r["top"], np.argmax(z, axis=1)), s
         # ---- the whole step from the tokens alone, where the oracle's own routing agrees
-        full = oracle.toy_lm_next(lm.embed, ls, lm.head, tok, big, c.gamma, c.k_big, c.k_little, c.renorm)
+        full = oracle.toy_lm_next(lm.embed, ls, lm.head, tok, big, c.gamma, c.k_big, c.k_little, c.renorm,
+                                  norm=lm.norm)
         total_rows += B
         agree_rows += int(same_sel.sum())
-        if same_sel.any():
+        if same_sel.any() and L <= 3:
             # three layers deep, each hand-over rounded to the storage type on both sides: a
-            # norm-wise bound (the element-wise bar is applied layer by layer above)
+            # norm-wise bound (the element-wise bar is applied layer by layer above).  A SwiGLU
+            # layer is quadratic in its input and doubles a relative perturbation, so deeper
+            # stacks are checked layer by layer only.
             d = z[same_sel].astype(np.float64) - full["lm_logits"][same_sel]
             assert np.linalg.norm(d) <= 3 * tol * np.linalg.norm(full["lm_logits"][same_sel]), s
         # ---- what the replay below needs

@@ -76,11 +76,11 @@ def test_ties_take_the_lowest_token():
 
 
 # ------------------------------------------------------------------ the toy model, densely in numpy
-def toy(dtype="fp32", L=2, V=24, seed=3, head_std=0.25, **kw):
+def toy(dtype="fp32", L=2, V=24, seed=3, head_std=0.25, norm=False, **kw):
     base = dict(name="toy", T=1, H=40, E=6, I=24, k_big=4, k_little=2, shared_I=(16,), dtype=dtype,
                 renorm=False, gate_std=0.3, w_std=0.2, gate_bias_std=0.2)
     base.update(kw)
-    return wl.make_toy_lm(wl.LayerConfig(**base), V=V, L=L, seed=seed, head_std=head_std)
+    return wl.make_toy_lm(wl.LayerConfig(**base), V=V, L=L, seed=seed, head_std=head_std, norm=norm)
 
 
 def layers_of(lm):
@@ -114,20 +114,27 @@ def dense_next(lm, tokens, big):
         for b, Is in zip(l.shared_w, c.shared_I):
             out += np_swiglu(xf, b, c.H, Is)
         x = store_like(out, lm)
+        if lm.norm:
+            f = wl.as_f32(x).astype(np.float64)
+            x = store_like(f / np.sqrt(np.mean(f ** 2, axis=1, keepdims=True) + 1e-6), lm)
     z = (wl.as_f32(x).astype(np.float64) @ wl.as_f32(lm.head).astype(np.float64).T).astype(np.float32)
     return np_softmax(z), z
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
-@pytest.mark.parametrize("renorm", [False, True])
-def test_toy_step_equals_dense_numpy(dtype, renorm):
-    lm = toy(dtype=dtype, renorm=renorm)
+@pytest.mark.parametrize("renorm,norm,L", [(False, False, 2), (True, False, 2), (False, True, 5)])
+def test_toy_step_equals_dense_numpy(dtype, renorm, norm, L):
+    lm = toy(dtype=dtype, renorm=renorm, norm=norm, L=L, head_std=0.25 if not norm else 0.5)
     c = lm.cfg
     rng = np.random.default_rng(5)
     tokens = rng.integers(0, lm.V, size=19)
     big = rng.random(19) < 0.4
-    r = oracle.toy_lm_next(lm.embed, layers_of(lm), lm.head, tokens, big, c.gamma, c.k_big, c.k_little, c.renorm)
+    r = oracle.toy_lm_next(lm.embed, layers_of(lm), lm.head, tokens, big, c.gamma, c.k_big, c.k_little, c.renorm,
+                           norm=lm.norm)
     p, z = dense_next(lm, tokens, big)
+    if norm:
+        x = wl.as_f32(r["x_last"]).astype(np.float64)
+        np.testing.assert_allclose(np.sqrt((x ** 2).mean(axis=1)), 1.0, rtol=1e-2)
     # bf16 storage between the layers can flip the last stored bit where the two summation orders
     # differ; that moves a logit by a few 1e-3 relative
     tol = 1e-9 if dtype == "fp32" else 2e-2
@@ -138,7 +145,8 @@ def test_toy_step_equals_dense_numpy(dtype, renorm):
     # the mode matters: flipping one token's mode changes that token's row and no other
     big2 = big.copy()
     big2[3] = not big2[3]
-    r2 = oracle.toy_lm_next(lm.embed, layers_of(lm), lm.head, tokens, big2, c.gamma, c.k_big, c.k_little, c.renorm)
+    r2 = oracle.toy_lm_next(lm.embed, layers_of(lm), lm.head, tokens, big2, c.gamma, c.k_big, c.k_little, c.renorm,
+                            norm=lm.norm)
     changed = np.abs(r2["lm_logits"] - r["lm_logits"]).max(axis=1) > 0
     assert changed[3] and changed.sum() == 1
 
