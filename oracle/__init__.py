@@ -39,7 +39,7 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_gate_logits", "oracle_token_confidence", "oracle_route",
                      "oracle_dispatch", "oracle_dispatch_from", "oracle_combine_add", "oracle_swiglu_rows", "oracle_expert_ffn",
-                     "oracle_combine", "oracle_num_threads"):
+                     "oracle_combine", "oracle_num_threads", "oracle_swiglu_rows_w8", "oracle_e4m3_decode"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -119,16 +119,35 @@ def dispatch(topk_idx: np.ndarray, k_t: np.ndarray, E: int):
     return off, st, sr, inv
 
 
+def w8_blob_bytes(H: int, I: int) -> int:
+    """Bytes of an expert with 8-bit weights: 3*H*I E4M3 codes + (2*I + H) fp32 row scales."""
+    return 3 * H * I + 4 * (2 * I + H)
+
+
+def e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    """Values of E4M3 ("e4m3fn", OCP 8-bit floating point) codes -> float64."""
+    c = _c(codes, np.uint8).ravel()
+    out = np.empty(c.shape, np.float64)
+    _check(_load().oracle_e4m3_decode(_p(c), c.size, _p(out)), "e4m3_decode")
+    return out.reshape(np.shape(codes))
+
+
 def swiglu_rows(x: np.ndarray, blob: np.ndarray, I: int,
                 tok: Optional[np.ndarray] = None) -> np.ndarray:
     """One expert (blob = [W_gate I*H | W_up I*H | W_down H*I] flat) on rows ``tok`` of x
-    (all rows in order when ``tok`` is None).  -> float64 [n,H]"""
+    (all rows in order when ``tok`` is None).  A uint8 blob holds 8-bit weights: E4M3 codes in
+    the same order, then the fp32 row scales [gate I | up I | down H].  -> float64 [n,H]"""
     x, blob = _c(x), _c(blob)
     T, H = x.shape
-    assert blob.size == 3 * H * I and _dtype_code(blob) == _dtype_code(x)
     tk = None if tok is None else _c(tok, np.int32)
     n = T if tk is None else tk.shape[0]
     y = np.empty((n, H), np.float64)
+    if blob.dtype == np.uint8:
+        assert blob.size == w8_blob_bytes(H, I)
+        _check(_load().oracle_swiglu_rows_w8(_p(x), _dtype_code(x), H, I, _p(blob), _p(tk), n, _p(y)),
+               "swiglu_rows_w8")
+        return y
+    assert blob.size == 3 * H * I and _dtype_code(blob) == _dtype_code(x)
     _check(_load().oracle_swiglu_rows(_p(x), _dtype_code(x), H, I, _p(blob), _p(tk), n, _p(y)),
            "swiglu_rows")
     return y
@@ -141,14 +160,18 @@ def expert_ffn(x: np.ndarray, expert_w: Sequence[np.ndarray], I: int, expert_off
     T, H = x.shape
     E = len(expert_w)
     blobs = [_c(b) for b in expert_w]
+    w8 = len(blobs) > 0 and blobs[0].dtype == np.uint8
     for b in blobs:
-        assert b.size == 3 * H * I and _dtype_code(b) == _dtype_code(x)
+        if w8:
+            assert b.dtype == np.uint8 and b.size == w8_blob_bytes(H, I)
+        else:
+            assert b.size == 3 * H * I and _dtype_code(b) == _dtype_code(x)
     ptrs = (ctypes.c_void_p * E)(*[b.ctypes.data for b in blobs])
     off = _c(expert_offsets, np.int32)
     st = _c(sorted_token, np.int32)
     P = int(off[E])
     y = np.zeros((P, H), np.float64)
-    _check(_load().oracle_expert_ffn(_p(x), _dtype_code(x), H, I, E, _p(off), _p(st), ptrs, _p(y)),
+    _check(_load().oracle_expert_ffn(_p(x), _dtype_code(x), H, I, E, _p(off), _p(st), ptrs, int(w8), _p(y)),
            "expert_ffn")
     return y
 

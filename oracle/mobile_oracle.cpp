@@ -47,6 +47,17 @@ inline double load_elem(const void* base, size_t i, int dtype) {
 
 inline size_t elem_size(int dtype) { return dtype == kFP32 ? 4 : 2; }
 
+// 8-bit float E4M3 of the OCP 8-bit floating point specification ("e4m3fn"): 1 sign, 4 exponent
+// (bias 7), 3 mantissa bits; no infinities; S.1111.111 is NaN; exponent field 0 is subnormal.
+inline double e4m3_value(uint8_t b) {
+  const int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+  double v;
+  if (e == 15 && m == 7) v = std::numeric_limits<double>::quiet_NaN();
+  else if (e == 0) v = std::ldexp((double)m, -9);            // (m / 8) * 2^-6
+  else v = std::ldexp(1.0 + m / 8.0, e - 7);
+  return sign ? -v : v;
+}
+
 // NaN router scores take part in selection and softmax as minus infinity.
 inline double clean_logit(float v) {
   return std::isnan(v) ? -std::numeric_limits<double>::infinity() : (double)v;
@@ -245,15 +256,61 @@ int oracle_swiglu_rows(const void* x, int dtype, int H, int I, const void* blob,
   return 0;
 }
 
+// The same feed-forward with the expert's weights stored in 8 bits (weight-only quantisation,
+// activations in `xdtype`):
+//   blob = [Q_gate I x H | Q_up I x H | Q_down H x I] one E4M3 byte per weight, followed by the
+//          fp32 row scales [s_gate I | s_up I | s_down H];  W[r][k] = s[r] * e4m3(Q[r][k])
+int oracle_swiglu_rows_w8(const void* x, int xdtype, int H, int I, const void* blob,
+                          const int32_t* tok, int n, double* y) {
+  if (!x || !blob || !y || H <= 0 || I <= 0 || n < 0) return -1;
+  const uint8_t* q = static_cast<const uint8_t*>(blob);
+  const uint8_t* Qgate = q;
+  const uint8_t* Qup = q + (size_t)I * H;
+  const uint8_t* Qdown = q + 2 * (size_t)I * H;
+  std::vector<float> sc(2 * (size_t)I + H);
+  std::memcpy(sc.data(), q + 3 * (size_t)I * H, sc.size() * sizeof(float));
+  const float* s_gate = sc.data();
+  const float* s_up = sc.data() + I;
+  const float* s_down = sc.data() + 2 * (size_t)I;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int r = 0; r < n; ++r) {
+    const size_t t = tok ? (size_t)tok[r] : (size_t)r;
+    std::vector<double> a(I);
+    for (int i = 0; i < I; ++i) {
+      double g = 0.0, u = 0.0;
+      for (int h = 0; h < H; ++h) {
+        const double xv = load_elem(x, t * H + h, xdtype);
+        g += (double)s_gate[i] * e4m3_value(Qgate[(size_t)i * H + h]) * xv;
+        u += (double)s_up[i] * e4m3_value(Qup[(size_t)i * H + h]) * xv;
+      }
+      a[i] = g / (1.0 + std::exp(-g)) * u;
+    }
+    for (int c = 0; c < H; ++c) {
+      double acc = 0.0;
+      for (int i = 0; i < I; ++i) acc += (double)s_down[c] * e4m3_value(Qdown[(size_t)c * I + i]) * a[i];
+      y[(size_t)r * H + c] = acc;
+    }
+  }
+  return 0;
+}
+
+int oracle_e4m3_decode(const uint8_t* codes, int n, double* out) {
+  if (!codes || !out || n < 0) return -1;
+  for (int i = 0; i < n; ++i) out[i] = e4m3_value(codes[i]);
+  return 0;
+}
+
 // Execution stage over the dispatched pairs: expert e processes positions
 // offsets[e] .. offsets[e+1]-1.  expert_w[e] points at expert e's blob (host memory).
+// w8 != 0: the blobs hold 8-bit weights with row scales (oracle_swiglu_rows_w8).
 int oracle_expert_ffn(const void* x, int dtype, int H, int I, int E, const int32_t* offsets,
-                      const int32_t* sorted_token, const void* const* expert_w, double* y) {
+                      const int32_t* sorted_token, const void* const* expert_w, int w8, double* y) {
   if (!offsets || !sorted_token || !expert_w) return -1;
   for (int e = 0; e < E; ++e) {
     const int b = offsets[e], n = offsets[e + 1] - b;
     if (n == 0) continue;
-    int rc = oracle_swiglu_rows(x, dtype, H, I, expert_w[e], sorted_token + b, n,
+    int rc = w8 ? oracle_swiglu_rows_w8(x, dtype, H, I, expert_w[e], sorted_token + b, n, y + (size_t)b * H)
+                : oracle_swiglu_rows(x, dtype, H, I, expert_w[e], sorted_token + b, n,
                                 y + (size_t)b * H);
     if (rc) return rc;
   }

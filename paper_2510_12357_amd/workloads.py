@@ -28,7 +28,8 @@ class LayerConfig:
     k_big: int                  # experts of an important token (the model's default K)
     k_little: int               # experts of every other token (K/2)
     shared_I: Tuple[int, ...] = ()   # always-on shared experts (intermediate sizes)
-    dtype: str = "bf16"         # storage type of x and all weights: "bf16" | "fp32"
+    dtype: str = "bf16"         # storage type of x and all weights: "bf16" | "fp32" | "bf16w8" (bf16
+                                # activations and router, expert weights in 8 bits with row scales)
     renorm: bool = False        # renormalise routing weights over the selected experts
     gamma: float = 0.7          # fallback threshold
     gate_std: float = 0.02
@@ -72,11 +73,47 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def _store(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Activations, router weights, embeddings: "bf16w8" stores them as bf16."""
     if dtype == "fp32":
         return np.ascontiguousarray(a, dtype=np.float32)
-    if dtype == "bf16":
+    if dtype in ("bf16", "bf16w8"):
         return f32_to_bf16_bits(a)
     raise ValueError(dtype)
+
+
+def _e4m3_positive_values() -> np.ndarray:
+    """The 127 finite non-negative values of the 8-bit float E4M3 ("e4m3fn"), by code 0x00..0x7E."""
+    code = np.arange(127)
+    e, m = code >> 3, code & 7
+    return np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
+
+
+def f32_to_e4m3_bits(a: np.ndarray) -> np.ndarray:
+    """Nearest finite E4M3 code of every entry (values beyond +-448 saturate); used to make up
+    8-bit expert weights, so any rounding would do."""
+    v = _e4m3_positive_values()
+    mid = (v[1:] + v[:-1]) / 2
+    mag = np.abs(np.asarray(a, np.float64))
+    code = np.searchsorted(mid, mag, side="left").astype(np.uint8)
+    return code | (np.signbit(a).astype(np.uint8) << 7)
+
+
+def w8_blob_bytes(H: int, I: int) -> int:
+    return 3 * H * I + 4 * (2 * I + H)
+
+
+def quantize_blob_w8(w: np.ndarray, H: int, I: int) -> np.ndarray:
+    """[W_gate I*H | W_up I*H | W_down H*I] in fp32 -> the 8-bit blob: E4M3 codes in the same order,
+    then the fp32 row scales [gate I | up I | down H]; a row's scale maps its largest magnitude to 448."""
+    w = np.asarray(w, np.float32)
+    rows = [w[:I * H].reshape(I, H), w[I * H:2 * I * H].reshape(I, H), w[2 * I * H:].reshape(H, I)]
+    codes, scales = [], []
+    for m in rows:
+        s = (np.abs(m).max(axis=1) / np.float32(448.0)).astype(np.float32)
+        s[s == 0] = np.float32(1.0)
+        codes.append(f32_to_e4m3_bits(m / s[:, None]).ravel())
+        scales.append(s)
+    return np.concatenate(codes + [np.concatenate(scales).view(np.uint8)])
 
 
 def as_f32(a: np.ndarray) -> np.ndarray:
@@ -143,7 +180,10 @@ def make_expert_blob(cfg: LayerConfig, seed: int, e: int, I: Optional[int] = Non
                      shared: bool = False) -> np.ndarray:
     I = cfg.I if I is None else I
     tid = (_ID_SHARED0 if shared else _ID_EXPERT0) + e
-    return _store(_normal(seed, tid, (3 * cfg.H * I,), cfg.w_std), cfg.dtype)
+    w = _normal(seed, tid, (3 * cfg.H * I,), cfg.w_std)
+    if cfg.dtype == "bf16w8":
+        return quantize_blob_w8(w, cfg.H, I)
+    return _store(w, cfg.dtype)
 
 
 def make_layer(cfg: LayerConfig, seed: int = 0, experts: bool = True) -> Layer:
