@@ -56,6 +56,8 @@ def parse_args():
 
 def workload_config(name: str, ratio: float):
     from paper_2510_12357_amd import workloads as wl
+    if name.startswith("fine60_decode_b") and name.endswith("_w8"):     # expert weights in 8 bits (not in the paper)
+        return wl.CONFIGS["fine60_decode"].with_(T=int(name[:-3].split("_b")[1]), fallback_ratio=ratio, dtype="bf16w8")
     if name.startswith("fine60_decode_b"):
         return wl.CONFIGS["fine60_decode"].with_(T=int(name.split("_b")[1]), fallback_ratio=ratio)
     if name == "fine64_prefill":
@@ -76,11 +78,26 @@ class DeviceLayers:
         self.cfg, self.L = cfg, L
         g = torch.Generator(device="cuda")
         g.manual_seed(seed)
-        dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-        blob = 3 * cfg.H * cfg.I
+        dt = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
+        w8 = cfg.dtype == "bf16w8"
+        blob = wl.w8_blob_bytes(cfg.H, cfg.I) if w8 else 3 * cfg.H * cfg.I
 
         def randn(shape, std):
             return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+
+        def weights(I):
+            """One expert blob: random weights in the layer's storage type; 8-bit blobs are E4M3 codes
+            (torch's float8_e4m3fn cast) followed by the fp32 row scales that map a row's peak to 448."""
+            if not w8:
+                return randn((3 * cfg.H * I,), cfg.w_std)
+            w = torch.randn((3 * cfg.H * I,), generator=g, device="cuda", dtype=torch.float32) * cfg.w_std
+            parts, scales = [], []
+            for m in (w[:I * cfg.H].view(I, cfg.H), w[I * cfg.H:2 * I * cfg.H].view(I, cfg.H),
+                      w[2 * I * cfg.H:].view(cfg.H, I)):
+                s = m.abs().amax(dim=1) / 448.0
+                parts.append((m / s[:, None]).to(torch.float8_e4m3fn).view(torch.uint8).reshape(-1))
+                scales.append(s)
+            return torch.cat(parts + [torch.cat(scales).view(torch.uint8)])
 
         self.x, self.Wg, self.bias, self.experts, self.table, self.shared, self.conf = [], [], [], [], [], [], []
         for l in range(L):
@@ -88,22 +105,23 @@ class DeviceLayers:
             self.Wg.append(randn((cfg.E, cfg.H), cfg.gate_std))
             self.bias.append(torch.randn((cfg.E,), generator=g, device="cuda") * cfg.gate_bias_std
                              if cfg.gate_bias_std > 0 else None)
-            ex = torch.empty((cfg.E, blob), dtype=dt, device="cuda")
+            ex = torch.empty((cfg.E, blob), dtype=torch.uint8 if w8 else dt, device="cuda")
             for e in range(cfg.E):                       # expert by expert: bounded fp32 temporaries
-                ex[e] = randn((blob,), cfg.w_std)
+                ex[e] = weights(cfg.I)
             self.experts.append(ex)
             stride = ex.stride(0) * ex.element_size()
             self.table.append(torch.tensor([ex.data_ptr() + e * stride for e in range(cfg.E)],
                                            dtype=torch.int64, device="cuda"))
-            self.shared.append([randn((3 * cfg.H * Is,), cfg.w_std) for Is in cfg.shared_I])
+            self.shared.append([weights(Is) for Is in cfg.shared_I])
             conf = wl.make_confidence(seed + l, cfg.T, cfg.gamma, cfg.fallback_ratio)
             self.conf.append(torch.from_numpy(conf).cuda())
         torch.cuda.synchronize()
 
     def bytes_per_layer(self) -> int:
         c = self.cfg
-        eb = 2 if c.dtype == "bf16" else 4
-        return eb * (c.E * 3 * c.H * c.I + sum(3 * c.H * i for i in c.shared_I) + c.E * c.H)
+        eb = 4 if c.dtype == "fp32" else 2
+        wb = {"fp32": 4, "bf16": 2, "bf16w8": 1}[c.dtype]
+        return wb * (c.E * 3 * c.H * c.I + sum(3 * c.H * i for i in c.shared_I)) + eb * c.E * c.H
 
 
 def eq1(T: float, T_l: float, T_b: float, r: float) -> float:
@@ -112,8 +130,8 @@ def eq1(T: float, T_l: float, T_b: float, r: float) -> float:
 
 
 def auto_layers(cfg) -> int:
-    eb = 2 if cfg.dtype == "bf16" else 4
-    per = eb * (cfg.E * 3 * cfg.H * cfg.I + sum(3 * cfg.H * i for i in cfg.shared_I))
+    wb = {"fp32": 4, "bf16": 2, "bf16w8": 1}[cfg.dtype]
+    per = wb * (cfg.E * 3 * cfg.H * cfg.I + sum(3 * cfg.H * i for i in cfg.shared_I))
     # enough distinct weights that a layer is evicted from the 256 MB last-level cache before
     # it is reused, within a budget of ~12 GB
     return int(max(2, min(8, (12 << 30) // per)))
@@ -451,16 +469,17 @@ def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: 
 def algorithmic_work(cfg, P: float, D: float):
     """Bytes and flops one step must move / do (weights of the D touched experts once, the shared
     experts, the router, activations in and out; flops of the P pair FFNs, shared FFNs, router)."""
-    eb = 2 if cfg.dtype == "bf16" else 4
+    eb = 4 if cfg.dtype == "fp32" else 2                              # activations, router matrix
+    wb = {"fp32": 4, "bf16": 2, "bf16w8": 1}[cfg.dtype]                # expert weights (row scales not counted)
     H, I, T, E = cfg.H, cfg.I, cfg.T, cfg.E
     sh = sum(cfg.shared_I)
-    step_bytes = eb * (D * 3 * H * I + 3 * H * sh + E * H) + 2 * eb * T * H
+    step_bytes = wb * (D * 3 * H * I + 3 * H * sh) + eb * E * H + 2 * eb * T * H
     step_flops = 2 * 3 * H * I * P + 2 * T * 3 * H * sh + 2 * T * E * H
     # gate+up kernel alone: two of the three matrices of every touched expert and shared expert,
     # the activations it reads, the SwiGLU activations it writes
-    gu_bytes = eb * (D * 2 * H * I + 2 * H * sh) + eb * T * H + eb * (P * I + T * sh)
+    gu_bytes = wb * (D * 2 * H * I + 2 * H * sh) + eb * T * H + eb * (P * I + T * sh)
     gu_flops = 2 * 2 * H * I * P + 2 * T * 2 * H * sh
-    dn_bytes = eb * (D * H * I + H * sh) + eb * (P * I + T * sh) + 4 * (P * H + len(cfg.shared_I) * T * H)
+    dn_bytes = wb * (D * H * I + H * sh) + eb * (P * I + T * sh) + 4 * (P * H + len(cfg.shared_I) * T * H)
     return dict(step_bytes=step_bytes, step_flops=step_flops, gate_up_bytes=gu_bytes,
                 gate_up_flops=gu_flops, down_bytes=dn_bytes)
 
@@ -605,7 +624,7 @@ def main():
         others = {}
         k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 2)
         names = [n for n in ("fine60_decode_b1", "fine60_decode_b8", "fine60_decode_b32", "fine60_decode_b64",
-                             "fine64_prefill") if n != args.workload]
+                             "fine64_prefill", "fine60_decode_b1_w8", "fine60_decode_b64_w8") if n != args.workload]
         for name in names:
             c2 = workload_config(name, args.ratio)
             r2 = time_workload(mm, torch, c2, k2, w2)

@@ -28,6 +28,10 @@
  *     enqueued asynchronously on it; no call synchronises with the host except where stated.
  *   - Tensors are row-major and dense.  dtype MOE_BF16: activations / weights are bf16,
  *     products accumulate in fp32.  dtype MOE_FP32: fp32 storage and arithmetic.
+ *     dtype MOE_BF16_W8 (decode regime only, T < 256; not in the paper): as MOE_BF16, but the
+ *     expert weights are stored in 8 bits with one fp32 scale per weight row, which halves the
+ *     bytes a decode step streams from HBM.  It needs H, I and every shared_I to be multiples
+ *     of 16.
  *   - Shape limits: H % 8 == 0, I % 8 == 0, every shared_I % 8 == 0, 1 <= k_little <= k_big
  *     <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS, n_shared <= MOE_MAX_SHARED,
  *     T * k_big < 2^31 / max(H, I).  Violations give MOE_E_SHAPE / MOE_E_UNSUPPORTED.
@@ -35,6 +39,11 @@
  *         [ W_gate : I x H | W_up : I x H | W_down : H x I ]      (each row-major)
  *     so that one expert is one host-to-device copy.  The feed-forward is SwiGLU:
  *         y = W_down ( silu(W_gate x) * (W_up x) ).
+ *     MOE_BF16_W8: the three matrices hold one E4M3 code per weight (OCP 8-bit floating point
+ *     "e4m3fn": 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities), followed by
+ *     the fp32 row scales [ s_gate : I | s_up : I | s_down : H ];  W[r][k] = s[r] * e4m3(Q[r][k]).
+ *     The codes are widened exactly to bf16, the products accumulate in fp32, and the row's scale
+ *     multiplies the sum.  moe_expert_blob_bytes gives the size of a blob.
  */
 #ifndef MOBILE_MOE_H_
 #define MOBILE_MOE_H_
@@ -50,7 +59,7 @@ extern "C" {
 #define MOE_MAX_EXPERTS 256
 #define MOE_MAX_TOPK 16
 
-enum { MOE_BF16 = 0, MOE_FP32 = 1 };
+enum { MOE_BF16 = 0, MOE_FP32 = 1, MOE_BF16_W8 = 2 };
 
 enum {
   MOE_OK = 0,
@@ -72,7 +81,8 @@ typedef struct moe_config {
   int32_t k_little; /* experts of every other token: K/2 in the paper, any 1..k_big here    */
   int32_t n_shared; /* always-on shared experts (weight 1, every token); 0 = none           */
   int32_t shared_I[MOE_MAX_SHARED]; /* their intermediate sizes                             */
-  int32_t dtype;    /* MOE_BF16 | MOE_FP32: storage of x, Wg, expert blobs, out             */
+  int32_t dtype;    /* MOE_BF16 | MOE_FP32: storage of x, Wg, expert blobs, out;
+                       MOE_BF16_W8: bf16 x, Wg, out with 8-bit expert blobs                 */
   int32_t renorm;   /* 0: routing weight = softmax over all E; 1: renormalised over the k_t
                        selected experts                                                     */
   float gamma;      /* fallback threshold of Alg. 1 (paper default 0.7)                     */
@@ -159,6 +169,9 @@ int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* 
  * The number of pairs per expert is read on the device; the host never waits for it.
  */
 size_t moe_expert_ffn_workspace_bytes(const moe_config* cfg);
+/* Bytes of one expert blob with intermediate size I (cfg->I for a routed expert, cfg->shared_I[s]
+ * for a shared one) in cfg->dtype; 0 on a bad config or I. */
+size_t moe_expert_blob_bytes(const moe_config* cfg, int32_t I);
 int32_t moe_shared_out_slabs(const moe_config* cfg); /* 0 without shared experts; -1 on a bad config */
 int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_t* expert_offsets,
                    const int32_t* sorted_token, const void* const* expert_w,

@@ -272,6 +272,8 @@ int oracle_swiglu_rows_w8(const void* x, int xdtype, int H, int I, const void* b
   const float* s_gate = sc.data();
   const float* s_up = sc.data() + I;
   const float* s_down = sc.data() + 2 * (size_t)I;
+  double value_of[256];                      // the 256 codes, decoded once
+  for (int b = 0; b < 256; ++b) value_of[b] = e4m3_value((uint8_t)b);
 #pragma omp parallel for schedule(dynamic, 1)
   for (int r = 0; r < n; ++r) {
     const size_t t = tok ? (size_t)tok[r] : (size_t)r;
@@ -280,14 +282,14 @@ int oracle_swiglu_rows_w8(const void* x, int xdtype, int H, int I, const void* b
       double g = 0.0, u = 0.0;
       for (int h = 0; h < H; ++h) {
         const double xv = load_elem(x, t * H + h, xdtype);
-        g += (double)s_gate[i] * e4m3_value(Qgate[(size_t)i * H + h]) * xv;
-        u += (double)s_up[i] * e4m3_value(Qup[(size_t)i * H + h]) * xv;
+        g += (double)s_gate[i] * value_of[Qgate[(size_t)i * H + h]] * xv;
+        u += (double)s_up[i] * value_of[Qup[(size_t)i * H + h]] * xv;
       }
       a[i] = g / (1.0 + std::exp(-g)) * u;
     }
     for (int c = 0; c < H; ++c) {
       double acc = 0.0;
-      for (int i = 0; i < I; ++i) acc += (double)s_down[c] * e4m3_value(Qdown[(size_t)c * I + i]) * a[i];
+      for (int i = 0; i < I; ++i) acc += (double)s_down[c] * value_of[Qdown[(size_t)c * I + i]] * a[i];
       y[(size_t)r * H + c] = acc;
     }
   }

@@ -18,7 +18,7 @@ from .workloads import LayerConfig
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmobile_moe.so")
 
-MOE_BF16, MOE_FP32 = 0, 1
+MOE_BF16, MOE_FP32, MOE_BF16_W8 = 0, 1, 2
 MOE_FETCH_DEMAND, MOE_FETCH_PREFETCH = 0, 1
 MOE_MAX_SHARED = 4
 MOE_OK = 0
@@ -27,7 +27,7 @@ ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "M
 
 EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_from", "moe_combine_add",
-           "moe_expert_ffn_workspace_bytes",
+           "moe_expert_ffn_workspace_bytes", "moe_expert_blob_bytes",
            "moe_shared_out_slabs", "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync")
 
@@ -79,6 +79,8 @@ def load_library() -> ctypes.CDLL:
     lib.moe_combine_add.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, vp]
     lib.moe_expert_ffn_workspace_bytes.argtypes = [cfgp]
     lib.moe_expert_ffn_workspace_bytes.restype = sz
+    lib.moe_expert_blob_bytes.argtypes = [cfgp, i32]
+    lib.moe_expert_blob_bytes.restype = sz
     lib.moe_shared_out_slabs.argtypes = [cfgp]
     lib.moe_shared_out_slabs.restype = i32
     lib.moe_expert_ffn.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
@@ -117,7 +119,7 @@ def make_config(cfg: LayerConfig, T: Optional[int] = None) -> moe_config:
     c.n_shared = len(cfg.shared_I)
     for i, v in enumerate(cfg.shared_I):
         c.shared_I[i] = v
-    c.dtype = MOE_FP32 if cfg.dtype == "fp32" else MOE_BF16
+    c.dtype = {"bf16": MOE_BF16, "fp32": MOE_FP32, "bf16w8": MOE_BF16_W8}[cfg.dtype]
     c.renorm = int(cfg.renorm)
     c.gamma = cfg.gamma
     return c
@@ -200,6 +202,10 @@ def moe_combine_add(cfg: moe_config, y, topk_w, inv_pos, k_t, j_lo: int, out, st
 
 def moe_expert_ffn_workspace_bytes(cfg: moe_config) -> int:
     return int(load_library().moe_expert_ffn_workspace_bytes(ctypes.byref(cfg)))
+
+
+def moe_expert_blob_bytes(cfg: moe_config, I: int) -> int:
+    return int(load_library().moe_expert_blob_bytes(ctypes.byref(cfg), I))
 
 
 def moe_shared_out_slabs(cfg: moe_config) -> int:

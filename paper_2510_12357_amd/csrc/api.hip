@@ -68,9 +68,12 @@ int device_cu_count() {
   return cached_cu;
 }
 
+// Steps of this many tokens and more run the LDS-tiled kernels, which read bf16 weights only.
+constexpr int kW8MaxT = 256;
+
 int validate_config(const moe_config* c) {
   if (!c) return fail(MOE_E_BADARG, "config is NULL");
-  if (c->dtype != MOE_BF16 && c->dtype != MOE_FP32) return fail(MOE_E_BADARG, "dtype %d", c->dtype);
+  if (c->dtype != MOE_BF16 && c->dtype != MOE_FP32 && c->dtype != MOE_BF16_W8) return fail(MOE_E_BADARG, "dtype %d", c->dtype);
   if (c->T < 0 || c->H <= 0 || c->E <= 0 || c->I <= 0) return fail(MOE_E_SHAPE, "T=%d H=%d E=%d I=%d", c->T, c->H, c->E, c->I);
   if (c->k_little < 1 || c->k_little > c->k_big || c->k_big > c->E)
     return fail(MOE_E_SHAPE, "need 1 <= k_little (%d) <= k_big (%d) <= E (%d)", c->k_little, c->k_big, c->E);
@@ -92,6 +95,14 @@ int validate_config(const moe_config* c) {
   const long long gate = eb * (long long)c->E * c->H;
   if (biggest >= (1ll << 31) || act >= (1ll << 31) || gate >= (1ll << 31))
     return fail(MOE_E_UNSUPPORTED, "a tensor of this layer reaches 2 GiB (expert blob, activations or gate matrix)");
+  if (c->dtype == MOE_BF16_W8) {
+    if (c->T >= kW8MaxT)
+      return fail(MOE_E_UNSUPPORTED, "8-bit expert weights are for the decode regime: T=%d, limit %d", c->T, kW8MaxT - 1);
+    // the kernel moves 16 codes of a weight row at a time
+    bool ok = c->H % 16 == 0 && c->I % 16 == 0;
+    for (int s = 0; s < c->n_shared; ++s) ok = ok && c->shared_I[s] % 16 == 0;
+    if (!ok) return fail(MOE_E_UNSUPPORTED, "8-bit expert weights need H, I and every shared_I to be multiples of 16");
+  }
   if (!(c->gamma == c->gamma)) return fail(MOE_E_BADARG, "gamma is NaN");
   return MOE_OK;
 }
@@ -239,6 +250,11 @@ extern "C" int moe_dispatch_from(const moe_config* cfg, const int32_t* topk_idx,
 extern "C" int32_t moe_shared_out_slabs(const moe_config* cfg) {
   if (validate_config(cfg)) return -1;
   return slab_plan(*cfg).n_slabs;
+}
+
+extern "C" size_t moe_expert_blob_bytes(const moe_config* cfg, int32_t I) {
+  if (validate_config(cfg) || I <= 0 || I % 8) return 0;
+  return expert_blob_bytes(cfg->dtype, cfg->H, I);
 }
 
 extern "C" size_t moe_expert_ffn_workspace_bytes(const moe_config* cfg) {

@@ -233,7 +233,7 @@ extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, cons
   if (rc) return rc;
   if (!c) return fail(MOE_E_BADARG, "moe_expert_ffn_cached: cache is NULL");
   if (cfg->E != c->E) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: cache holds %d experts, layer has %d", c->E, cfg->E);
-  const size_t need = (size_t)3 * cfg->H * cfg->I * elem_bytes(cfg->dtype);
+  const size_t need = expert_blob_bytes(cfg->dtype, cfg->H, cfg->I);
   if (need != c->blob_bytes) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: blob of %zu bytes, layer needs %zu", c->blob_bytes, need);
   moe_fetch_stats sum = {0, 0, 0, 0, 0};
   if (n_waves) *n_waves = 0;

@@ -85,7 +85,7 @@ int launch_combine_add(const moe_config& c, const float* y, const float* w, cons
                        const int32_t* k_t, int j_lo, void* out, hipStream_t s) {
   if (c.T == 0) return MOE_OK;
   const dim3 grid((unsigned)c.T, (unsigned)((c.H / 4 + kThreads - 1) / kThreads));
-  if (c.dtype == MOE_BF16)
+  if (c.dtype != MOE_FP32)
     hipLaunchKernelGGL(combine_add_kernel<true>, grid, dim3(kThreads), 0, s, y, w, inv_pos, k_t, j_lo, c.H,
                        c.k_big, c.T * c.k_big, out);
   else
@@ -99,7 +99,7 @@ int launch_combine(const moe_config& c, const float* y, const float* w, const in
   if (c.T == 0) return MOE_OK;
   const dim3 grid((unsigned)c.T, (unsigned)((c.H / 4 + kThreads - 1) / kThreads));
   const int ns = shared_out ? slab_plan(c).n_slabs : 0;
-  if (c.dtype == MOE_BF16)
+  if (c.dtype != MOE_FP32)
     hipLaunchKernelGGL(combine_kernel<true>, grid, dim3(kThreads), 0, s, y, w, inv_pos, k_t, shared_out,
                        ns, c.T, c.H, c.k_big, c.T * c.k_big, out);
   else

@@ -48,6 +48,8 @@ struct Group {
   const void* w0;   // first weight matrix, already advanced to the K chunk
   const void* b;    // B rows, already advanced to the K chunk (and to row0 for routed kDown)
   void* out;        // h rows / y rows / slab base, already advanced to row0 where it applies
+  const float* scale;  // 8-bit weights only: fp32 scale of weight row n at scale[n] (gate/up: the
+                       // up rows' scales follow at scale[N + n]); unused otherwise
 };
 
 // What resolving a group has to read from memory; the rest of a Group follows from the kernel
@@ -80,12 +82,16 @@ __device__ __forceinline__ GroupSrc load_group_src(const StreamArgs& a, int g) {
   return s;
 }
 
-template <typename S, int MODE>
+// S: storage type of the activations (and of the router matrix); WB: bytes per expert weight
+// (sizeof(S), or 1 for 8-bit weights with the fp32 row scales [gate | up | down] behind the three
+// matrices of a blob).  ldw counts elements for both the weight rows and the B rows.
+template <typename S, int MODE, int WB = (int)sizeof(S)>
 __device__ __forceinline__ Group make_group(const StreamArgs& a, int g, const GroupSrc& src) {
   constexpr unsigned esz = sizeof(S);
+  constexpr unsigned wsz = (unsigned)WB;
   Group G;
-  G.gather = 0; G.row0 = src.row0; G.m = src.m;
-  const S* blob = static_cast<const S*>(src.blob);
+  G.gather = 0; G.row0 = src.row0; G.m = src.m; G.scale = nullptr;
+  const char* blob = static_cast<const char*>(src.blob);
   if (MODE == kRouter) {
     G.N = a.E; G.K = a.H; G.ldw = a.H;
     G.w0 = a.Wg; G.b = a.x; G.out = a.logits;
@@ -97,32 +103,38 @@ __device__ __forceinline__ Group make_group(const StreamArgs& a, int g, const Gr
     int s = g, chunk = 0;
     if (MODE == kDown) { s = a.slab_shared[g]; chunk = a.slab_chunk[g]; }
     const int Is = a.shared_I[s];
+    const float* scales = reinterpret_cast<const float*>(blob + 3 * (size_t)Is * a.H * wsz);
     if (MODE == kGateUp) {
       G.N = Is; G.K = a.H; G.ldw = a.H;
       G.w0 = blob; G.b = a.x; G.out = a.h_shared[s];
-      G.wbytes = 2u * Is * a.H * esz; G.bbytes = (unsigned)a.T * a.H * esz;
+      G.wbytes = 2u * Is * a.H * wsz; G.bbytes = (unsigned)a.T * a.H * esz;
+      G.scale = scales;
     } else {
       const int kb = chunk * a.shared_kchunk[s];
       G.N = a.H; G.K = min(a.shared_kchunk[s], Is - kb); G.ldw = Is;
-      G.w0 = blob + 2 * (size_t)Is * a.H + kb;
+      G.w0 = blob + (2 * (size_t)Is * a.H + kb) * wsz;
       G.b = static_cast<const S*>(a.h_shared[s]) + kb;
       G.out = a.shared_out + (size_t)g * a.T * a.H;
-      G.wbytes = ((unsigned)a.H * Is - kb) * esz; G.bbytes = ((unsigned)a.T * Is - kb) * esz;
+      G.wbytes = ((unsigned)a.H * Is - kb) * wsz; G.bbytes = ((unsigned)a.T * Is - kb) * esz;
+      G.scale = scales + 2 * (size_t)Is;
     }
     return G;
   }
   const int b0 = src.row0;
+  const float* scales = reinterpret_cast<const float*>(blob + 3 * (size_t)a.I * a.H * wsz);
   if (MODE == kGateUp) {
     G.N = a.I; G.K = a.H; G.ldw = a.H; G.gather = 1;
     G.w0 = blob; G.b = a.x;
     G.out = static_cast<S*>(a.h_routed) + (size_t)b0 * a.I;
-    G.wbytes = 2u * a.I * a.H * esz; G.bbytes = (unsigned)a.T * a.H * esz;
+    G.wbytes = 2u * a.I * a.H * wsz; G.bbytes = (unsigned)a.T * a.H * esz;
+    G.scale = scales;
   } else {
     G.N = a.H; G.K = a.I; G.ldw = a.I;
-    G.w0 = blob + 2 * (size_t)a.I * a.H;
+    G.w0 = blob + 2 * (size_t)a.I * a.H * wsz;
     G.b = static_cast<const S*>(a.h_routed) + (size_t)b0 * a.I;
     G.out = a.y + (size_t)b0 * a.H;
-    G.wbytes = (unsigned)a.H * a.I * esz; G.bbytes = (unsigned)G.m * a.I * esz;
+    G.wbytes = (unsigned)a.H * a.I * wsz; G.bbytes = (unsigned)G.m * a.I * esz;
+    G.scale = scales + 2 * (size_t)a.I;
   }
   return G;
 }

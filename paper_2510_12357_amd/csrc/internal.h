@@ -31,7 +31,13 @@ struct ProfScope {
 int device_cu_count();
 
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+// bytes of an activation / router-matrix element, and of an expert weight
 inline size_t elem_bytes(int dtype) { return dtype == MOE_FP32 ? 4 : 2; }
+inline size_t weight_bytes(int dtype) { return dtype == MOE_FP32 ? 4 : (dtype == MOE_BF16_W8 ? 1 : 2); }
+// one expert: [W_gate I x H | W_up I x H | W_down H x I] (+ the fp32 row scales of 8-bit weights)
+inline size_t expert_blob_bytes(int dtype, int H, int I) {
+  return (size_t)3 * H * I * weight_bytes(dtype) + (dtype == MOE_BF16_W8 ? (size_t)4 * (2 * (size_t)I + H) : 0);
+}
 
 // ---- skinny grouped GEMM  D[r][n] = sum_k W[n][k] * B[r][k]  (weights streamed once) --------
 // Three uses: router logits, gate/up projection with fused SwiGLU, down projection.
@@ -74,8 +80,9 @@ struct StreamArgs {
 };
 
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s);
-// bf16 kGateUp / kDown with the weights streamed through an LDS ring (stream_lds.hip)
-int launch_stream_lds(StreamMode mode, const StreamArgs& a, hipStream_t s);
+// kGateUp / kDown on bf16 activations with the weights (2 bytes: bf16, 1 byte: E4M3 + row
+// scales) streamed through an LDS ring (stream_lds.hip)
+int launch_stream_lds(StreamMode mode, int weight_bytes, const StreamArgs& a, hipStream_t s);
 
 // ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime, bf16) -------------------------
 int launch_tiled(StreamMode mode, const StreamArgs& a, hipStream_t s);

@@ -274,7 +274,7 @@ int launch_route(const moe_config& c, const float* conf, const float* logits, in
 int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,
                      hipStream_t s) {
   if (c.T == 0) return MOE_OK;
-  const bool bf = c.dtype == MOE_BF16;
+  const bool bf = c.dtype != MOE_FP32;
   if (c.T <= 4) {
     if (bf) launch_gemv<uint16_t, 1, 1>(c, x, Wg, bias, logits, s); else launch_gemv<float, 1, 1>(c, x, Wg, bias, logits, s);
   } else if (c.T <= 32) {

@@ -409,11 +409,16 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
 }  // namespace
 
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s) {
+  if (dtype == MOE_BF16_W8) {
+    // the router matrix of such a layer is bf16; its expert weights exist for the LDS kernel only
+    if (mode == kRouter) return launch_typed<BF16, kRouter, 4>(a, s);
+    return launch_stream_lds(mode, 1, a, s);
+  }
   if (dtype == MOE_BF16 && mode != kRouter) {
     // bf16 expert GEMMs stream through LDS (stream_lds.hip); MOE_STREAM_LDS=0 selects the
     // register-ring kernel of this file instead (read per call, so a test can flip it)
     const char* env = getenv("MOE_STREAM_LDS");
-    if (!env || atoi(env) != 0) return launch_stream_lds(mode, a, s);
+    if (!env || atoi(env) != 0) return launch_stream_lds(mode, 2, a, s);
   }
   if (dtype == MOE_BF16) {
     switch (mode) {

@@ -1,5 +1,6 @@
 // Skinny grouped GEMM for the decode regime with the weights streamed from HBM directly into
-// LDS (bf16 only; same operation, groups and work items as stream_gemm.hip).
+// LDS (bf16 activations; bf16 weights, or 8-bit E4M3 weights with fp32 row scales; same
+// operation, groups and work items as stream_gemm.hip).
 //
 //   kGateUp  h = silu(W_gate x) * (W_up x)     (execution stage of Sec. II-A, SwiGLU)
 //   kDown    y = W_down h
@@ -34,6 +35,11 @@
 //   * Groups with more than 32 token rows become several items that read the same weights; the
 //     item order places them 8 items apart, i.e. on workgroups of the same XCD at the same time,
 //     so that the repeats hit in that XCD's L2.
+//   * 8-bit weights (WB = 1): the same stages and loads carry 512 k per chunk.  A 16-byte column
+//     then holds 16 consecutive k of a row, i.e. the weights of two MFMA k-steps; the k order
+//     inside a chunk is permuted accordingly, and the token rows are loaded with the same
+//     permutation.  The computers widen the codes to bf16 (exact: 3 mantissa bits) in front of
+//     the MFMAs, and the row scale multiplies the fp32 sum in the epilogue.
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -51,8 +57,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int kKC = 256;                     // k per chunk
-constexpr int kRowBytes = kKC * 2;           // 512 B of one weight row per chunk
+constexpr int kRowBytes = 512;               // bytes of one weight row per chunk: 256 k in bf16, 512 k in 8 bits
 constexpr int kRows = 32;                    // weight rows per item
 constexpr int kStageBytes = kRows * kRowBytes;
 constexpr int kStages = 4;
@@ -60,7 +65,7 @@ constexpr int kWorkers = 4;                  // loader waves = computer waves
 constexpr int kThreadsL = 2 * kWorkers * 64;
 constexpr int kTok = 32;                     // token rows per item, at most (two tiles of 16)
 constexpr int kKParts = 2;                   // worker waves that split the k-steps of one token tile
-constexpr int kBLoads = kKC / 32 / kKParts;  // token-row loads per worker and chunk (k-steps of 32)
+constexpr int kReads = kRowBytes / 16 / 4 / kKParts;   // fragment reads (16-byte columns) per worker, row tile and chunk
 
 // vmcnt(n): bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima (no wait)
 #define MM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
@@ -87,7 +92,9 @@ struct Item {
   int r0, n0;       // first token row / first weight row of the item
   int ntn;          // token tiles in use (1..2)
   int gather, row0;
-  unsigned ldwb;    // bytes between rows of W and of B
+  unsigned ldwb;    // bytes between rows of W
+  unsigned ldbb;    // bytes between rows of B
+  const float* scale;   // 8-bit weights: row scales of the group (see Group::scale)
   unsigned wbytes, bbytes;
   const void* w0;
   const void* b;
@@ -97,7 +104,7 @@ struct Item {
   unsigned boff;        // computers: byte offset of this lane's token row (kOob: none)
 };
 
-template <int MODE>
+template <int MODE, int WB>
 __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int total, int n_groups,
                                             const int* s_prefix, const GroupSrc* s_src, int wave, int lane) {
   Item it;
@@ -113,7 +120,8 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   const int g = it.valid ? __builtin_amdgcn_readfirstlane(cnt) : 0;
   GroupSrc src = s_src[g];
   src.m = uni(src.m); src.row0 = uni(src.row0); src.blob = uni(src.blob);
-  const Group G = make_group<uint16_t, MODE>(a, g, src);
+  const Group G = make_group<uint16_t, MODE, WB>(a, g, src);
+  constexpr int KC = kRowBytes / WB;
   // Items of a group, in blocks of 8 row tiles: all token blocks of row tile (8 b + i) are
   // 8 items apart, i.e. they run at the same time on workgroups of the same XCD.
   const int local = item - uni(s_prefix[g]);
@@ -132,10 +140,12 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   it.n0 = row_item * per;
   it.K = it.valid ? G.K : 0;
   it.N = G.N; it.m = it.valid ? G.m : 0;
-  it.nch = (it.K + kKC - 1) / kKC;
+  it.nch = (it.K + KC - 1) / KC;
   it.ntn = clampi((it.m - it.r0 + 15) >> 4, 1, kTok / 16);
   it.gather = G.gather; it.row0 = G.row0;
-  it.ldwb = (unsigned)G.ldw * 2u;
+  it.ldwb = (unsigned)G.ldw * (unsigned)WB;
+  it.ldbb = (unsigned)G.ldw * 2u;
+  it.scale = G.scale;
   // an item that does not exist keeps valid pointers and empty buffers: every load is out of range
   it.wbytes = it.valid ? G.wbytes : 0u; it.bbytes = it.valid ? G.bbytes : 0u;
   it.w0 = it.valid ? G.w0 : a.x; it.b = it.valid ? G.b : a.x; it.out = G.out;
@@ -158,7 +168,7 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
     const bool val = it.valid && r < it.m;
     int row = r;
     if (it.gather) row = val ? clampi(a.sorted_token[it.row0 + r], 0, a.T - 1) : 0;
-    it.boff = val ? (unsigned)row * it.ldwb : kOob;
+    it.boff = val ? (unsigned)row * it.ldbb : kOob;
   }
   return it;
 }
@@ -171,8 +181,17 @@ struct Smem {
   int prefix[kMaxGroups + 1];
 };
 
-template <int MODE>
+// 8 E4M3 codes (two dwords, k ascending with the byte address) -> 8 bf16, exactly.
+__device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
+  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
+  const auto c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
+  return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
+}
+
+template <int MODE, int WB>
 __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4))) void stream_lds_kernel(const StreamArgs a) {
+  constexpr int KC = kRowBytes / WB;         // k per chunk
+  constexpr int kHalves = 2 / WB;            // MFMA k-steps fed by one 16-byte column: 1 (bf16) or 2 (8-bit)
   // One LDS object, ring first (1 KB aligned: every load instruction fills one aligned KB).
   __shared__ __attribute__((aligned(1024))) Smem sm;
   char* const s_ring = sm.ring;
@@ -188,7 +207,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   // ---- group table and item list ----
   for (int g = tid; g < n_groups; g += kThreadsL) {
     const GroupSrc src = load_group_src<MODE>(a, g);
-    const Group G = make_group<uint16_t, MODE>(a, g, src);
+    const Group G = make_group<uint16_t, MODE, WB>(a, g, src);
     const int rows = (G.N + (MODE == kGateUp ? 16 : 32) - 1) / (MODE == kGateUp ? 16 : 32);
     const int tgs = (G.m + kTok - 1) / kTok;
     s_src[g] = src;
@@ -216,7 +235,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
 
   if (wave < kWorkers) {
     // =================================== loader ===================================
-    Item it = decode_item<MODE>(a, 0, total, n_groups, s_prefix, s_src, wave, lane);
+    Item it = decode_item<MODE, WB>(a, 0, total, n_groups, s_prefix, s_src, wave, lane);
     Item nx = it;
     int j = 0, k = 0, drain = 0, s = 0;
     unsigned a_col[4], addr[4];     // logical 16-byte column per load instruction; running offsets
@@ -231,7 +250,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     for (;;) {
       const bool real = k < it.nch;                         // an item that does not exist has no chunks
       char* stage = s_ring + (s & (kStages - 1)) * kStageBytes + wave * 4096;
-      if (real && (k + 1) * kKC <= it.K) {                  // whole chunk inside K
+      if (real && (k + 1) * KC <= it.K) {                   // whole chunk inside K
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16, (int)addr[i], 0, 0, 0);
@@ -239,7 +258,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
         // last, partial chunk, or no chunk: lanes out of range fill their part of the stage with zeros
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int kk = k * kKC + (int)a_col[i] * 8;
+          const int kk = k * KC + (int)a_col[i] * (16 / WB);
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16,
                                                    (int)((real && kk < it.K) ? addr[i] : kOob), 0, 0, 0);
         }
@@ -248,7 +267,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
         ++k;
 #pragma unroll
         for (int i = 0; i < 4; ++i) addr[i] += kRowBytes;
-        if (k == 1) nx = decode_item<MODE>(a, j + 1, total, n_groups, s_prefix, s_src, wave, lane);   // under the loads
+        if (k == 1) nx = decode_item<MODE, WB>(a, j + 1, total, n_groups, s_prefix, s_src, wave, lane);   // under the loads
         if (k == it.nch) {
           it = nx; ++j; k = 0;
           rs = make_rsrc(it.w0, it.wbytes);
@@ -268,22 +287,40 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
 
   // =================================== computer ===================================
   const int c = wave - kWorkers, tw = c & 1, kp = c >> 1;
-  Item cur = decode_item<MODE>(a, 0, total, n_groups, s_prefix, s_src, c, lane);
-  Item nx = decode_item<MODE>(a, 1, total, n_groups, s_prefix, s_src, c, lane);
+  Item cur = decode_item<MODE, WB>(a, 0, total, n_groups, s_prefix, s_src, c, lane);
+  Item nx = decode_item<MODE, WB>(a, 1, total, n_groups, s_prefix, s_src, c, lane);
   int j = 0, k = 0;                 // item ordinal and chunk being consumed
   int pending = 0;                  // the previous item's partial sums wait for their epilogue
   int need_nx = 0;                  // nx is stale (cur just moved on)
   int f_r0 = 0, f_n0 = 0, f_m = 0, f_N = 0, f_ntn = 0;
   void* f_out = nullptr;
+  // 8-bit weights: the row scales this lane's outputs need, loaded when an item starts (sc) and
+  // kept for the item whose epilogue is pending (f_sc), so that no epilogue waits for memory
+  f32x4 sc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}}, f_sc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
+  auto load_scales = [&](const Item& it) {
+    if (WB != 1) return;
+    // gate rows n0 + 4q + v and the same up rows (N further on); down rows n0 + 16 rt + 4q + v
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const int n = (MODE == kGateUp) ? it.n0 + 4 * q : it.n0 + rt * 16 + 4 * q;
+      const bool ok = it.valid && n < it.N;                 // N is a multiple of 16: all four or none
+      const float* p = it.scale + ((MODE == kGateUp && rt == 1) ? it.N + n : n);
+      sc[rt] = ok ? *reinterpret_cast<const f32x4*>(p) : f32x4{0, 0, 0, 0};
+    }
+  };
+  load_scales(cur);
   const unsigned ring_base = (unsigned)(size_t)s_ring;
   const unsigned b_lane = (unsigned)(kp * 64 + q * 16);     // this lane's bytes into a chunk of a token row
-  unsigned rd_off[kBLoads];         // LDS offsets of this lane's fragments inside a stage (row tile 0)
+  unsigned rd_off[kReads];          // LDS offsets of this lane's fragments inside a stage (row tile 0)
 #pragma unroll
-  for (int t = 0; t < kBLoads; ++t)
+  for (int t = 0; t < kReads; ++t)
     rd_off[t] = ring_base + (unsigned)c16 * kRowBytes + (unsigned)((((kp + t * kKParts) * 4 + q) ^ c16) * 16);
-  i32x4 bbuf[kBLoads];
+  // token rows of one chunk: for read t, the 8 k (bf16) or 2 x 8 k (8-bit) behind column (kp + 2t) * 4 + q
+  i32x4 bbuf[kReads][kHalves];
 #pragma unroll
-  for (int t = 0; t < kBLoads; ++t) bbuf[t] = i32x4{0, 0, 0, 0};
+  for (int t = 0; t < kReads; ++t)
+#pragma unroll
+    for (int h = 0; h < kHalves; ++h) bbuf[t][h] = i32x4{0, 0, 0, 0};
   f32x4 acc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
 
   auto epilogue = [&]() {
@@ -294,6 +331,12 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int v = 0; v < 4; ++v) val[rt][v] = s_red[tw][rt][v][lane] + s_red[tw + 2][rt][v][lane];
+      if (WB == 1) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) val[rt][v] *= f_sc[rt][v];
+      }
       const int r = f_r0 + tw * 16 + c16;
       if (r < f_m) {
         if (MODE == kGateUp) {
@@ -327,8 +370,8 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     if (s >= 3 && cur.valid) {
       if (tw < cur.ntn) {
         const unsigned st = (unsigned)(((s + 1) & (kStages - 1)) * kStageBytes);
-        bf16x8 f0[kBLoads], f1[kBLoads];                     // row tile 0 / 1, one per k-step
-        static_assert(kBLoads == 4, "the fragment reads below are written for four k-steps per wave");
+        bf16x8 f0[kReads], f1[kReads];                       // row tile 0 / 1, one 16-byte column each
+        static_assert(kReads == 4, "the fragment reads below are written for four columns per wave and row tile");
         asm volatile(
             "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:8192\n"
             "ds_read_b128 %2, %9\n ds_read_b128 %3, %9 offset:8192\n"
@@ -339,10 +382,20 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
             : "v"(rd_off[0] + st), "v"(rd_off[1] + st), "v"(rd_off[2] + st), "v"(rd_off[3] + st)
             : "memory");
 #pragma unroll
-        for (int t = 0; t < kBLoads; ++t) {
-          const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t]);
-          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
+        for (int t = 0; t < kReads; ++t) {
+          if (WB == 2) {
+            const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][0]);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
+          } else {
+            const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
+#pragma unroll
+            for (int h = 0; h < kHalves; ++h) {
+              const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
+              acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w0[2 * h], w0[2 * h + 1]), bv, acc[0], 0, 0, 0);
+              acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w1[2 * h], w1[2 * h + 1]), bv, acc[1], 0, 0, 0);
+            }
+          }
         }
       }
       if (++k == cur.nch) {         // item done: hand the partial sums over, move on
@@ -352,6 +405,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
           for (int v = 0; v < 4; ++v) s_red[c][rt][v][lane] = acc[rt][v];
         acc[0] = f32x4{0, 0, 0, 0}; acc[1] = f32x4{0, 0, 0, 0};
         f_r0 = cur.r0; f_n0 = cur.n0; f_m = cur.m; f_N = cur.N; f_ntn = cur.ntn; f_out = cur.out;
+        f_sc[0] = sc[0]; f_sc[1] = sc[1];
         pending = 1;
         cur = nx; ++j; k = 0;
         need_nx = 1;
@@ -359,30 +413,38 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     }
     // Token rows of the chunk consumed in the next iteration: issued here, behind the MFMAs that
     // read the previous ones, they arrive while this wave waits at the two barriers.
-    if (s >= 2) {                   // that chunk is (cur, k): the one after the chunk just consumed
+    if (s >= 2 && tw < cur.ntn) {   // that chunk is (cur, k): the one after the chunk just consumed; a wave
+                                    // whose token tile is empty loads nothing (its MFMAs are skipped as well)
       // Nothing of this wave is in flight any more (the previous token rows were consumed or
       // belong to a tile this wave skips).  Saying so keeps the compiler from guarding every one
       // of the loads below against a load of the previous iteration into the same registers.
       MM_WAIT_VMCNT(0);
       const __amdgpu_buffer_rsrc_t rb = make_rsrc(cur.b, cur.bbytes);
 #pragma unroll
-      for (int t = 0; t < kBLoads; ++t) {
-        const int kk = k * kKC + (kp + t * kKParts) * 32 + q * 8;
-        const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
-        bbuf[t] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
-      }
+      for (int t = 0; t < kReads; ++t)
+#pragma unroll
+        for (int h = 0; h < kHalves; ++h) {
+          // the k behind 16-byte column (kp + 2t) * 4 + q of the weight rows (second half: h = 1)
+          const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * (16 / WB) + h * 8;
+          const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
+          bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
+        }
     }
     lds_barrier();                                          // "free"; partial sums of an item that ended are complete
     // what follows runs while the loaders wait for their next chunk
     if (pending) { pending = 0; epilogue(); }
-    if (need_nx) { need_nx = 0; nx = decode_item<MODE>(a, j + 1, total, n_groups, s_prefix, s_src, c, lane); }
+    if (need_nx) {
+      need_nx = 0;
+      load_scales(cur);
+      nx = decode_item<MODE, WB>(a, j + 1, total, n_groups, s_prefix, s_src, c, lane);
+    }
     return cur.valid || s < 2;
   };
 
   for (int s = 0; step(s); ++s) {}
 }
 
-template <int MODE>
+template <int MODE, int WB>
 int launch_lds_typed(const StreamArgs& a, hipStream_t s) {
   const long items = item_upper_bound((StreamMode)MODE, a, kTok);
   if (items <= 0) return MOE_OK;
@@ -390,25 +452,27 @@ int launch_lds_typed(const StreamArgs& a, hipStream_t s) {
   static int per_cu = 0;
   if (per_cu == 0) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, stream_lds_kernel<MODE>, kThreadsL, 0) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, stream_lds_kernel<MODE, WB>, kThreadsL, 0) != hipSuccess || n < 1) n = 1;
     if (const char* env = getenv("MOE_STREAM_WG_PER_CU")) { const int v = atoi(env); if (v > 0) n = v; }
     per_cu = n;
   }
   long grid = (long)device_cu_count() * per_cu;
   if (grid > items) grid = items;
-  hipLaunchKernelGGL((stream_lds_kernel<MODE>), dim3((unsigned)grid), dim3(kThreadsL), 0, s, a);
+  hipLaunchKernelGGL((stream_lds_kernel<MODE, WB>), dim3((unsigned)grid), dim3(kThreadsL), 0, s, a);
   return hip_fail(hipGetLastError(), "stream_lds_kernel launch");
 }
 
 }  // namespace
 
-int launch_stream_lds(StreamMode mode, const StreamArgs& a, hipStream_t s) {
-  switch (mode) {
-    case kGateUp: return launch_lds_typed<kGateUp>(a, s);
-    case kDown: return launch_lds_typed<kDown>(a, s);
-    default: break;
+int launch_stream_lds(StreamMode mode, int weight_bytes, const StreamArgs& a, hipStream_t s) {
+  if (weight_bytes == 2) {
+    if (mode == kGateUp) return launch_lds_typed<kGateUp, 2>(a, s);
+    if (mode == kDown) return launch_lds_typed<kDown, 2>(a, s);
+  } else if (weight_bytes == 1) {
+    if (mode == kGateUp) return launch_lds_typed<kGateUp, 1>(a, s);
+    if (mode == kDown) return launch_lds_typed<kDown, 1>(a, s);
   }
-  return fail(MOE_E_BADARG, "bad stream mode");
+  return fail(MOE_E_BADARG, "bad stream mode / weight width");
 }
 
 }  // namespace mm
