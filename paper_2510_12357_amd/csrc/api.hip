@@ -194,6 +194,16 @@ extern "C" int moe_route(const moe_config* cfg, const void* x, const void* Wg, c
   hipStream_t s = static_cast<hipStream_t>(stream);
   // decode sizes: plain-FMA GEMV spread over many waves; larger T: MFMA router GEMM
   constexpr int kGemvMaxT = 256;
+  // decode batches: logits and selection of a token in one workgroup, one launch
+  static int fused_max_t = -1;
+  if (fused_max_t < 0) {
+    fused_max_t = 64;
+    if (const char* env = getenv("MOE_FUSED_ROUTE_MAX_T")) fused_max_t = atoi(env) >= 0 ? atoi(env) : 64;
+  }
+  if (!logits_given && cfg->T <= fused_max_t) {
+    ProfScope ps(kProfRouteTopk, s);
+    return launch_gate_route(*cfg, x, Wg, gate_bias, conf, logits, topk_idx, topk_w, important, k_t, s);
+  }
   if (!logits_given) {
     ProfScope ps(kProfRouterGemm, s);
     if (cfg->T <= kGemvMaxT) {

@@ -92,6 +92,8 @@ int launch_route(const moe_config& c, const float* conf, const float* logits, in
                  float* w, uint8_t* important, int32_t* k_t, hipStream_t s);
 int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,
                      hipStream_t s);
+int launch_gate_route(const moe_config& c, const void* x, const void* Wg, const float* bias, const float* conf,
+                      float* logits, int32_t* idx, float* w, uint8_t* important, int32_t* k_t, hipStream_t s);
 int launch_confidence(const float* z, int T, int V, float* conf, hipStream_t s);
 int dispatch_chunks(int T);          // workgroups (token chunks) of the large-T dispatch
 // pairs (t, j) with j_lo <= j < k_t[t]

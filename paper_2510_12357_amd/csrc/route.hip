@@ -7,10 +7,13 @@
 // selection decisions are comparisons on the fp32 logits, so they are exact and reproducible.
 //
 // Kernels:
-//   gate_gemv_kernel  router logits at decode sizes (few tokens): plain fp32 FMAs, one wave per
+//   gate_route_kernel router logits and selection of one token per workgroup (decode batches)
+//   gate_gemv_kernel  router logits alone (up to 256 tokens): plain fp32 FMAs, one wave per
 //                     small block of logits, so that even one token spreads over E waves
 //   route_kernel      softmax / importance / top-k on given logits
 #include <math.h>
+
+#include <type_traits>
 
 #include "internal.h"
 
@@ -20,20 +23,34 @@ namespace {
 constexpr int kPerLane = MOE_MAX_EXPERTS / 64;   // 4
 constexpr int kWavesPerBlock = 4;
 
+// Wave-wide reductions on the data-parallel-primitive path (no LDS round trips): quads, half
+// rows and rows with quad_perm / row_half_mirror / row_mirror, then lane 15 of a row into the
+// next row and lane 31 into rows 2 and 3, so that lane 63 holds the result, which is read back
+// as a scalar.  `ident` is what a lane outside the row mask contributes.
+template <typename T, typename Op>
+__device__ __forceinline__ T wave_reduce(T v, T ident, Op op) {
+  const auto dpp = [](T old, T x, auto ctrl, auto rows) {
+    const int r = __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, x),
+                                              decltype(ctrl)::value, decltype(rows)::value, 0xf, false);
+    return __builtin_bit_cast(T, r);
+  };
+  using std::integral_constant;
+  v = op(v, dpp(v, v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xf>{}));    // quad_perm [1,0,3,2]
+  v = op(v, dpp(v, v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xf>{}));    // quad_perm [2,3,0,1]
+  v = op(v, dpp(v, v, integral_constant<int, 0x141>{}, integral_constant<int, 0xf>{}));   // row_half_mirror
+  v = op(v, dpp(v, v, integral_constant<int, 0x140>{}, integral_constant<int, 0xf>{}));   // row_mirror
+  v = op(v, dpp(ident, v, integral_constant<int, 0x142>{}, integral_constant<int, 0xa>{}));   // row_bcast:15 into rows 1, 3
+  v = op(v, dpp(ident, v, integral_constant<int, 0x143>{}, integral_constant<int, 0xc>{}));   // row_bcast:31 into rows 2, 3
+  return __builtin_bit_cast(T, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d));
-  return v;
+  return wave_reduce(v, -INFINITY, [](float a, float b) { return fmaxf(a, b); });
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  return v;
+  return wave_reduce(v, 0.f, [](float a, float b) { return a + b; });
 }
 __device__ __forceinline__ int wave_min_int(int v) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v = min(v, __shfl_xor(v, d));
-  return v;
+  return wave_reduce(v, 0x7fffffff, [](int a, int b) { return min(a, b); });
 }
 
 struct RouteParams {
@@ -223,6 +240,76 @@ void launch_gemv(const moe_config& c, const void* x, const void* Wg, const float
                      c.T, c.H, c.E, logits);
 }
 
+// Router logits and selection of one token in one workgroup (decode batches): the waves split the
+// experts, every wave sums its experts' dot products exactly as gate_gemv_kernel does (per lane
+// the 8-element chunks lane, lane + 64, ... in ascending order, then the same shuffle reduction),
+// so the logits are bit-identical to that kernel's; they go to global memory and to LDS, and wave
+// 0 selects from LDS.  One launch instead of two dependent ones.
+constexpr int kFusedWaves = 16;
+
+template <typename S>
+__global__ __launch_bounds__(kFusedWaves * 64) void gate_route_kernel(const S* __restrict__ x,
+                                                                       const S* __restrict__ Wg,
+                                                                       const float* __restrict__ bias, int H,
+                                                                       float* __restrict__ logits,
+                                                                       const RouteParams P) {
+  __shared__ float s_logit[MOE_MAX_EXPERTS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x, E = P.E;
+  const S* xr = x + (size_t)t * H;
+  const int nchunk = H >> 3;
+  constexpr int U = sizeof(S) == 2 ? 4 : 2;
+  constexpr int TE = 4;                                // experts per pass of a wave
+  for (int e0 = wave * TE; e0 < E; e0 += kFusedWaves * TE) {
+    float acc[TE];
+#pragma unroll
+    for (int a = 0; a < TE; ++a) acc[a] = 0.f;
+    for (int c0 = lane; c0 < nchunk; c0 += 64 * U) {
+      Raw8<S> xv[U], wv[U][TE];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int c = min(c0 + 64 * u, nchunk - 1);    // a chunk past the end is loaded again and skipped
+        xv[u].load(xr + c * 8);
+#pragma unroll
+        for (int a = 0; a < TE; ++a) wv[u][a].load(Wg + (size_t)min(e0 + a, E - 1) * H + c * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (c0 + 64 * u < nchunk) {
+          float xf[8];
+          xv[u].get(xf);
+#pragma unroll
+          for (int a = 0; a < TE; ++a) {
+            float wf[8];
+            wv[u][a].get(wf);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[a] = fmaf(xf[i], wf[i], acc[a]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < TE; ++a) {
+      const float sum = wave_sum(acc[a]);
+      const int e = e0 + a;
+      if (lane == 0 && e < E) {
+        const float z = sum + (bias ? bias[e] : 0.f);
+        logits[(size_t)t * E + e] = z;
+        s_logit[e] = z;
+      }
+    }
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  float raw[kPerLane];
+#pragma unroll
+  for (int c = 0; c < kPerLane; ++c) {
+    const int e = lane + 64 * c;
+    raw[c] = (e < E) ? s_logit[e] : 0.f;
+  }
+  select_token(P, t, lane, raw);
+}
+
 // conf[t] = 1 / sum_v exp(z_tv - max_v z_tv): one workgroup per token, two sweeps over the row.
 constexpr int kConfThreads = 256;
 __global__ __launch_bounds__(kConfThreads) void confidence_kernel(const float* __restrict__ z, int V,
@@ -269,6 +356,20 @@ int launch_route(const moe_config& c, const float* conf, const float* logits, in
   hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(kWavesPerBlock * 64), 0, s, logits,
                      make_params(c, conf, idx, w, important, k_t));
   return hip_fail(hipGetLastError(), "route_kernel launch");
+}
+
+// Router logits + selection in one launch; for steps of at most kFusedRouteMaxT tokens.
+int launch_gate_route(const moe_config& c, const void* x, const void* Wg, const float* bias, const float* conf,
+                      float* logits, int32_t* idx, float* w, uint8_t* important, int32_t* k_t, hipStream_t s) {
+  if (c.T == 0) return MOE_OK;
+  const RouteParams P = make_params(c, conf, idx, w, important, k_t);
+  if (c.dtype != MOE_FP32)
+    hipLaunchKernelGGL(gate_route_kernel<uint16_t>, dim3((unsigned)c.T), dim3(kFusedWaves * 64), 0, s,
+                       static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(Wg), bias, c.H, logits, P);
+  else
+    hipLaunchKernelGGL(gate_route_kernel<float>, dim3((unsigned)c.T), dim3(kFusedWaves * 64), 0, s,
+                       static_cast<const float*>(x), static_cast<const float*>(Wg), bias, c.H, logits, P);
+  return hip_fail(hipGetLastError(), "gate_route_kernel launch");
 }
 
 int launch_gate_gemv(const moe_config& c, const void* x, const void* Wg, const float* bias, float* logits,

@@ -443,3 +443,31 @@ def test_many_experts_and_largest_top_k():
     # group tables near their limits: 200 routed experts + 4 shared experts, top-16 of them
     check_layer(cfg_small(T=33, E=200, k_big=16, k_little=8, shared_I=(24, 40, 8, 16), I=72), seed=8)
     check_layer(cfg_small(T=3, E=256, k_big=16, k_little=8, shared_I=(), I=40), seed=9)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_one_launch_router_equals_the_two_kernels(dtype):
+    """Steps of at most 64 tokens compute router logits and selection in one launch; larger steps use
+    the separate logits kernel and the selection kernel.  Same rows in: bit-identical logits and
+    selections out, and the selections are the oracle's on those logits."""
+    cfg = cfg_small(T=40, E=60, k_big=4, k_little=2, dtype=dtype, gate_bias_std=0.5, fallback_ratio=0.4)
+    layer = wl.make_layer(cfg, seed=12, experts=False)
+    x, Wg = mm.to_device(layer.x, cfg), mm.to_device(layer.Wg, cfg)
+    bias, conf = torch.from_numpy(layer.gate_bias).cuda(), torch.from_numpy(layer.conf).cuda()
+    b1 = mm.StepBuffers(cfg)
+    mm.moe_route(b1.c, x, Wg, bias, conf, b1.logits, False, b1.topk_idx, b1.topk_w, b1.important, b1.k_t)
+    big = cfg.with_(T=100)
+    rows = torch.arange(100, device="cuda") % cfg.T
+    b2 = mm.StepBuffers(big)
+    mm.moe_route(b2.c, x[rows].contiguous(), Wg, bias, conf[rows].contiguous(), b2.logits, False, b2.topk_idx,
+                 b2.topk_w, b2.important, b2.k_t)
+    torch.cuda.synchronize()
+    assert torch.equal(b1.logits, b2.logits[:cfg.T])
+    assert torch.equal(b1.topk_idx, b2.topk_idx[:cfg.T]) and torch.equal(b1.topk_w, b2.topk_w[:cfg.T])
+    assert torch.equal(b1.k_t, b2.k_t[:cfg.T]) and torch.equal(b1.important, b2.important[:cfg.T])
+    idx, w, imp, kt = oracle.route(b1.logits.cpu().numpy(), layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, cfg.renorm)
+    assert np.array_equal(i32(b1.topk_idx), idx) and np.array_equal(i32(b1.k_t), kt)
+    assert np.array_equal(b1.important.cpu().numpy(), imp)
+    np.testing.assert_allclose(b1.topk_w.cpu().numpy(), w, rtol=2e-6, atol=1e-9)
+    assert rel_err(b1.logits.cpu().numpy(), oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)) <= \
+        (TOL_OUT if dtype == "bf16" else 1e-4)
