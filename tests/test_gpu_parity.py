@@ -445,12 +445,14 @@ def test_many_experts_and_largest_top_k():
     check_layer(cfg_small(T=3, E=256, k_big=16, k_little=8, shared_I=(), I=40), seed=9)
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
-def test_one_launch_router_equals_the_two_kernels(dtype):
+@pytest.mark.parametrize("dtype,T,E,kb", [("bf16", 40, 60, 4), ("fp32", 40, 60, 4), ("bf16", 64, 256, 16),
+                                          ("bf16", 1, 7, 3)])
+def test_one_launch_router_equals_the_two_kernels(dtype, T, E, kb):
     """Steps of at most 64 tokens compute router logits and selection in one launch; larger steps use
     the separate logits kernel and the selection kernel.  Same rows in: bit-identical logits and
     selections out, and the selections are the oracle's on those logits."""
-    cfg = cfg_small(T=40, E=60, k_big=4, k_little=2, dtype=dtype, gate_bias_std=0.5, fallback_ratio=0.4)
+    cfg = cfg_small(T=T, E=E, k_big=kb, k_little=max(1, kb // 2), dtype=dtype, gate_bias_std=0.5,
+                    fallback_ratio=0.4)
     layer = wl.make_layer(cfg, seed=12, experts=False)
     x, Wg = mm.to_device(layer.x, cfg), mm.to_device(layer.Wg, cfg)
     bias, conf = torch.from_numpy(layer.gate_bias).cuda(), torch.from_numpy(layer.conf).cuda()
