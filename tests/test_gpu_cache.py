@@ -74,8 +74,8 @@ def run_offloaded(cfg, n_slots, seed, steps=2, prefetch=False):
     """The layer with routed experts in pinned host DRAM behind an n_slots cache."""
     layer = wl.make_layer(cfg, seed=seed)
     dl = DeviceLayer(layer)                    # x, Wg, shared experts on the device
-    blob_elems = 3 * cfg.H * cfg.I
     host = torch.stack([mm.to_device(b, cfg, "cpu") for b in layer.expert_w]).pin_memory()
+    blob_elems = host.shape[1]                 # 3*H*I weights; 8-bit blobs also carry their row scales
     slots_dev = torch.zeros((n_slots, blob_elems), dtype=host.dtype, device="cuda")
     h = mm.moe_cache_create(cfg.E, blob_elems * host.element_size(), n_slots, host, slots_dev)
     logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
@@ -130,3 +130,11 @@ def test_shared2_offload_config_full_size():
     assert D > 16                                               # the step needs more experts than slots
     assert stats[0][0] + stats[0][1] == D and stats[0][0] >= 1  # prefetched experts count as hits
     assert stats[0][2] == -(-D // 16)
+
+
+def test_offloaded_layer_with_8_bit_experts():
+    cfg = wl.LayerConfig("off_w8", T=16, H=272, E=12, I=144, k_big=4, k_little=2, shared_I=(80,), dtype="bf16w8",
+                         gate_std=0.3, w_std=0.1, fallback_ratio=0.3)
+    stats, ref = run_offloaded(cfg, n_slots=5, seed=3)
+    D = int((np.diff(ref["expert_offsets"]) > 0).sum())
+    assert D > 5 and stats[0][1] == D and stats[0][2] == -(-D // 5)
