@@ -69,6 +69,20 @@ def workload_config(name: str, ratio: float):
     raise SystemExit(f"unknown workload {name}")
 
 
+def random_blob(torch, g, cfg, I: int):
+    """One expert blob on the device: random weights in the layer's storage type; 8-bit blobs are E4M3
+    codes (torch's float8_e4m3fn cast) followed by the fp32 row scales that map a row's peak to 448."""
+    w = torch.randn((3 * cfg.H * I,), generator=g, device="cuda", dtype=torch.float32) * cfg.w_std
+    if cfg.dtype != "bf16w8":
+        return w.to(torch.float32 if cfg.dtype == "fp32" else torch.bfloat16)
+    parts, scales = [], []
+    for m in (w[:I * cfg.H].view(I, cfg.H), w[I * cfg.H:2 * I * cfg.H].view(I, cfg.H), w[2 * I * cfg.H:].view(cfg.H, I)):
+        s = m.abs().amax(dim=1) / 448.0
+        parts.append((m / s[:, None]).to(torch.float8_e4m3fn).view(torch.uint8).reshape(-1))
+        scales.append(s)
+    return torch.cat(parts + [torch.cat(scales).view(torch.uint8)])
+
+
 class DeviceLayers:
     """L synthetic layers generated on the device with a seeded torch generator (inputs only)."""
 
@@ -86,18 +100,7 @@ class DeviceLayers:
             return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
 
         def weights(I):
-            """One expert blob: random weights in the layer's storage type; 8-bit blobs are E4M3 codes
-            (torch's float8_e4m3fn cast) followed by the fp32 row scales that map a row's peak to 448."""
-            if not w8:
-                return randn((3 * cfg.H * I,), cfg.w_std)
-            w = torch.randn((3 * cfg.H * I,), generator=g, device="cuda", dtype=torch.float32) * cfg.w_std
-            parts, scales = [], []
-            for m in (w[:I * cfg.H].view(I, cfg.H), w[I * cfg.H:2 * I * cfg.H].view(I, cfg.H),
-                      w[2 * I * cfg.H:].view(cfg.H, I)):
-                s = m.abs().amax(dim=1) / 448.0
-                parts.append((m / s[:, None]).to(torch.float8_e4m3fn).view(torch.uint8).reshape(-1))
-                scales.append(s)
-            return torch.cat(parts + [torch.cat(scales).view(torch.uint8)])
+            return random_blob(torch, g, cfg, I)
 
         self.x, self.Wg, self.bias, self.experts, self.table, self.shared, self.conf = [], [], [], [], [], [], []
         for l in range(L):
@@ -208,24 +211,26 @@ def time_offload(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16, pre
     known one step ahead, as for a token whose little pass was discarded).
     -> step time, hits / misses per step, achieved host-to-device rate."""
     DEMAND, PREFETCH = 0, 1
-    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    dt = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
     g = torch.Generator(device="cuda")
     g.manual_seed(7)
-    blob = 3 * cfg.H * cfg.I
 
     def randn(shape, std):
         return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
 
-    host = torch.empty((cfg.E, blob), dtype=dt).pin_memory()
-    for e in range(cfg.E):
-        host[e].copy_(randn((blob,), cfg.w_std))
+    first = random_blob(torch, g, cfg, cfg.I)
+    blob = first.numel()
+    host = torch.empty((cfg.E, blob), dtype=first.dtype).pin_memory()
+    host[0].copy_(first)
+    for e in range(1, cfg.E):
+        host[e].copy_(random_blob(torch, g, cfg, cfg.I))
     Wg = randn((cfg.E, cfg.H), cfg.gate_std)
-    shared = [randn((3 * cfg.H * Is,), cfg.w_std) for Is in cfg.shared_I]
+    shared = [random_blob(torch, g, cfg, Is) for Is in cfg.shared_I]
     nb = 8
     xs = [randn((cfg.T, cfg.H), 1.0) for _ in range(nb)]
     from paper_2510_12357_amd import workloads as wl
     confs = [torch.from_numpy(wl.make_confidence(100 + i, cfg.T, cfg.gamma, cfg.fallback_ratio)).cuda() for i in range(nb)]
-    slots = torch.zeros((n_slots, blob), dtype=dt, device="cuda")
+    slots = torch.zeros((n_slots, blob), dtype=host.dtype, device="cuda")
     h = mm.moe_cache_create(cfg.E, blob * host.element_size(), n_slots, host, slots)
     bufs = [mm.StepBuffers(cfg) for _ in range(2)]
     wanted = {}
@@ -352,19 +357,21 @@ def time_alg1_offload(mm, torch, cfg, steps: int, warmup: int, L: int, n_slots: 
     B = cfg.T
     g = torch.Generator(device="cuda")
     g.manual_seed(11)
-    dt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
-    blob = 3 * cfg.H * cfg.I
+    dt = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
 
     def randn(shape, std):
         return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
     host, layers = [], []
     for l in range(L):
-        h = torch.empty((cfg.E, blob), dtype=dt).pin_memory()
-        for e in range(cfg.E):
-            h[e].copy_(randn((blob,), cfg.w_std))
+        first = random_blob(torch, g, cfg, cfg.I)
+        h = torch.empty((cfg.E, first.numel()), dtype=first.dtype).pin_memory()
+        h[0].copy_(first)
+        for e in range(1, cfg.E):
+            h[e].copy_(random_blob(torch, g, cfg, cfg.I))
         host.append(h)
         layers.append(dict(Wg=randn((cfg.E, cfg.H), cfg.gate_std), gate_bias=None, table=None,
-                           shared=[randn((3 * cfg.H * Is,), cfg.w_std) for Is in cfg.shared_I]))
+                           shared=[random_blob(torch, g, cfg, Is) for Is in cfg.shared_I]))
+    blob = host[0].shape[1]
     embed = randn((V, cfg.H), 1.0)
     head32 = torch.randn((V, cfg.H), generator=g, device="cuda")
     prompts = wl.make_prompt_tokens(5, 1 << 16, V)
@@ -555,7 +562,9 @@ def main():
         light = real.with_(name="light_offload", H=1024, I=256, shared_I=(256, 256))
         res = dict(metric="Alg. 1 with offloaded experts: step time by prefetch distance",
                    shared2_offload=time_alg1_offload(mm, torch, real, args.steps, args.warmup, L, 48, ratio=args.ratio),
-                   light_offload=time_alg1_offload(mm, torch, light, args.steps, args.warmup, L, 48, ratio=args.ratio))
+                   light_offload=time_alg1_offload(mm, torch, light, args.steps, args.warmup, L, 48, ratio=args.ratio),
+                   shared2_offload_w8=time_alg1_offload(mm, torch, real.with_(dtype="bf16w8"), args.steps, args.warmup, L,
+                                                        48, ratio=args.ratio, distances=(0, 1)))
         print(json.dumps(res))
         return
 
@@ -655,7 +664,8 @@ def main():
         oc = wl.CONFIGS["shared2_offload"].with_(fallback_ratio=args.ratio)
         # (prefetching the next batch's experts cannot help a single layer whose demand misses already
         # saturate the link: there is no other layer's compute to hide the copies under)
-        others["shared2_offload_b16"] = dict(demand_only=time_offload(mm, torch, oc, 24, 8))
+        others["shared2_offload_b16"] = dict(demand_only=time_offload(mm, torch, oc, 24, 8),
+                                             demand_only_w8=time_offload(mm, torch, oc.with_(dtype="bf16w8"), 24, 8))
         torch.cuda.empty_cache()
         # Alg. 1 end to end on a toy language model made of this layer (realised fallback ratio)
         others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 10,

@@ -47,8 +47,8 @@ class ToyLMDevice:
         self.cfg, self.V, self.device = cfg, V, embed.device
         self.embed, self.head, self.layers, self.norm = embed, head, layers, norm
         # the head as a "router" over V outputs with one selected entry
-        self.head_cfg = wl.LayerConfig("lm_head", T=1, H=cfg.H, E=V, I=8, k_big=1, k_little=1,
-                                       dtype=cfg.dtype, gamma=cfg.gamma)
+        self.head_cfg = wl.LayerConfig("lm_head", T=1, H=cfg.H, E=V, I=16, k_big=1, k_little=1,
+                                       dtype="fp32" if cfg.dtype == "fp32" else "bf16", gamma=cfg.gamma)
 
     @classmethod
     def upload(cls, lm: wl.ToyLM, device="cuda") -> "ToyLMDevice":
