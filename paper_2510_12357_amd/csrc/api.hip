@@ -288,7 +288,12 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
     return fail(MOE_E_BADARG, "moe_expert_ffn: shared part needs shared_w and shared_out");
   if (shared)
     for (int s = 0; s < cfg->n_shared; ++s)
+    {
       if (!shared_w[s]) return fail(MOE_E_BADARG, "moe_expert_ffn: shared_w[%d] is NULL", s);
+      // expert blobs are read in 16-byte pieces (the routed experts' pointers live on the device
+      // and cannot be checked here)
+      if ((uintptr_t)shared_w[s] & 15) return fail(MOE_E_BADARG, "moe_expert_ffn: shared_w[%d] is not 16-byte aligned", s);
+    }
   const FfnLayout L = ffn_layout(*cfg);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < L.total)
     return fail(MOE_E_WORKSPACE, "moe_expert_ffn: workspace %p of %zu bytes (need %zu, 256-byte aligned)", ws,

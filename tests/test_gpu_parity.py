@@ -225,6 +225,15 @@ def test_zero_tokens_and_bad_arguments():
         mm.moe_dispatch(ok.c, ok.topk_idx, ok.k_t, ok.expert_offsets, ok.sorted_token, ok.sorted_rank,
                         ok.inv_pos, ok.dws, 0)
     assert ei.value.code == -6
+    # a shared expert blob that is not 16-byte aligned is refused before anything is launched
+    one = cfg_small(T=4)
+    l1 = DeviceLayer(wl.make_layer(one, seed=0))
+    b1 = mm.StepBuffers(one)
+    raw = torch.zeros(l1.shared[0].numel() + 8, dtype=l1.shared[0].dtype, device="cuda")
+    with pytest.raises(mm.MoeError) as ei:
+        mm.moe_expert_ffn(b1.c, l1.x, b1.expert_offsets, b1.sorted_token, None, [raw[1:]], False, True, b1.y,
+                          b1.shared_out, b1.fws, b1.fws_bytes)
+    assert ei.value.code == -1
 
 
 def test_null_expert_pointer_skips_expert():
