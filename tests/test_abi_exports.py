@@ -45,3 +45,12 @@ def test_config_validation_codes_without_gpu():
         rc = lib.moe_combine(ctypes.byref(c), None, None, None, None, None, None, None)
         assert rc == code, (bad, rc, mm.moe_last_error())
         assert mm.moe_last_error()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """Every box of this build has one GPU: the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "single-GPU" in (r.stderr + r.stdout)
