@@ -247,7 +247,9 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     }
     __amdgpu_buffer_rsrc_t rs = make_rsrc(it.w0, it.wbytes);
     MM_WAIT_VMCNT(0);
-    for (;;) {
+    // Issues the next chunk of the stream (4 loads of this wave) into stage s & 3 and advances;
+    // false for a slot behind the last chunk (4 loads that only zero-fill).
+    auto issue_next = [&]() -> bool {
       const bool real = k < it.nch;                         // an item that does not exist has no chunks
       char* stage = s_ring + (s & (kStages - 1)) * kStageBytes + wave * 4096;
       if (real && (k + 1) * KC <= it.K) {                   // whole chunk inside K
@@ -275,10 +277,14 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
           for (int i = 0; i < 4; ++i) addr[i] = it.a_row[i] + a_col[i] * 16u;
         }
       }
+      ++s;
+      return real;
+    };
+    for (;;) {
+      const bool real = issue_next();
       MM_WAIT_VMCNT(12);                                    // the chunk issued three iterations ago has landed
       lds_barrier();                                        // "landed"
       lds_barrier();                                        // "free": stage (s + 1) & 3 was consumed
-      ++s;
       if (!real && ++drain == 3) break;                     // the computers lag three iterations
     }
     MM_WAIT_VMCNT(0);
@@ -323,6 +329,39 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     for (int h = 0; h < kHalves; ++h) bbuf[t][h] = i32x4{0, 0, 0, 0};
   f32x4 acc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
 
+  // Scale (8-bit weights), activate and store this lane's 2 x 4 sums of the item that ended.
+  auto store_outputs = [&](float (&val)[2][4]) {
+    if (WB == 1) {
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) val[rt][v] *= f_sc[rt][v];
+    }
+    const int r = f_r0 + tw * 16 + c16;
+    if (r < f_m) {
+      if (MODE == kGateUp) {
+        const int i = f_n0 + 4 * q;
+        if (i < f_N) {
+          float hv[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const float gte = val[0][v];
+            hv[v] = gte / (1.f + __expf(-gte)) * val[1][v];
+          }
+          bf16x4 o = {(__bf16)hv[0], (__bf16)hv[1], (__bf16)hv[2], (__bf16)hv[3]};
+          *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(f_out) + (size_t)r * f_N + i) = o;
+        }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          const int col = f_n0 + rt * 16 + 4 * q;
+          if (col < f_N)
+            *reinterpret_cast<f32x4*>(static_cast<float*>(f_out) + (size_t)r * a.H + col) =
+                f32x4{val[rt][0], val[rt][1], val[rt][2], val[rt][3]};
+        }
+      }
+    }
+  };
   auto epilogue = [&]() {
     // computers 0 and 1 finish token tiles 0 and 1: add the two k parts, activate, store
     if (kp == 0 && tw < f_ntn) {
@@ -331,73 +370,64 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int v = 0; v < 4; ++v) val[rt][v] = s_red[tw][rt][v][lane] + s_red[tw + 2][rt][v][lane];
-      if (WB == 1) {
+      store_outputs(val);
+    }
+  };
+
+  // Fragments of the chunk in stage `stage`, MFMAs against the token rows in bbuf.
+  auto consume = [&](int stage) {
+    const unsigned st = (unsigned)(stage * kStageBytes);
+    bf16x8 f0[kReads], f1[kReads];                           // row tile 0 / 1, one 16-byte column each
+    static_assert(kReads == 4, "the fragment reads below are written for four columns per wave and row tile");
+    asm volatile(
+        "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:8192\n"
+        "ds_read_b128 %2, %9\n ds_read_b128 %3, %9 offset:8192\n"
+        "ds_read_b128 %4, %10\n ds_read_b128 %5, %10 offset:8192\n"
+        "ds_read_b128 %6, %11\n ds_read_b128 %7, %11 offset:8192\n"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(f0[0]), "=&v"(f1[0]), "=&v"(f0[1]), "=&v"(f1[1]), "=&v"(f0[2]), "=&v"(f1[2]), "=&v"(f0[3]), "=&v"(f1[3])
+        : "v"(rd_off[0] + st), "v"(rd_off[1] + st), "v"(rd_off[2] + st), "v"(rd_off[3] + st)
+        : "memory");
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+    for (int t = 0; t < kReads; ++t) {
+      if (WB == 2) {
+        const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][0]);
+        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
+      } else {
+        const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
 #pragma unroll
-          for (int v = 0; v < 4; ++v) val[rt][v] *= f_sc[rt][v];
-      }
-      const int r = f_r0 + tw * 16 + c16;
-      if (r < f_m) {
-        if (MODE == kGateUp) {
-          const int i = f_n0 + 4 * q;
-          if (i < f_N) {
-            float hv[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-              const float gte = val[0][v];
-              hv[v] = gte / (1.f + __expf(-gte)) * val[1][v];
-            }
-            bf16x4 o = {(__bf16)hv[0], (__bf16)hv[1], (__bf16)hv[2], (__bf16)hv[3]};
-            *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(f_out) + (size_t)r * f_N + i) = o;
-          }
-        } else {
-#pragma unroll
-          for (int rt = 0; rt < 2; ++rt) {
-            const int col = f_n0 + rt * 16 + 4 * q;
-            if (col < f_N)
-              *reinterpret_cast<f32x4*>(static_cast<float*>(f_out) + (size_t)r * a.H + col) =
-                  f32x4{val[rt][0], val[rt][1], val[rt][2], val[rt][3]};
-          }
+        for (int h = 0; h < kHalves; ++h) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w0[2 * h], w0[2 * h + 1]), bv, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w1[2 * h], w1[2 * h + 1]), bv, acc[1], 0, 0, 0);
         }
       }
     }
+  };
+  // Token rows of chunk (cur, k) into bbuf.  Nothing of this wave is in flight any more (the
+  // previous token rows were consumed or belong to a tile this wave skips); saying so keeps the
+  // compiler from guarding every one of the loads against a load of the previous iteration into
+  // the same registers.
+  auto load_token_rows = [&]() {
+    MM_WAIT_VMCNT(0);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(cur.b, cur.bbytes);
+#pragma unroll
+    for (int t = 0; t < kReads; ++t)
+#pragma unroll
+      for (int h = 0; h < kHalves; ++h) {
+        // the k behind 16-byte column (kp + 2t) * 4 + q of the weight rows (second half: h = 1)
+        const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * (16 / WB) + h * 8;
+        const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
+        bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
+      }
   };
 
   // One iteration.
   auto step = [&](int s) -> bool {
     lds_barrier();                                          // "landed": the chunk issued three iterations ago
     if (s >= 3 && cur.valid) {
-      if (tw < cur.ntn) {
-        const unsigned st = (unsigned)(((s + 1) & (kStages - 1)) * kStageBytes);
-        bf16x8 f0[kReads], f1[kReads];                       // row tile 0 / 1, one 16-byte column each
-        static_assert(kReads == 4, "the fragment reads below are written for four columns per wave and row tile");
-        asm volatile(
-            "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:8192\n"
-            "ds_read_b128 %2, %9\n ds_read_b128 %3, %9 offset:8192\n"
-            "ds_read_b128 %4, %10\n ds_read_b128 %5, %10 offset:8192\n"
-            "ds_read_b128 %6, %11\n ds_read_b128 %7, %11 offset:8192\n"
-            "s_waitcnt lgkmcnt(0)"
-            : "=&v"(f0[0]), "=&v"(f1[0]), "=&v"(f0[1]), "=&v"(f1[1]), "=&v"(f0[2]), "=&v"(f1[2]), "=&v"(f0[3]), "=&v"(f1[3])
-            : "v"(rd_off[0] + st), "v"(rd_off[1] + st), "v"(rd_off[2] + st), "v"(rd_off[3] + st)
-            : "memory");
-#pragma unroll
-        for (int t = 0; t < kReads; ++t) {
-          if (WB == 2) {
-            const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][0]);
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
-          } else {
-            const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
-#pragma unroll
-            for (int h = 0; h < kHalves; ++h) {
-              const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
-              acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w0[2 * h], w0[2 * h + 1]), bv, acc[0], 0, 0, 0);
-              acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w1[2 * h], w1[2 * h + 1]), bv, acc[1], 0, 0, 0);
-            }
-          }
-        }
-      }
+      if (tw < cur.ntn) consume((s + 1) & (kStages - 1));
       if (++k == cur.nch) {         // item done: hand the partial sums over, move on
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
@@ -412,24 +442,10 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
       }
     }
     // Token rows of the chunk consumed in the next iteration: issued here, behind the MFMAs that
-    // read the previous ones, they arrive while this wave waits at the two barriers.
-    if (s >= 2 && tw < cur.ntn) {   // that chunk is (cur, k): the one after the chunk just consumed; a wave
-                                    // whose token tile is empty loads nothing (its MFMAs are skipped as well)
-      // Nothing of this wave is in flight any more (the previous token rows were consumed or
-      // belong to a tile this wave skips).  Saying so keeps the compiler from guarding every one
-      // of the loads below against a load of the previous iteration into the same registers.
-      MM_WAIT_VMCNT(0);
-      const __amdgpu_buffer_rsrc_t rb = make_rsrc(cur.b, cur.bbytes);
-#pragma unroll
-      for (int t = 0; t < kReads; ++t)
-#pragma unroll
-        for (int h = 0; h < kHalves; ++h) {
-          // the k behind 16-byte column (kp + 2t) * 4 + q of the weight rows (second half: h = 1)
-          const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * (16 / WB) + h * 8;
-          const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
-          bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
-        }
-    }
+    // read the previous ones, they arrive while this wave waits at the two barriers.  That chunk
+    // is (cur, k): the one after the chunk just consumed; a wave whose token tile is empty loads
+    // nothing (its MFMAs are skipped as well).
+    if (s >= 2 && tw < cur.ntn) load_token_rows();
     lds_barrier();                                          // "free"; partial sums of an item that ended are complete
     // what follows runs while the loaders wait for their next chunk
     if (pending) { pending = 0; epilogue(); }
