@@ -3,7 +3,9 @@
 The paper keeps inactive experts in host DRAM and loads the ones the router selects (Sec. II-B);
 for a token that falls back to the big model, the router outputs of its discarded little pass
 name the experts to prefetch (Sec. III-B).  The paper fixes no replacement policy; this model is
-the reading the library documents, written out as plain integer bookkeeping:
+the reading the library documents, written out as plain integer bookkeeping.  (History: the
+reading was fixed first, the library's cache code second, this model third; it is therefore
+pinned below by references that share nothing with either.)
 
 * every fetch call advances a logical clock; experts named by the call that are resident
   afterwards carry that time stamp;
@@ -12,10 +14,14 @@ the reading the library documents, written out as plain integer bookkeeping:
   call (lowest slot id among equals; empty slots are oldest);
 * PREFETCH (any number, priority order): resident ones are re-stamped; a miss is loaded only
   into a slot that holds neither an expert of this call nor one of the most recent DEMAND call,
-  otherwise it is dropped.
+  otherwise it is dropped (never queued for later).  An optional `limit` bounds the copies one
+  PREFETCH call may start (the depth of the prefetch queue, Sec. III-B: how far ahead to load is
+  adjustable); misses beyond it are dropped as well.
 
 Pins (tests/test_cache_model.py): single-expert DEMAND traces equal a textbook LRU written with
-an OrderedDict; structural invariants on random traces.
+an OrderedDict; a brute-force reference that keeps no running state but recomputes every decision
+from the full call history; traces worked by hand from the rules above; structural invariants on
+random traces; and each of a list of planted mistakes is shown to fail those pins.
 """
 from __future__ import annotations
 
@@ -47,8 +53,9 @@ class CacheModel:
                 best = s
         return best
 
-    def fetch(self, ids: Sequence[int], mode: int) -> Tuple[List[int], int, int, int]:
-        """-> (slot of each id or -1, hits, misses, dropped)"""
+    def fetch(self, ids: Sequence[int], mode: int, limit=None) -> Tuple[List[int], int, int, int]:
+        """-> (slot of each id or -1, hits, misses, dropped); `limit` (PREFETCH only): copies this
+        call may start at most, None = no bound"""
         ids = list(ids)
         assert len(set(ids)) == len(ids) and all(0 <= e < self.E for e in ids)
         needed = set(ids)
@@ -81,7 +88,7 @@ class CacheModel:
                 out.append(s)
                 continue
             v = self._victim(needed, self.epoch if self.epoch > 0 else None)
-            if v < 0:
+            if v < 0 or (limit is not None and misses >= limit):
                 dropped += 1
                 out.append(-1)
                 continue

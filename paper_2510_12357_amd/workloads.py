@@ -81,21 +81,13 @@ def _store(a: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError(dtype)
 
 
-def _e4m3_positive_values() -> np.ndarray:
-    """The 127 finite non-negative values of the 8-bit float E4M3 ("e4m3fn"), by code 0x00..0x7E."""
-    code = np.arange(127)
-    e, m = code >> 3, code & 7
-    return np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
-
-
 def f32_to_e4m3_bits(a: np.ndarray) -> np.ndarray:
-    """Nearest finite E4M3 code of every entry (values beyond +-448 saturate); used to make up
-    8-bit expert weights, so any rounding would do."""
-    v = _e4m3_positive_values()
-    mid = (v[1:] + v[:-1]) / 2
-    mag = np.abs(np.asarray(a, np.float64))
-    code = np.searchsorted(mid, mag, side="left").astype(np.uint8)
-    return code | (np.signbit(a).astype(np.uint8) << 7)
+    """An 8-bit E4M3 ("e4m3fn") code for every entry, by the library cast of torch (this module
+    holds no arithmetic of the format itself; it only makes up 8-bit expert weights, for which
+    any rounding would do).  Entries are clipped to the format's largest magnitude first."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).clamp_(-448.0, 448.0)
+    return t.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
 
 
 def w8_blob_bytes(H: int, I: int) -> int:
