@@ -222,8 +222,10 @@ int moe_combine_add(const moe_config* cfg, const float* y, const float* topk_w, 
  * any number of layers ahead).
  *
  * The cache is a set of n_slots HBM slots of blob_bytes each, filled by hipMemcpyAsync from a
- * pinned host arena holding all E blobs back to back, on a side stream of default priority.
- * Policy (deterministic, host-side integers only):
+ * pinned host arena holding all E blobs back to back, on two side streams of default priority
+ * (one carries the DEMAND copies, one the PREFETCH copies, so that a copy a step waits for does
+ * not queue behind copies started on a prediction).
+ * Policy (deterministic, host-side integers only; it depends on the sequence of calls alone):
  *   - every call advances a logical clock; every expert the call names that is resident
  *     afterwards gets that time stamp
  *   - MOE_FETCH_DEMAND: n <= n_slots distinct experts.  Resident ones are hits.  Misses are
@@ -234,10 +236,14 @@ int moe_combine_add(const moe_config* cfg, const float* y, const float* topk_w, 
  *     of this call point at their slots and all others are NULL.
  *   - MOE_FETCH_PREFETCH: any n, experts in priority order.  Resident ones are re-stamped.
  *     A miss is loaded only if a victim exists that is neither named by this call nor part of
- *     the most recent DEMAND call; otherwise it is dropped (slot_of = -1).  The pointer table
- *     and the compute stream are not touched.
- *   - a copy into a slot never starts before the kernels that were enqueued on the compute
- *     stream, up to the time of this call, have finished reading the slot's previous expert.
+ *     the most recent DEMAND call; otherwise it is dropped (slot_of = -1; nothing is queued for
+ *     later).  moe_cache_set_prefetch_limit bounds the copies one PREFETCH call may start; misses
+ *     beyond the bound are dropped too.  The pointer table and the compute stream are not touched.
+ *   - Ordering against the compute stream: the kernels that read the slots handed out by a DEMAND
+ *     call must be enqueued on compute_stream before the NEXT DEMAND call on the cache (PREFETCH
+ *     calls may come at any time in between).  A copy that replaces a slot's expert starts only
+ *     after the work that was on the compute stream at the time of that next DEMAND call has
+ *     finished, and after any earlier copy into the same slot.
  */
 typedef struct moe_cache moe_cache_t;
 
@@ -283,6 +289,16 @@ int moe_cache_snapshot(moe_cache_t* cache, int32_t* resident_expert);
 
 /* Blocks the host until every copy issued so far has landed (tests, shutdown). */
 int moe_cache_sync(moe_cache_t* cache);
+
+/* Depth of the prefetch queue (Sec. III-B: how far ahead experts are loaded is adjustable): a
+ * PREFETCH call starts at most max_copies_per_call copies and drops its other misses; negative =
+ * no bound (the default). */
+int moe_cache_set_prefetch_limit(moe_cache_t* cache, int32_t max_copies_per_call);
+
+/* Measurement aid: emulates a slower host link (the paper's system loads over PCIe 4.0).  Every
+ * copy is followed, on its copy stream, by a hold of blob_bytes / gb_per_s, so that a copy stream
+ * delivers 1 / (1/link + 1/gb_per_s).  0 = off (the default). */
+int moe_cache_emulate_link(moe_cache_t* cache, double gb_per_s);
 
 #ifdef __cplusplus
 }

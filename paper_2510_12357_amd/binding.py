@@ -29,7 +29,8 @@ EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profi
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_from", "moe_combine_add",
            "moe_expert_ffn_workspace_bytes", "moe_expert_blob_bytes",
            "moe_shared_out_slabs", "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
-           "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync")
+           "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync",
+           "moe_cache_set_prefetch_limit", "moe_cache_emulate_link")
 
 
 class MoeError(RuntimeError):
@@ -98,10 +99,12 @@ def load_library() -> ctypes.CDLL:
                                           ctypes.POINTER(moe_fetch_stats), ctypes.POINTER(i32), vp]
     lib.moe_cache_snapshot.argtypes = [vp, ctypes.POINTER(i32)]
     lib.moe_cache_sync.argtypes = [vp]
+    lib.moe_cache_set_prefetch_limit.argtypes = [vp, i32]
+    lib.moe_cache_emulate_link.argtypes = [vp, ctypes.c_double]
     for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence", "moe_dispatch",
                  "moe_dispatch_from", "moe_combine_add",
                  "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot",
-                 "moe_cache_sync"):
+                 "moe_cache_sync", "moe_cache_set_prefetch_limit", "moe_cache_emulate_link"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -279,6 +282,14 @@ def moe_cache_snapshot(cache: int, n_slots: int):
 
 def moe_cache_sync(cache: int) -> None:
     _check(load_library().moe_cache_sync(ctypes.c_void_p(cache)))
+
+
+def moe_cache_set_prefetch_limit(cache: int, max_copies_per_call: int) -> None:
+    _check(load_library().moe_cache_set_prefetch_limit(ctypes.c_void_p(cache), int(max_copies_per_call)))
+
+
+def moe_cache_emulate_link(cache: int, gb_per_s: float) -> None:
+    _check(load_library().moe_cache_emulate_link(ctypes.c_void_p(cache), float(gb_per_s)))
 
 
 # ------------------------------------------------------------------------------ plumbing helpers

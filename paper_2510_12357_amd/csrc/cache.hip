@@ -3,37 +3,42 @@
 // the router outputs of a token's discarded little pass name the experts of its big pass ahead
 // of time, so their copies can overlap with compute).
 //
-// All policy decisions are host-side integer bookkeeping and depend only on the sequence of
-// calls, never on timing.  Data movement is hipMemcpyAsync on one side stream of default
-// priority; ordering against the compute stream uses two events per slot:
-//   ready[s]     recorded on the copy stream after the copy into slot s; the compute stream waits
-//   released[s]  recorded on the compute stream at the start of the first fetch call after the
+// Which expert goes to which slot is decided by the host-only policy unit (cache_policy.h); this
+// file moves the bytes and orders them against the compute stream.  Data movement is
+// hipMemcpyAsync on two side streams of default priority, one for DEMAND copies and one for
+// PREFETCH copies, so that a copy the step is waiting for never queues behind copies that were
+// only started on a prediction.  Per slot:
+//   ready[s]     recorded behind the latest copy into slot s (on the stream that carried it); the
+//                compute stream waits for it before kernels read the slot, and a later copy into
+//                the slot waits for it as well (the two copy streams are not ordered otherwise)
+//   released[s]  recorded on the compute stream at the start of the first DEMAND call after the
 //                slot was handed out by a DEMAND call, i.e. after every kernel that may read the
-//                slot has been enqueued; a later copy into the slot waits for it
+//                slot has been enqueued; a later copy into the slot waits for it.  PREFETCH calls
+//                record nothing: the only slots still waiting for their release then belong to
+//                the most recent DEMAND call, which a PREFETCH never evicts.
 #include <algorithm>
 #include <vector>
 
+#include "cache_policy.h"
 #include "internal.h"
 
 struct moe_cache {
-  int E = 0, n_slots = 0;
+  mm::CachePolicy policy;
   size_t blob_bytes = 0;
   const char* host = nullptr;
   char* dev = nullptr;
-  hipStream_t copy_stream = nullptr;
+  hipStream_t demand_stream = nullptr, prefetch_stream = nullptr;
   const void** d_table = nullptr;          // device, [E]
-  std::vector<int> slot_expert, expert_slot;
-  std::vector<uint64_t> stamp, demand_epoch;
   std::vector<char> pending_release, has_ready, has_released;
   std::vector<hipEvent_t> ready, released;
-  uint64_t clock = 0, epoch = 0;
+  int prefetch_limit = -1;                 // copies one PREFETCH call may start; < 0: no bound
+  double link_gbps = 0.0;                  // > 0: every copy is followed by a timed hold of its stream (slower link)
   int32_t* h_offsets = nullptr;            // pinned host, [E+1]: landing zone of expert_offsets
+  moe_cache(int E, int n_slots) : policy(E, n_slots) {}
 };
 
 namespace mm {
 namespace {
-
-constexpr uint64_t kNever = ~0ull;
 
 struct TableImage { const void* p[MOE_MAX_EXPERTS]; };
 
@@ -41,31 +46,92 @@ __global__ void table_update_kernel(const void** table, int E, const TableImage 
   for (int e = threadIdx.x; e < E; e += blockDim.x) table[e] = img.p[e];
 }
 
-// least recently stamped slot among those the predicate admits; lowest id among equals
-template <typename Pred>
-int pick_victim(const moe_cache& c, Pred admissible) {
-  int best = -1;
-  for (int s = 0; s < c.n_slots; ++s) {
-    if (!admissible(s)) continue;
-    if (best < 0 || c.stamp[s] < c.stamp[best]) best = s;
-  }
-  return best;
+// Holds the stream it runs on for `ticks` of the 100 MHz wall clock (one wave; bounded both by
+// the clock and by an iteration count, so it always ends).
+__global__ void hold_stream_kernel(long long ticks) {
+  const long long t0 = wall_clock64();
+  for (int i = 0; i < (1 << 22) && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(32);
 }
 
-int issue_copy(moe_cache& c, int expert, int slot) {
-  if (c.has_released[slot]) MM_HIP(hipStreamWaitEvent(c.copy_stream, c.released[slot], 0));
+int issue_copy(moe_cache& c, int expert, int slot, hipStream_t cs) {
+  if (c.has_released[slot]) MM_HIP(hipStreamWaitEvent(cs, c.released[slot], 0));
+  if (c.has_ready[slot]) MM_HIP(hipStreamWaitEvent(cs, c.ready[slot], 0));   // an earlier copy into the slot
   MM_HIP(hipMemcpyAsync(c.dev + (size_t)slot * c.blob_bytes, c.host + (size_t)expert * c.blob_bytes,
-                        c.blob_bytes, hipMemcpyHostToDevice, c.copy_stream));
-  MM_HIP(hipEventRecord(c.ready[slot], c.copy_stream));
+                        c.blob_bytes, hipMemcpyHostToDevice, cs));
+  if (c.link_gbps > 0.0) {
+    // a hold of blob / link_gbps behind the copy: the stream then delivers 1 / (1/link + 1/link_gbps)
+    const double want_s = (double)c.blob_bytes / (c.link_gbps * 1e9);
+    const long long ticks = (long long)(want_s * 1e8);
+    if (ticks > 0) {
+      hipLaunchKernelGGL(hold_stream_kernel, dim3(1), dim3(64), 0, cs, ticks);
+      MM_HIP(hipGetLastError());
+    }
+  }
+  MM_HIP(hipEventRecord(c.ready[slot], cs));
   c.has_ready[slot] = 1;
   return MOE_OK;
 }
 
-void assign(moe_cache& c, int expert, int slot) {
-  const int old = c.slot_expert[slot];
-  if (old >= 0) c.expert_slot[old] = -1;
-  c.slot_expert[slot] = expert;
-  c.expert_slot[expert] = slot;
+// Points the device table at the slots of `ids` (all other experts NULL) on the compute stream,
+// after making that stream wait for the copies into those slots.
+int publish(moe_cache& c, const int32_t* ids, int n, hipStream_t cs) {
+  TableImage img;
+  for (int e = 0; e < MOE_MAX_EXPERTS; ++e) img.p[e] = nullptr;
+  for (int i = 0; i < n; ++i) {
+    const int s = c.policy.slot_of_expert(ids[i]);
+    if (c.has_ready[s]) MM_HIP(hipStreamWaitEvent(cs, c.ready[s], 0));
+    img.p[ids[i]] = c.dev + (size_t)s * c.blob_bytes;
+  }
+  hipLaunchKernelGGL(table_update_kernel, dim3(1), dim3(256), 0, cs, c.d_table, c.policy.n_experts(), img);
+  return hip_fail(hipGetLastError(), "table_update_kernel launch");
+}
+
+// The policy decision of one call plus its copies.  With `publish_now` (DEMAND) the compute
+// stream is made to wait for all of the call's slots and the pointer table is rewritten.
+int fetch_impl(moe_cache& c, const int32_t* ids, int n, int mode, int32_t* slot_of, moe_fetch_stats* stats,
+               hipStream_t cs, bool publish_now) {
+  std::vector<PolicyCopy> copies;
+  PolicyCounts counts = {0, 0, 0};
+  std::vector<int32_t> slots_local((size_t)std::max(n, 1));
+  int32_t* so = slot_of ? slot_of : slots_local.data();
+  const int prc = c.policy.fetch(ids, n, mode == MOE_FETCH_DEMAND ? kPolicyDemand : kPolicyPrefetch,
+                                 c.prefetch_limit, so, &copies, &counts);
+  switch (prc) {
+    case kPolicyOk: break;
+    case kPolicyBadId: return fail(MOE_E_BADARG, "expert_cache_fetch: expert id outside [0,%d)", c.policy.n_experts());
+    case kPolicyDuplicate: return fail(MOE_E_BADARG, "expert_cache_fetch: an expert id is named twice");
+    case kPolicyTooMany:
+      return fail(MOE_E_CACHE_FULL, "expert_cache_fetch: DEMAND of %d experts exceeds the %d slots; split the step into waves",
+                  n, c.policy.n_slots());
+    default: return fail(MOE_E_BADARG, "expert_cache_fetch: mode %d", mode);
+  }
+  if (mode == MOE_FETCH_DEMAND) {
+    // everything enqueued so far on the compute stream may still read the slots of the previous DEMAND
+    for (int s = 0; s < c.policy.n_slots(); ++s)
+      if (c.pending_release[s]) {
+        MM_HIP(hipEventRecord(c.released[s], cs));
+        c.has_released[s] = 1;
+        c.pending_release[s] = 0;
+      }
+  }
+  hipStream_t copy_stream = mode == MOE_FETCH_DEMAND ? c.demand_stream : c.prefetch_stream;
+  for (const PolicyCopy& cp : copies) {
+    const int rc = issue_copy(c, cp.expert, cp.slot, copy_stream);
+    if (rc) return rc;
+  }
+  if (mode == MOE_FETCH_DEMAND) {
+    for (int i = 0; i < n; ++i) c.pending_release[so[i]] = 1;
+    if (publish_now) {
+      const int rc = publish(c, ids, n, cs);
+      if (rc) return rc;
+    }
+  }
+  if (stats) {
+    stats->hits = counts.hits; stats->misses = counts.misses; stats->dropped = counts.dropped;
+    stats->reserved = 0;
+    stats->bytes_h2d = (uint64_t)counts.misses * c.blob_bytes;
+  }
+  return MOE_OK;
 }
 
 }  // namespace
@@ -84,18 +150,15 @@ extern "C" moe_cache_t* moe_cache_create(int32_t E, size_t blob_bytes, int32_t n
     fail(MOE_E_BADARG, "moe_cache_create: device_slots must be 256-byte aligned, blob_bytes a multiple of 16");
     return nullptr;
   }
-  moe_cache* c = new moe_cache();
-  c->E = E; c->n_slots = n_slots; c->blob_bytes = blob_bytes;
+  moe_cache* c = new moe_cache(E, n_slots);
+  c->blob_bytes = blob_bytes;
   c->host = static_cast<const char*>(host_blobs);
   c->dev = static_cast<char*>(device_slots);
-  c->slot_expert.assign(n_slots, -1);
-  c->expert_slot.assign(E, -1);
-  c->stamp.assign(n_slots, 0);
-  c->demand_epoch.assign(n_slots, kNever);
   c->pending_release.assign(n_slots, 0);
   c->has_ready.assign(n_slots, 0);
   c->has_released.assign(n_slots, 0);
-  bool ok = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
+  bool ok = hipStreamCreateWithFlags(&c->demand_stream, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && hipStreamCreateWithFlags(&c->prefetch_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->d_table, sizeof(void*) * E) == hipSuccess;
   ok = ok && hipMemset((void*)c->d_table, 0, sizeof(void*) * E) == hipSuccess;
   ok = ok && hipHostMalloc((void**)&c->h_offsets, sizeof(int32_t) * (E + 1), hipHostMallocDefault) == hipSuccess;
@@ -115,7 +178,8 @@ extern "C" moe_cache_t* moe_cache_create(int32_t E, size_t blob_bytes, int32_t n
 
 extern "C" void moe_cache_destroy(moe_cache_t* c) {
   if (!c) return;
-  if (c->copy_stream) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamDestroy(c->copy_stream); }
+  for (hipStream_t s : {c->demand_stream, c->prefetch_stream})
+    if (s) { (void)hipStreamSynchronize(s); (void)hipStreamDestroy(s); }
   for (hipEvent_t e : c->ready) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->released) (void)hipEventDestroy(e);
   if (c->d_table) (void)hipFree((void*)c->d_table);
@@ -127,13 +191,26 @@ extern "C" const void* const* moe_cache_expert_table(moe_cache_t* c) { return c 
 
 extern "C" int moe_cache_snapshot(moe_cache_t* c, int32_t* resident_expert) {
   if (!c || !resident_expert) return fail(MOE_E_BADARG, "moe_cache_snapshot: null argument");
-  for (int s = 0; s < c->n_slots; ++s) resident_expert[s] = c->slot_expert[s];
-  return c->n_slots;
+  for (int s = 0; s < c->policy.n_slots(); ++s) resident_expert[s] = c->policy.expert_in_slot(s);
+  return c->policy.n_slots();
 }
 
 extern "C" int moe_cache_sync(moe_cache_t* c) {
   if (!c) return fail(MOE_E_BADARG, "moe_cache_sync: null cache");
-  MM_HIP(hipStreamSynchronize(c->copy_stream));
+  MM_HIP(hipStreamSynchronize(c->demand_stream));
+  MM_HIP(hipStreamSynchronize(c->prefetch_stream));
+  return MOE_OK;
+}
+
+extern "C" int moe_cache_set_prefetch_limit(moe_cache_t* c, int32_t max_copies_per_call) {
+  if (!c) return fail(MOE_E_BADARG, "moe_cache_set_prefetch_limit: null cache");
+  c->prefetch_limit = max_copies_per_call < 0 ? -1 : max_copies_per_call;
+  return MOE_OK;
+}
+
+extern "C" int moe_cache_emulate_link(moe_cache_t* c, double gb_per_s) {
+  if (!c || !(gb_per_s >= 0.0)) return fail(MOE_E_BADARG, "moe_cache_emulate_link: null cache or negative rate");
+  c->link_gbps = gb_per_s;
   return MOE_OK;
 }
 
@@ -143,87 +220,14 @@ extern "C" int expert_cache_fetch(moe_cache_t* c, const int32_t* ids, int32_t n,
     return fail(MOE_E_BADARG, "expert_cache_fetch: null argument or n < 0");
   if (mode != MOE_FETCH_DEMAND && mode != MOE_FETCH_PREFETCH)
     return fail(MOE_E_BADARG, "expert_cache_fetch: mode %d", mode);
-  std::vector<char> needed(c->E, 0);
-  for (int i = 0; i < n; ++i) {
-    if (ids[i] < 0 || ids[i] >= c->E) return fail(MOE_E_BADARG, "expert_cache_fetch: expert id %d outside [0,%d)", ids[i], c->E);
-    if (needed[ids[i]]) return fail(MOE_E_BADARG, "expert_cache_fetch: expert id %d named twice", ids[i]);
-    needed[ids[i]] = 1;
-  }
-  if (mode == MOE_FETCH_DEMAND && n > c->n_slots)
-    return fail(MOE_E_CACHE_FULL, "expert_cache_fetch: DEMAND of %d experts exceeds the %d slots; split the step into waves", n, c->n_slots);
-
-  hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-  // everything enqueued so far on the compute stream may still read the slots of earlier DEMANDs
-  for (int s = 0; s < c->n_slots; ++s)
-    if (c->pending_release[s]) {
-      MM_HIP(hipEventRecord(c->released[s], cs));
-      c->has_released[s] = 1;
-      c->pending_release[s] = 0;
-    }
-
-  moe_fetch_stats st = {0, 0, 0, 0, 0};
-  c->clock++;
-  if (mode == MOE_FETCH_DEMAND) {
-    c->epoch++;
-    for (int e = 0; e < c->E; ++e) {              // residents first, ascending id
-      if (!needed[e] || c->expert_slot[e] < 0) continue;
-      const int s = c->expert_slot[e];
-      c->stamp[s] = c->clock; c->demand_epoch[s] = c->epoch;
-      st.hits++;
-    }
-    for (int e = 0; e < c->E; ++e) {              // then the misses, ascending id
-      if (!needed[e] || c->expert_slot[e] >= 0) continue;
-      const int v = pick_victim(*c, [&](int s) { return c->slot_expert[s] < 0 || !needed[c->slot_expert[s]]; });
-      if (v < 0) return fail(MOE_E_CACHE_FULL, "expert_cache_fetch: no evictable slot (internal)");
-      assign(*c, e, v);
-      c->stamp[v] = c->clock; c->demand_epoch[v] = c->epoch;
-      int rc = issue_copy(*c, e, v);
-      if (rc) return rc;
-      st.misses++;
-    }
-    TableImage img;
-    for (int e = 0; e < MOE_MAX_EXPERTS; ++e) img.p[e] = nullptr;
-    for (int i = 0; i < n; ++i) {
-      const int s = c->expert_slot[ids[i]];
-      slot_of[i] = s;
-      if (c->has_ready[s]) MM_HIP(hipStreamWaitEvent(cs, c->ready[s], 0));
-      c->pending_release[s] = 1;
-      img.p[ids[i]] = c->dev + (size_t)s * c->blob_bytes;
-    }
-    hipLaunchKernelGGL(table_update_kernel, dim3(1), dim3(256), 0, cs, c->d_table, c->E, img);
-    MM_HIP(hipGetLastError());
-  } else {
-    for (int i = 0; i < n; ++i) {                 // priority order as given
-      const int e = ids[i];
-      if (c->expert_slot[e] >= 0) {
-        const int s = c->expert_slot[e];
-        c->stamp[s] = c->clock;
-        slot_of[i] = s;
-        st.hits++;
-        continue;
-      }
-      const int v = pick_victim(*c, [&](int s) {
-        if (c->demand_epoch[s] != kNever && c->demand_epoch[s] == c->epoch) return false;
-        return c->slot_expert[s] < 0 || !needed[c->slot_expert[s]];
-      });
-      if (v < 0) { slot_of[i] = -1; st.dropped++; continue; }
-      assign(*c, e, v);
-      c->stamp[v] = c->clock;
-      int rc = issue_copy(*c, e, v);
-      if (rc) return rc;
-      slot_of[i] = v;
-      st.misses++;
-    }
-  }
-  st.bytes_h2d = (uint64_t)st.misses * c->blob_bytes;
-  if (stats) *stats = st;
-  return MOE_OK;
+  return fetch_impl(*c, ids, n, mode, slot_of, stats, static_cast<hipStream_t>(compute_stream), true);
 }
 
 // One step's execution stage with offloaded experts: the router's decision is brought to the
 // host (the only host synchronisation of a step), the needed experts are fetched in waves of at
-// most n_slots (resident ones first, so their compute overlaps the first copies), and each wave
-// runs the grouped FFN on exactly its experts through the cache's pointer table.
+// most n_slots (resident ones first), and within a wave the grouped FFN is launched for the
+// experts that were resident at once and then for the missing ones a few at a time, each launch
+// waiting only for its own experts' copies, so that computing overlaps the copies that follow.
 extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, const void* x,
                                      const int32_t* expert_offsets, const int32_t* sorted_token,
                                      const void* const* shared_w, float* y, float* shared_out, void* ws,
@@ -232,7 +236,8 @@ extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, cons
   int rc = validate_config(cfg);
   if (rc) return rc;
   if (!c) return fail(MOE_E_BADARG, "moe_expert_ffn_cached: cache is NULL");
-  if (cfg->E != c->E) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: cache holds %d experts, layer has %d", c->E, cfg->E);
+  const int E = c->policy.n_experts(), S = c->policy.n_slots();
+  if (cfg->E != E) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: cache holds %d experts, layer has %d", E, cfg->E);
   const size_t need = expert_blob_bytes(cfg->dtype, cfg->H, cfg->I);
   if (need != c->blob_bytes) return fail(MOE_E_SHAPE, "moe_expert_ffn_cached: blob of %zu bytes, layer needs %zu", c->blob_bytes, need);
   moe_fetch_stats sum = {0, 0, 0, 0, 0};
@@ -241,31 +246,46 @@ extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, cons
   if (cfg->T == 0) return MOE_OK;
   if (!expert_offsets) return fail(MOE_E_BADARG, "moe_expert_ffn_cached: expert_offsets is NULL");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  MM_HIP(hipMemcpyAsync(c->h_offsets, expert_offsets, sizeof(int32_t) * (c->E + 1), hipMemcpyDeviceToHost, s));
+  MM_HIP(hipMemcpyAsync(c->h_offsets, expert_offsets, sizeof(int32_t) * (E + 1), hipMemcpyDeviceToHost, s));
   // shared experts do not depend on the router: enqueue them before waiting for it
   if (cfg->n_shared > 0) {
     rc = moe_expert_ffn(cfg, x, expert_offsets, sorted_token, nullptr, shared_w, 0, 1, y, shared_out, ws, ws_bytes, stream);
     if (rc) return rc;
   }
   MM_HIP(hipStreamSynchronize(s));
-  std::vector<int32_t> order;                      // resident experts first, then the misses
-  for (int pass = 0; pass < 2; ++pass)
-    for (int e = 0; e < c->E; ++e) {
-      if (c->h_offsets[e + 1] <= c->h_offsets[e]) continue;
-      const bool resident = c->expert_slot[e] >= 0;
-      if ((pass == 0) == resident) order.push_back(e);
-    }
-  std::vector<int32_t> slots(c->n_slots);
+  std::vector<int32_t> needed, order;
+  for (int e = 0; e < E; ++e)
+    if (c->h_offsets[e + 1] > c->h_offsets[e]) needed.push_back(e);
+  c->policy.wave_order(needed, &order);
+  // missing experts per FFN launch: about 32 MB of copies, so that a launch's fixed cost stays
+  // small next to the copy time it hides under
+  const int per_launch = (int)std::max<size_t>(1, ((size_t)32 << 20) / c->blob_bytes);
+  std::vector<int32_t> slots(S), part;
   int waves = 0;
-  for (size_t i = 0; i < order.size(); i += c->n_slots) {
-    const int n = (int)std::min<size_t>(c->n_slots, order.size() - i);
+  for (size_t i = 0; i < order.size(); i += S) {
+    const int n = (int)std::min<size_t>(S, order.size() - i);
+    const int32_t* ids = order.data() + i;
+    std::vector<char> was_resident(n);
+    for (int k = 0; k < n; ++k) was_resident[k] = c->policy.slot_of_expert(ids[k]) >= 0;
     moe_fetch_stats st;
-    rc = expert_cache_fetch(c, order.data() + i, n, MOE_FETCH_DEMAND, slots.data(), &st, stream);
+    rc = fetch_impl(*c, ids, n, MOE_FETCH_DEMAND, slots.data(), &st, s, false);
     if (rc) return rc;
     sum.hits += st.hits; sum.misses += st.misses; sum.bytes_h2d += st.bytes_h2d;
-    rc = moe_expert_ffn(cfg, x, expert_offsets, sorted_token, moe_cache_expert_table(c), nullptr, 1, 0, y,
-                        shared_out, ws, ws_bytes, stream);
-    if (rc) return rc;
+    // residents of the wave in one launch, then the misses in copy order (ascending id)
+    for (int pass = 0; pass < 2; ++pass) {
+      part.clear();
+      for (int k = 0; k <= n; ++k) {
+        if (k < n && (pass == 0) == (bool)was_resident[k]) part.push_back(ids[k]);
+        const bool flush = k == n || (pass == 1 && (int)part.size() == per_launch);
+        if (!flush || part.empty()) continue;
+        rc = publish(*c, part.data(), (int)part.size(), s);
+        if (rc) return rc;
+        rc = moe_expert_ffn(cfg, x, expert_offsets, sorted_token, moe_cache_expert_table(c), nullptr, 1, 0, y,
+                            shared_out, ws, ws_bytes, stream);
+        if (rc) return rc;
+        part.clear();
+      }
+    }
     ++waves;
   }
   if (n_waves) *n_waves = waves;

@@ -138,3 +138,70 @@ def test_offloaded_layer_with_8_bit_experts():
     stats, ref = run_offloaded(cfg, n_slots=5, seed=3)
     D = int((np.diff(ref["expert_offsets"]) > 0).sum())
     assert D > 5 and stats[0][1] == D and stats[0][2] == -(-D // 5)
+
+
+def test_prefetch_between_demand_and_ffn_launch():
+    """A PREFETCH call may come between a DEMAND call and the launch of the kernels that read its
+    slots: the next DEMAND call's copies into those slots still wait for these kernels.  The kernels
+    are held back on the compute stream by unrelated work, so a copy that did not wait would land
+    first and the layer output would be wrong."""
+    cfg = wl.LayerConfig("off_order", T=2, H=264, E=8, I=136, k_big=2, k_little=1, gate_std=0.3, w_std=0.1,
+                         fallback_ratio=0.5)
+    layer = wl.make_layer(cfg, seed=5)
+    dl = DeviceLayer(layer)
+    host = torch.stack([mm.to_device(b, cfg, "cpu") for b in layer.expert_w]).pin_memory()
+    n_slots = 4
+    slots_dev = torch.zeros((n_slots, host.shape[1]), dtype=host.dtype, device="cuda")
+    h = mm.moe_cache_create(cfg.E, host.shape[1] * host.element_size(), n_slots, host, slots_dev)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    ref = run_oracle_layer(layer, logits=logits)
+    busy = torch.randn((4096, 4096), device="cuda")
+    try:
+        for rep in range(3):
+            b = mm.StepBuffers(cfg)
+            b.logits.copy_(torch.from_numpy(logits))
+            mm.moe_route(b.c, dl.x, dl.Wg, dl.gate_bias, dl.conf, b.logits, True, b.topk_idx, b.topk_w, b.important,
+                         b.k_t)
+            mm.moe_dispatch(b.c, b.topk_idx, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                            b.dws, b.dws_bytes)
+            off = b.expert_offsets.cpu().numpy()
+            need = [e for e in range(cfg.E) if off[e + 1] > off[e]]
+            others = [e for e in range(cfg.E) if e not in need]
+            assert 1 <= len(need) <= n_slots and len(others) >= n_slots
+            mm.expert_cache_fetch(h, need, DEMAND)
+            mm.expert_cache_fetch(h, others[:2], PREFETCH)          # between the DEMAND and its kernels
+            for _ in range(12):                                     # keeps the compute stream busy for a while
+                busy = torch.tanh(busy @ busy * 1e-3)
+            mm.moe_expert_ffn(b.c, dl.x, b.expert_offsets, b.sorted_token, mm.moe_cache_expert_table(h), dl.shared,
+                              True, True, b.y, b.shared_out, b.fws, b.fws_bytes)
+            mm.expert_cache_fetch(h, others[:n_slots], DEMAND)      # evicts every slot the kernels above read
+            mm.moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out)
+            torch.cuda.synchronize()
+            e = rel_err(out_to_f64(b.out), ref["out"])
+            assert e <= TOL_OUT, (rep, e)
+    finally:
+        mm.moe_cache_destroy(h)
+
+
+def test_prefetch_limit_and_slower_link_emulation():
+    E, n_slots, blob = 16, 8, 1 << 16
+    h, host, dev = make_cache(E, blob, n_slots, seed=4)
+    model = CacheModel(E, n_slots)
+    try:
+        mm.moe_cache_emulate_link(h, 0.5)                 # 128 KB blobs: about 0.26 ms of hold per copy
+        mm.moe_cache_set_prefetch_limit(h, 2)
+        for ids, mode in (([0, 1], DEMAND), ([2, 3, 4, 5], PREFETCH), ([2, 6, 7, 8, 9], PREFETCH), ([3, 9], DEMAND)):
+            slots, st = mm.expert_cache_fetch(h, ids, mode)
+            ref = model.fetch(ids, mode, 2) if mode == PREFETCH else model.fetch(ids, mode)
+            assert (slots, st.hits, st.misses, st.dropped) == (list(ref[0]), ref[1], ref[2], ref[3])
+        mm.moe_cache_set_prefetch_limit(h, -1)
+        slots, st = mm.expert_cache_fetch(h, [10, 11, 12], PREFETCH)
+        ref = model.fetch([10, 11, 12], PREFETCH)
+        assert (slots, st.misses, st.dropped) == (list(ref[0]), ref[2], ref[3]) and st.misses == 3
+        mm.moe_cache_sync(h)
+        torch.cuda.synchronize()
+        for s, e in enumerate(model.slot_expert):
+            if e >= 0:
+                assert torch.equal(dev[s].cpu(), host[e])
+    finally:
+        mm.moe_cache_destroy(h)
