@@ -178,6 +178,20 @@ int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_t* expert_o
                    const void* const* shared_w, int run_routed, int run_shared, float* y,
                    float* shared_out, void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): moe_expert_ffn with the SwiGLU activations kept in a
+ * buffer that is built into the library (device memory of moe_expert_ffn_static_max_bytes() =
+ * 8 MiB per GPU, held until the process ends) instead of a caller workspace.  Same arguments,
+ * results and errors as moe_expert_ffn otherwise; it calls no allocating routine.  A step whose
+ * moe_expert_ffn_workspace_bytes(cfg) exceeds the built-in buffer gets MOE_E_WORKSPACE and
+ * enqueues nothing.  All calls on one GPU share the buffer: calls that may overlap on that GPU
+ * (different streams without ordering between them) race; calls on one stream are safe. */
+size_t moe_expert_ffn_static_max_bytes(void);
+int moe_expert_ffn_static(const moe_config* cfg, const void* x, const int32_t* expert_offsets,
+                          const int32_t* sorted_token, const void* const* expert_w,
+                          const void* const* shared_w, int run_routed, int run_shared, float* y,
+                          float* shared_out, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * "... and finally summed" (Sec. II-A):
  *   out[t][:] = sum_{j < k_t[t]} topk_w[t][j] * y[inv_pos[t][j]][:]  +  sum_s shared_out[s][t][:]

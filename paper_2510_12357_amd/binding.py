@@ -28,7 +28,8 @@ ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "M
 EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_from", "moe_combine_add",
            "moe_expert_ffn_workspace_bytes", "moe_expert_blob_bytes",
-           "moe_shared_out_slabs", "moe_expert_ffn", "moe_combine", "moe_cache_create", "moe_cache_destroy",
+           "moe_shared_out_slabs", "moe_expert_ffn", "moe_expert_ffn_static", "moe_expert_ffn_static_max_bytes",
+           "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync",
            "moe_cache_set_prefetch_limit", "moe_cache_emulate_link")
 
@@ -86,6 +87,11 @@ def load_library() -> ctypes.CDLL:
     lib.moe_shared_out_slabs.restype = i32
     lib.moe_expert_ffn.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
                                    ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.moe_expert_ffn_static.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
+                                          ctypes.c_int, vp, vp, vp]
+    lib.moe_expert_ffn_static.restype = ctypes.c_int
+    lib.moe_expert_ffn_static_max_bytes.argtypes = []
+    lib.moe_expert_ffn_static_max_bytes.restype = sz
     lib.moe_combine.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_cache_create.argtypes = [i32, sz, i32, vp, vp]
     lib.moe_cache_create.restype = vp
@@ -225,6 +231,21 @@ def moe_expert_ffn(cfg: moe_config, x, expert_offsets, sorted_token, expert_w, s
                                          _ptr(sorted_token), ew, sw, int(bool(run_routed)),
                                          int(bool(run_shared)), _ptr(y), _ptr(shared_out), _ptr(ws),
                                          ws_bytes, _stream(stream)))
+
+
+def moe_expert_ffn_static_max_bytes() -> int:
+    return int(load_library().moe_expert_ffn_static_max_bytes())
+
+
+def moe_expert_ffn_static(cfg: moe_config, x, expert_offsets, sorted_token, expert_w, shared_w: Sequence,
+                          run_routed, run_shared, y, shared_out, stream=None) -> None:
+    """moe_expert_ffn without a workspace argument (the library's built-in scratch buffer)."""
+    sw = (ctypes.c_void_p * max(1, len(shared_w)))(*[t.data_ptr() for t in shared_w])
+    ew = ctypes.c_void_p(expert_w) if isinstance(expert_w, int) else _ptr(expert_w)
+    _check(load_library().moe_expert_ffn_static(ctypes.byref(cfg), _ptr(x), _ptr(expert_offsets),
+                                                _ptr(sorted_token), ew, sw, int(bool(run_routed)),
+                                                int(bool(run_shared)), _ptr(y), _ptr(shared_out),
+                                                _stream(stream)))
 
 
 def moe_combine(cfg: moe_config, y, topk_w, inv_pos, k_t, shared_out, out, stream=None) -> None:

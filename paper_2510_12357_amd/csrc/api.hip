@@ -5,9 +5,16 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "internal.h"
+
+// Scratch of moe_expert_ffn_static: the SwiGLU activations of one step, for callers that cannot
+// allocate.  One copy per GPU the library runs on, held until the process ends.  In host code the
+// name below is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+#define MOE_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
 
 namespace mm {
 
@@ -360,4 +367,48 @@ extern "C" int moe_combine_add(const moe_config* cfg, const float* y, const floa
   if (!y || !topk_w || !inv_pos || !k_t || !out) return fail(MOE_E_BADARG, "moe_combine_add: null tensor");
   ProfScope ps(kProfCombine, static_cast<hipStream_t>(stream));
   return launch_combine_add(*cfg, y, topk_w, inv_pos, k_t, j_lo, out, static_cast<hipStream_t>(stream));
+}
+
+// ---- the execution stage without any allocation ------------------------------------------------
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of `scratch`, looked up once per device (with it current).
+int static_scratch(void** out) {
+  int dev = 0;
+  MM_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MOE_E_UNSUPPORTED, "moe_expert_ffn_static: device ordinal %d", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    MM_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255)) return fail(MOE_E_HIP, "moe_expert_ffn_static: scratch symbol at %p", p);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return MOE_OK;
+}
+}  // namespace
+
+extern "C" size_t moe_expert_ffn_static_max_bytes(void) { return MOE_STATIC_SCRATCH_BYTES; }
+
+extern "C" int moe_expert_ffn_static(const moe_config* cfg, const void* x, const int32_t* expert_offsets,
+                                     const int32_t* sorted_token, const void* const* expert_w,
+                                     const void* const* shared_w, int run_routed, int run_shared, float* y,
+                                     float* shared_out, void* stream) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  const size_t need = ffn_layout(*cfg).total;
+  if (need > MOE_STATIC_SCRATCH_BYTES)
+    return fail(MOE_E_WORKSPACE, "moe_expert_ffn_static: the step needs %zu bytes of scratch, the built-in buffer holds %u; "
+                                 "use moe_expert_ffn with a workspace", need, MOE_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  // Nothing in the buffer has to start at zero: every activation row a down projection reads was
+  // written by the gate/up projection of the same call.
+  return moe_expert_ffn(cfg, x, expert_offsets, sorted_token, expert_w, shared_w, run_routed, run_shared, y,
+                        shared_out, ws, need, stream);
 }
