@@ -98,7 +98,7 @@ int moe_device_info(int32_t* n_cu, int32_t* is_gfx950);
  * moe_profile_enable(1) also clears earlier records.  moe_profile_read waits for the events of
  * one kind and returns how many launch sites were recorded and their summed duration.
  * Kinds: 0 router GEMM, 1 softmax/top-k/importance, 2 dispatch, 3 FFN gate+up (SwiGLU),
- * 4 FFN down, 5 combine, 6 token confidence. */
+ * 4 FFN down, 5 combine, 6 token confidence, 7 whole decode step (moe_layer_decode). */
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, int64_t* launches, double* total_ms);
 
@@ -201,6 +201,39 @@ int moe_expert_ffn_static(const moe_config* cfg, const void* x, const int32_t* e
 int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,
                 const int32_t* inv_pos, const int32_t* k_t, const float* shared_out, void* out,
                 void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * One decode step of the layer in ONE kernel launch: moe_route + moe_dispatch + moe_expert_ffn +
+ * moe_combine (selection and execution stage of Sec. II-A with the per-token expert count of
+ * Sec. III-A / Alg. 1) for steps of at most 64 tokens, dtype MOE_BF16 or MOE_BF16_W8.  Same
+ * arithmetic and the same outputs as the four calls: logits, topk_idx, topk_w, important, k_t,
+ * expert_offsets, sorted_token, sorted_rank, inv_pos, y, shared_out and out are all written and
+ * have the layouts documented above.  A decode step only streams 0.1 .. 1 GB of weights, so the
+ * launch gaps and pipeline ramps of five dependent kernels are a large part of it; here the
+ * shared experts (which need nothing from the router) stream while the selection is computed,
+ * and the down projections, the final sum and the next weights overlap inside one persistent
+ * kernel whose workgroups hand results over through device memory.
+ *
+ * expert_w  DEVICE array of E device pointers; every expert the step selects must be non-NULL
+ *           (an expert with a NULL entry is skipped and its rows of y keep their old contents)
+ * shared_w  HOST array of n_shared device pointers
+ * ws        device workspace of moe_layer_decode_workspace_bytes(cfg) bytes, 256-byte aligned.
+ *           It starts with the kernel's hand-over counters: call moe_layer_decode_init on it once
+ *           before its first use (enqueues a clear on `stream`); every step leaves them at zero.
+ *           Steps that share a workspace must not overlap (one stream, or ordered streams).
+ * Every wait inside the kernel is bounded; moe_layer_decode_status (synchronous, for tests and
+ * diagnostics) returns how many waits have ever given up on this workspace: 0 in a healthy run.
+ * Errors: MOE_E_UNSUPPORTED for fp32 layers and for T > 64 (use the separate calls).
+ */
+size_t moe_layer_decode_workspace_bytes(const moe_config* cfg);
+int moe_layer_decode_init(void* ws, size_t ws_bytes, void* stream);
+int moe_layer_decode_status(const void* ws, int32_t* timed_out_waits);
+int moe_layer_decode(const moe_config* cfg, const void* x, const void* Wg, const float* gate_bias,
+                     const float* conf, const void* const* expert_w, const void* const* shared_w,
+                     float* logits, int logits_given, int32_t* topk_idx, float* topk_w,
+                     uint8_t* important, int32_t* k_t, int32_t* expert_offsets, int32_t* sorted_token,
+                     int32_t* sorted_rank, int32_t* inv_pos, float* y, float* shared_out, void* out,
+                     void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Second pass of Alg. 1 at layer level.  Alg. 1 runs the little model (k_little experts per token)

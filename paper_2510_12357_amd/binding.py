@@ -28,7 +28,8 @@ ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "M
 EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_from", "moe_combine_add",
            "moe_expert_ffn_workspace_bytes", "moe_expert_blob_bytes",
-           "moe_shared_out_slabs", "moe_expert_ffn", "moe_expert_ffn_static", "moe_expert_ffn_static_max_bytes",
+           "moe_shared_out_slabs", "moe_layer_decode_workspace_bytes", "moe_layer_decode_init",
+           "moe_layer_decode_status", "moe_layer_decode", "moe_expert_ffn", "moe_expert_ffn_static", "moe_expert_ffn_static_max_bytes",
            "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync",
            "moe_cache_set_prefetch_limit", "moe_cache_emulate_link")
@@ -87,6 +88,15 @@ def load_library() -> ctypes.CDLL:
     lib.moe_shared_out_slabs.restype = i32
     lib.moe_expert_ffn.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
                                    ctypes.c_int, vp, vp, vp, sz, vp]
+    lib.moe_layer_decode_workspace_bytes.argtypes = [cfgp]
+    lib.moe_layer_decode_workspace_bytes.restype = sz
+    lib.moe_layer_decode_init.argtypes = [vp, sz, vp]
+    lib.moe_layer_decode_init.restype = ctypes.c_int
+    lib.moe_layer_decode_status.argtypes = [vp, ctypes.POINTER(i32)]
+    lib.moe_layer_decode_status.restype = ctypes.c_int
+    lib.moe_layer_decode.argtypes = [cfgp, vp, vp, vp, vp, vp, ctypes.POINTER(vp), vp, ctypes.c_int] + [vp] * 11 + [
+        vp, sz, vp]
+    lib.moe_layer_decode.restype = ctypes.c_int
     lib.moe_expert_ffn_static.argtypes = [cfgp, vp, vp, vp, vp, ctypes.POINTER(vp), ctypes.c_int,
                                           ctypes.c_int, vp, vp, vp]
     lib.moe_expert_ffn_static.restype = ctypes.c_int
@@ -161,7 +171,7 @@ def moe_device_info():
 
 
 PROFILE_KINDS = ("router_gemm", "route_topk", "dispatch", "ffn_gate_up", "ffn_down", "combine",
-                 "token_confidence")
+                 "token_confidence", "decode_step")
 
 
 def moe_profile_enable(on: bool) -> None:
@@ -231,6 +241,33 @@ def moe_expert_ffn(cfg: moe_config, x, expert_offsets, sorted_token, expert_w, s
                                          _ptr(sorted_token), ew, sw, int(bool(run_routed)),
                                          int(bool(run_shared)), _ptr(y), _ptr(shared_out), _ptr(ws),
                                          ws_bytes, _stream(stream)))
+
+
+def moe_layer_decode_workspace_bytes(cfg: moe_config) -> int:
+    return int(load_library().moe_layer_decode_workspace_bytes(ctypes.byref(cfg)))
+
+
+def moe_layer_decode_init(ws, ws_bytes: int, stream=None) -> None:
+    _check(load_library().moe_layer_decode_init(_ptr(ws), ws_bytes, _stream(stream)))
+
+
+def moe_layer_decode_status(ws) -> int:
+    """-> number of waits inside the kernel that have ever given up on this workspace (synchronises)"""
+    n = ctypes.c_int32(0)
+    _check(load_library().moe_layer_decode_status(_ptr(ws), ctypes.byref(n)))
+    return n.value
+
+
+def moe_layer_decode(cfg: moe_config, x, Wg, gate_bias, conf, expert_w, shared_w: Sequence, logits, logits_given,
+                     topk_idx, topk_w, important, k_t, expert_offsets, sorted_token, sorted_rank, inv_pos, y,
+                     shared_out, out, ws, ws_bytes: int, stream=None) -> None:
+    sw = (ctypes.c_void_p * max(1, len(shared_w)))(*[t.data_ptr() for t in shared_w])
+    ew = ctypes.c_void_p(expert_w) if isinstance(expert_w, int) else _ptr(expert_w)
+    _check(load_library().moe_layer_decode(ctypes.byref(cfg), _ptr(x), _ptr(Wg), _ptr(gate_bias), _ptr(conf), ew, sw,
+                                           _ptr(logits), int(bool(logits_given)), _ptr(topk_idx), _ptr(topk_w),
+                                           _ptr(important), _ptr(k_t), _ptr(expert_offsets), _ptr(sorted_token),
+                                           _ptr(sorted_rank), _ptr(inv_pos), _ptr(y), _ptr(shared_out), _ptr(out),
+                                           _ptr(ws), ws_bytes, _stream(stream)))
 
 
 def moe_expert_ffn_static_max_bytes() -> int:
@@ -354,6 +391,12 @@ class StepBuffers:
         self.fws_bytes = moe_expert_ffn_workspace_bytes(self.c)
         self.fws = torch.empty((self.fws_bytes,), dtype=torch.uint8, device=device)
         self.ev_in, self.ev_shared = torch.cuda.Event(), torch.cuda.Event()
+        # workspace of moe_layer_decode (steps of at most 64 tokens, bf16 activations), cleared once
+        self.lws_bytes = moe_layer_decode_workspace_bytes(self.c) if 0 < T <= 64 and cfg.dtype != "fp32" else 0
+        self.lws = None
+        if self.lws_bytes:
+            self.lws = torch.empty((self.lws_bytes,), dtype=torch.uint8, device=device)
+            moe_layer_decode_init(self.lws, self.lws_bytes)
 
 
 def layer_step(b: StepBuffers, x, Wg, gate_bias, conf, expert_table, shared_w, logits_given=False,
@@ -380,6 +423,15 @@ def layer_step(b: StepBuffers, x, Wg, gate_bias, conf, expert_table, shared_w, l
     if overlap:
         main.wait_event(b.ev_shared)
     moe_combine(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, b.shared_out, b.out, stream)
+    return b.out
+
+
+def layer_decode_step(b: StepBuffers, x, Wg, gate_bias, conf, expert_table, shared_w, logits_given=False,
+                      stream=None) -> torch.Tensor:
+    """One decode step (at most 64 tokens) of the layer in one launch: a single C call."""
+    moe_layer_decode(b.c, x, Wg, gate_bias, conf, expert_table, shared_w, b.logits, logits_given, b.topk_idx,
+                     b.topk_w, b.important, b.k_t, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos, b.y,
+                     b.shared_out, b.out, b.lws, b.lws_bytes, stream)
     return b.out
 
 

@@ -369,6 +369,72 @@ extern "C" int moe_combine_add(const moe_config* cfg, const float* y, const floa
   return launch_combine_add(*cfg, y, topk_w, inv_pos, k_t, j_lo, out, static_cast<hipStream_t>(stream));
 }
 
+// ---- one decode step in one launch --------------------------------------------------------------
+namespace {
+int validate_decode(const moe_config* cfg) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (cfg->dtype == MOE_FP32) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: bf16 activations only (use the separate calls for fp32)");
+  if (cfg->T > kDecodeMaxTokens) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: T=%d above %d tokens (use the separate calls)", cfg->T, kDecodeMaxTokens);
+  if ((long long)cfg->T * cfg->k_big * cfg->H * 4 >= (1ll << 31)) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: y reaches 2 GiB");
+  return MOE_OK;
+}
+}  // namespace
+
+extern "C" size_t moe_layer_decode_workspace_bytes(const moe_config* cfg) {
+  if (validate_decode(cfg)) return 0;
+  return decode_sync_bytes() + ffn_layout(*cfg).total;
+}
+
+extern "C" int moe_layer_decode_init(void* ws, size_t ws_bytes, void* stream) {
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < decode_sync_bytes())
+    return fail(MOE_E_WORKSPACE, "moe_layer_decode_init: workspace %p of %zu bytes", ws, ws_bytes);
+  return launch_decode_sync_clear(ws, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int moe_layer_decode_status(const void* ws, int32_t* timed_out_waits) {
+  if (!ws || !timed_out_waits) return fail(MOE_E_BADARG, "moe_layer_decode_status: null argument");
+  int32_t v = 0;
+  MM_HIP(hipMemcpy(&v, static_cast<const int32_t*>(ws) + decode_sync_error_word(), sizeof v, hipMemcpyDeviceToHost));
+  *timed_out_waits = v;
+  return MOE_OK;
+}
+
+extern "C" int moe_layer_decode(const moe_config* cfg, const void* x, const void* Wg, const float* gate_bias,
+                                const float* conf, const void* const* expert_w, const void* const* shared_w,
+                                float* logits, int logits_given, int32_t* topk_idx, float* topk_w,
+                                uint8_t* important, int32_t* k_t, int32_t* expert_offsets, int32_t* sorted_token,
+                                int32_t* sorted_rank, int32_t* inv_pos, float* y, float* shared_out, void* out,
+                                void* ws, size_t ws_bytes, void* stream) {
+  int rc = validate_decode(cfg);
+  if (rc) return rc;
+  if (cfg->T == 0) return MOE_OK;
+  if (!x || !expert_w || !logits || !topk_idx || !topk_w || !important || !k_t || !expert_offsets || !sorted_token ||
+      !sorted_rank || !inv_pos || !y || !out)
+    return fail(MOE_E_BADARG, "moe_layer_decode: null tensor");
+  if (!logits_given && !Wg) return fail(MOE_E_BADARG, "moe_layer_decode: Wg is needed unless logits_given");
+  if (cfg->n_shared > 0 && (!shared_w || !shared_out)) return fail(MOE_E_BADARG, "moe_layer_decode: shared_w / shared_out missing");
+  for (int s = 0; s < cfg->n_shared; ++s)
+    if (!shared_w[s] || ((uintptr_t)shared_w[s] & 15)) return fail(MOE_E_BADARG, "moe_layer_decode: shared_w[%d] null or not 16-byte aligned", s);
+  const FfnLayout L = ffn_layout(*cfg);
+  const size_t sync_bytes = decode_sync_bytes();
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < sync_bytes + L.total)
+    return fail(MOE_E_WORKSPACE, "moe_layer_decode: workspace %p of %zu bytes (need %zu, 256-byte aligned)", ws, ws_bytes,
+                sync_bytes + L.total);
+  DecodeLaunch D = {};
+  D.x = x; D.Wg = Wg; D.gate_bias = gate_bias; D.conf = conf; D.expert_w = expert_w;
+  char* wsb = static_cast<char*>(ws) + sync_bytes;
+  for (int s = 0; s < cfg->n_shared; ++s) { D.shared_w[s] = shared_w[s]; D.h_shared[s] = wsb + L.h_shared[s]; }
+  D.logits_given = logits_given != 0;
+  D.logits = logits; D.topk_idx = topk_idx; D.topk_w = topk_w; D.important = important; D.k_t = k_t;
+  D.expert_offsets = expert_offsets; D.sorted_token = sorted_token; D.sorted_rank = sorted_rank; D.inv_pos = inv_pos;
+  D.h_routed = wsb + L.h_routed; D.y = y; D.shared_out = shared_out; D.out = out;
+  D.sync = ws;
+  D.spin_limit = 1 << 18;                 // a good tenth of a second of polling: far beyond any wait of a healthy step
+  ProfScope ps(kProfDecodeStep, static_cast<hipStream_t>(stream));
+  return launch_decode_step(*cfg, D, static_cast<hipStream_t>(stream));
+}
+
 // ---- the execution stage without any allocation ------------------------------------------------
 namespace {
 constexpr int kMaxDevices = 64;

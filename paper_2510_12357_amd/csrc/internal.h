@@ -21,7 +21,7 @@ int validate_config(const moe_config* cfg);
 
 // ---- optional per-kernel timing (moe_profile_*): an event pair around each launch site -------
 enum ProfKind { kProfRouterGemm = 0, kProfRouteTopk, kProfDispatch, kProfFfnGateUp, kProfFfnDown,
-                kProfCombine, kProfConfidence, kProfKinds };
+                kProfCombine, kProfConfidence, kProfDecodeStep, kProfKinds };
 void prof_mark(int kind, bool begin, hipStream_t s);
 struct ProfScope {
   int kind; hipStream_t s;
@@ -86,6 +86,25 @@ int launch_stream_lds(StreamMode mode, int weight_bytes, const StreamArgs& a, hi
 
 // ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime, bf16) -------------------------
 int launch_tiled(StreamMode mode, const StreamArgs& a, hipStream_t s);
+
+// ---- a whole decode step in one launch (decode_step.hip) -------------------------------------
+constexpr int kDecodeMaxTokens = 64;
+struct DecodeLaunch {
+  const void* x; const void* Wg; const float* gate_bias; const float* conf;
+  const void* const* expert_w;            // device table [E]
+  const void* shared_w[MOE_MAX_SHARED];
+  int logits_given;
+  float* logits; int32_t* topk_idx; float* topk_w; uint8_t* important; int32_t* k_t;
+  int32_t* expert_offsets; int32_t* sorted_token; int32_t* sorted_rank; int32_t* inv_pos;
+  void* h_routed; void* h_shared[MOE_MAX_SHARED];
+  float* y; float* shared_out; void* out;
+  void* sync;                             // decode_sync_bytes() of counters, zero between steps
+  int spin_limit;                         // polls after which a wait inside the kernel gives up
+};
+size_t decode_sync_bytes();
+int decode_sync_error_word();             // index (in ints) of the error word inside the counters
+int launch_decode_sync_clear(void* sync, hipStream_t s);
+int launch_decode_step(const moe_config& c, const DecodeLaunch& L, hipStream_t s);
 
 // ---- selection, dispatch, combine -----------------------------------------------------------
 int launch_route(const moe_config& c, const float* conf, const float* logits, int32_t* idx,
