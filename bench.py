@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--layers", type=int, default=0, help="distinct layers cycled (0 = auto)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="decode steps through the four separate calls instead of moe_layer_decode")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: throughput over fallback ratio and little-model size "
                          "(one JSON line per point; the shapes of the paper's Tables 4 and 5)")
@@ -152,8 +154,22 @@ def side_stream(torch):
     return _SIDE["s"]
 
 
+SEPARATE_CALLS = False
+
+
+def one_launch(cfg) -> bool:
+    """Steps of at most 64 tokens on bf16 activations run as one launch (moe_layer_decode)."""
+    return not SEPARATE_CALLS and 0 < cfg.T <= 64 and cfg.dtype != "fp32"
+
+
 def run_steps(mm, torch, layers: DeviceLayers, bufs, n: int, first: int = 0):
     L = layers.L
+    if one_launch(layers.cfg):
+        for i in range(first, first + n):
+            l = i % L
+            mm.layer_decode_step(bufs, layers.x[l], layers.Wg[l], layers.bias[l], layers.conf[l], layers.table[l],
+                                 layers.shared[l])
+        return
     side = side_stream(torch)
     for i in range(first, first + n):
         l = i % L
@@ -600,11 +616,16 @@ def main():
                               write_bytes_per_launch=n)))
         return
 
+    global SEPARATE_CALLS
+    SEPARATE_CALLS = args.separate_calls
     cfg = workload_config(args.workload, args.ratio)
     main_res = time_workload(mm, torch, cfg, args.steps, args.warmup, args.layers)
     work = algorithmic_work(cfg, main_res["P_mean"], main_res["D_mean"])
     kern = main_res["kernels"]
-    gu = kern["ffn_gate_up"]
+    fused = one_launch(cfg)
+    gu = kern["decode_step"] if fused else kern["ffn_gate_up"]
+    if fused:       # the one kernel of the step moves all of the step's bytes
+        work["gate_up_bytes"], work["gate_up_flops"] = work["step_bytes"], work["step_flops"]
     prefill = cfg.T >= 1024
     if prefill and work["gate_up_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e12 > work["gate_up_bytes"] / HBM_PEAK_GBS / 1e9:
         ach = work["gate_up_flops"] / (gu["avg_us"] * 1e-6) / 1e12
@@ -614,7 +635,8 @@ def main():
         ach = work["gate_up_bytes"] / (gu["avg_us"] * 1e-6) / 1e9
         roofline = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS,
                         traffic=stored_traffic(args.workload))
-    roofline["kernel"] = ("tiled_kernel<kGateUp>" if cfg.T >= 256 else "stream_lds_kernel<kGateUp>") + " (ffn_gate_up)"
+    roofline["kernel"] = ("decode_step_kernel (the whole step)" if fused else
+                          ("tiled_kernel<kGateUp>" if cfg.T >= 256 else "stream_lds_kernel<kGateUp>") + " (ffn_gate_up)")
     roofline["avg_us"] = gu["avg_us"]
     roofline["algorithmic_bytes"] = work["gate_up_bytes"]
 
@@ -639,12 +661,16 @@ def main():
             r2 = time_workload(mm, torch, c2, k2, w2)
             wk = algorithmic_work(c2, r2["P_mean"], r2["D_mean"])
             floor = max(wk["step_bytes"] / HBM_PEAK_GBS / 1e3, wk["step_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e6)
-            g2 = r2["kernels"]["ffn_gate_up"]["avg_us"]
             others[name] = dict(tokens_per_s=r2["tokens_per_s"], us_per_step=r2["ms_per_step"] * 1e3,
                                 step_roofline_frac=floor / (r2["ms_per_step"] * 1e3),
-                                gate_up_us=g2, gate_up_hbm_frac=wk["gate_up_bytes"] / (g2 * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                                gate_up_mfma_frac=wk["gate_up_flops"] / (g2 * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                                 kernels_us={k: round(v["avg_us"], 2) for k, v in r2["kernels"].items()})
+            if "ffn_gate_up" in r2["kernels"]:
+                g2 = r2["kernels"]["ffn_gate_up"]["avg_us"]
+                others[name].update(gate_up_us=g2, gate_up_hbm_frac=wk["gate_up_bytes"] / (g2 * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                    gate_up_mfma_frac=wk["gate_up_flops"] / (g2 * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+            else:
+                g2 = r2["kernels"]["decode_step"]["avg_us"]
+                others[name].update(step_kernel_us=g2, step_kernel_hbm_frac=wk["step_bytes"] / (g2 * 1e-6) / 1e9 / HBM_PEAK_GBS)
             del r2
             torch.cuda.empty_cache()
         # Eq. 1 of the paper from measured layer times: T (all big), T_l (all little), T_b (all big,

@@ -30,13 +30,15 @@
 //     that starts a down item first waits until that group's counter has reached the number of tiles
 //     the group has.  The loaders never wait: the down weights are already in the ring by then.
 //   * down -> sum: the wave that stored a tile of y bumps `col_done` of its 32 output columns; the
-//     wave that brings it to the number of tiles of the step sums those columns for all tokens
-//     (ascending rank, then the shared slabs: the order of the stand-alone combine).
-//   * hand-over through memory: producers store with the system-coherent cache policy, wait for
-//     the stores (s_waitcnt vmcnt(0)) and then bump the counter with a device-scope atomic;
-//     consumers poll the counter with device-scope atomic loads and read the data with coherent
-//     loads.  (Plain accesses are not enough: the eight XCDs have separate L2 caches, and a line
-//     left there by the previous step would be served again.)
+//     workgroup whose wave brings it to the number of tiles of the step notes the columns and, when
+//     it has run out of items, sums them for all tokens with all its waves (ascending rank, then
+//     the shared slabs: the order of the stand-alone combine).
+//   * hand-over through memory: producers store with the device-coherent cache policy (sc1:
+//     written through), and one iteration later, when the stores have long been acknowledged
+//     (s_waitcnt vmcnt(0) then costs nothing), bump the counter with a device-scope atomic;
+//     consumers poll the counter with device-scope atomic loads and read the data with sc1 loads.
+//     (Plain accesses are not enough: the eight XCDs have separate L2 caches; plain stores stay
+//     in the writer's L2 and plain loads are served stale lines, as a probe on the box showed.)
 //   * no deadlock: an item only ever waits for items that precede it in the list, every workgroup
 //     walks its items in list order, and all workgroups are resident.  Every wait is bounded all the
 //     same: after `spin_limit` polls it gives up, records the fact in the error word and goes on.
@@ -66,7 +68,17 @@ constexpr int kThreadsD = 2 * kWorkers * 64;
 constexpr int kTok = 32;                     // token rows per item, at most
 constexpr int kKParts = 2;
 constexpr int kReads = kRowBytes / 16 / 4 / kKParts;
-constexpr int kCoherent = 17;                // cache policy bits sc0 | sc1 of buffer loads / stores
+#ifndef MOE_DECODE_LD_AUX
+#define MOE_DECODE_LD_AUX 16
+#endif
+#ifndef MOE_DECODE_ST_AUX
+#define MOE_DECODE_ST_AUX 16
+#endif
+#ifndef MOE_DECODE_POLL_SLEEP
+#define MOE_DECODE_POLL_SLEEP 48
+#endif
+constexpr int kCoherent = 16;                // cache policy bit sc1 of buffer loads / stores: coherent across the device
+constexpr int kCoherentLd = MOE_DECODE_LD_AUX, kCoherentSt = MOE_DECODE_ST_AUX;   // the bulk data: activations, y
 constexpr unsigned kWholeBuffer = 0x7ffffff0u;
 
 #define MM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
@@ -85,12 +97,42 @@ __device__ __forceinline__ P* uni(P* p) {
 
 // ---- counters of a step (ints, in the caller's workspace; zero between steps) ------------------
 constexpr int kMaxColTiles = 1024;                            // H <= 32768
+// A counter that many workgroups bump within a short time (the activations of one group: one bump
+// per 16 x 16 tile) is cut into kShards counters; the tile picks its shard, a reader adds them up.
+constexpr int kShards = 8;
 enum {
   kSyncRouteDone = 0, kSyncExit = 1, kSyncErr = 2,
-  kSyncHDone = 4,                                             // [kMaxSlabs + MOE_MAX_EXPERTS]
-  kSyncColDone = kSyncHDone + kMaxSlabs + MOE_MAX_EXPERTS,    // [kMaxColTiles]
-  kSyncInts = kSyncColDone + kMaxColTiles
+  kSyncExitSub = 4,                                           // [kShards] first level of the exit ticket
+  kSyncHDone = kSyncExitSub + kShards,                        // [(kMaxSlabs + MOE_MAX_EXPERTS) * kShards]
+  kSyncColDone = kSyncHDone + (kMaxSlabs + MOE_MAX_EXPERTS) * kShards,   // [kMaxColTiles]
+  kSyncToken = kSyncColDone + kMaxColTiles,                   // [kDecodeMaxTokens] router parts of a token that are done
+  kSyncInts = kSyncToken + kDecodeMaxTokens
 };
+
+#ifdef MOE_DECODE_TRACE
+// Timeline of a step for analysis builds: 16 time stamps (100 MHz wall clock) per workgroup behind the counters.
+constexpr int kTraceSlots = 16;
+#define MM_TRACE(slot) do { if (tid == 4 * 64 && (slot) < kTraceSlots) \
+  reinterpret_cast<long long*>(a.sync + kSyncInts * kCtrStride)[(size_t)blockIdx.x * kTraceSlots + (slot)] = wall_clock64(); } while (0)
+#else
+#define MM_TRACE(slot) do { } while (0)
+#endif
+#if defined(MOE_DECODE_TRACE) && MOE_DECODE_TRACE == 2
+// per-iteration stamps: loader wave 0 in slots 0..15 of the upper half, computer wave 4 in the lower half
+#define MM_TRACE_IT(who, it) do { if ((it) < 16 && lane == 0 && wave == (who)) \
+  reinterpret_cast<long long*>(a.sync + kSyncInts * kCtrStride)[(size_t)(512 + ((who) ? 512 : 0) + blockIdx.x) * kTraceSlots + (it)] = wall_clock64(); } while (0)
+#else
+#define MM_TRACE_IT(who, it) do { } while (0)
+#endif
+
+// Every counter sits in a block of its own: device-scope atomics on one address are served one
+// after the other at the memory side, and counters that shared a cache line made all their updates
+// queue on one memory channel, in front of the weight stream.
+#ifndef MOE_DECODE_CTR_STRIDE
+#define MOE_DECODE_CTR_STRIDE 64
+#endif
+constexpr int kCtrStride = MOE_DECODE_CTR_STRIDE;             // ints between counters (256 bytes)
+__device__ __forceinline__ int* ctr(int* sync, int index) { return sync + (size_t)index * kCtrStride; }
 
 __device__ __forceinline__ int counter_load(const int* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -98,12 +140,29 @@ __device__ __forceinline__ int counter_load(const int* p) {
 __device__ __forceinline__ int counter_bump(int* p) {
   return __hip_atomic_fetch_add(p, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// One lane polls until the counter has reached `want`; bounded.
+// Sum of the kShards counters behind `index`: lane s < kShards loads shard s.  The loads are issued
+// here; `shard_sum` turns what they brought into the sum.
+__device__ __forceinline__ int shard_load(int* sync, int index, int lane) {
+  return lane < kShards ? counter_load(ctr(sync, index + lane)) : 0;
+}
+__device__ __forceinline__ int shard_sum(int v) { return wave_reduce(v, 0, [](int x, int y) { return x + y; }); }
+
+// One lane polls until the counter has reached `want`; bounded.  The pause between polls keeps
+// the polling of many waiting workgroups (all on a few addresses, i.e. on one memory channel) from
+// slowing the weight stream down.
 __device__ __forceinline__ void counter_wait(int* sync, int index, int want, int spin_limit) {
   int spins = 0;
-  while (counter_load(sync + index) < want) {
-    __builtin_amdgcn_s_sleep(8);
-    if (++spins > spin_limit) { atomicAdd(sync + kSyncErr, 1); break; }
+  while (counter_load(ctr(sync, index)) < want) {
+    __builtin_amdgcn_s_sleep(MOE_DECODE_POLL_SLEEP);
+    if (++spins > spin_limit) { atomicAdd(ctr(sync, kSyncErr), 1); break; }
+  }
+}
+// The same for a sharded counter: the whole wave takes part.
+__device__ __forceinline__ void shard_wait(int* sync, int index, int want, int spin_limit, int lane) {
+  int spins = 0;
+  while (shard_sum(shard_load(sync, index, lane)) < want) {
+    __builtin_amdgcn_s_sleep(MOE_DECODE_POLL_SLEEP);
+    if (++spins > spin_limit) { if (lane == 0) atomicAdd(ctr(sync, kSyncErr), 1); break; }
   }
 }
 
@@ -130,6 +189,7 @@ struct DecodeArgs {
   const float* bias;
   const float* conf;
   int logits_given;
+  int route_split;                    // workgroups that share the router dot products of one token
   float* logits;                      // [T,E]
   int32_t* topk_idx;                  // [T,k_big]
   float* topk_w;
@@ -158,6 +218,9 @@ struct Smem {
   int off[MOE_MAX_EXPERTS + 1];        // first dispatch position of each expert
   int prefix[kMaxUGroups + 1];         // first item of each group of the unified list
   int col_want;                        // y tiles per 32 output columns in this step
+  unsigned tile_bits[kMaxColTiles / 32];   // column tiles this workgroup sums when it has no items left
+  int dep_seq;                         // 1 + ordinal of the latest item whose dependency wave 4 has seen met
+  int flag;
 };
 
 struct DItem {
@@ -245,7 +308,7 @@ __device__ __forceinline__ DItem decode_item(const DecodeArgs& a, const Smem& sm
     out = static_cast<char*>(a.h_routed) + (size_t)row0 * a.I * 2u;
     scale = reinterpret_cast<const float*>(blob + 3 * (size_t)a.I * a.H * wsz);
     it.expert = gg;
-    it.sig = kSyncHDone + a.n_slabs + gg;
+    it.sig = kSyncHDone + (a.n_slabs + gg) * kShards;     // + shard, per item below
   } else if ((gg -= a.E) < a.n_slabs) {                        // C: down, K chunk of a shared expert
     const int s = a.slab_shared[gg], kb = a.slab_chunk[gg] * a.shared_kchunk[s];
     const int Is = a.shared_I[s];
@@ -256,7 +319,7 @@ __device__ __forceinline__ DItem decode_item(const DecodeArgs& a, const Smem& sm
     out = reinterpret_cast<char*>(a.shared_out + (size_t)gg * a.T * a.H);
     scale = reinterpret_cast<const float*>(blob + 3 * (size_t)Is * a.H * wsz) + 2 * (size_t)Is;
     it.down = 1;
-    it.dep = kSyncHDone + gg; it.dep_want = ((K + 15) / 16) * ((a.T + 15) / 16);
+    it.dep = kSyncHDone + gg * kShards; it.dep_want = ((K + 15) / 16) * ((a.T + 15) / 16);
   } else {                                                     // C: down of routed expert gg
     gg -= a.n_slabs;
     const char* blob = static_cast<const char*>(uni(sm.blob[gg]));
@@ -268,7 +331,7 @@ __device__ __forceinline__ DItem decode_item(const DecodeArgs& a, const Smem& sm
     out = reinterpret_cast<char*>(a.y + (size_t)row0 * a.H);
     scale = reinterpret_cast<const float*>(blob + 3 * (size_t)a.I * a.H * wsz) + 2 * (size_t)a.I;
     it.down = 1;
-    it.dep = kSyncHDone + a.n_slabs + gg; it.dep_want = ((a.I + 15) / 16) * ((m + 15) / 16);
+    it.dep = kSyncHDone + (a.n_slabs + gg) * kShards; it.dep_want = ((a.I + 15) / 16) * ((m + 15) / 16);
   }
   // ---- the item inside the group: blocks of 8 row tiles, the token blocks of a row tile 8 items
   // apart (on workgroups of the same XCD at the same time, so the repeated weight reads hit in L2)
@@ -298,7 +361,9 @@ __device__ __forceinline__ DItem decode_item(const DecodeArgs& a, const Smem& sm
     // the K chunk of the shared expert's down projection that these 16 activations feed
     int first_slab = 0;
     for (int s = 0; s < g; ++s) first_slab += (a.shared_I[s] + a.shared_kchunk[s] - 1) / a.shared_kchunk[s];
-    it.sig = kSyncHDone + first_slab + it.n0 / a.shared_kchunk[g];
+    it.sig = kSyncHDone + (first_slab + it.n0 / a.shared_kchunk[g]) * kShards + ((it.n0 >> 4) & (kShards - 1));
+  } else if (it.expert >= 0) {
+    it.sig += (it.n0 >> 4) & (kShards - 1);
   } else if (it.down) {
     it.sig = kSyncColDone + it.n0 / 32;
   }
@@ -333,33 +398,57 @@ __device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
   return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
 }
 
-// out[t][c .. c+3] for the 32 columns of tile `tile` and all tokens: one wave.  Sum order: rank
-// ascending, then the shared slabs ascending (as the stand-alone combine).
-__device__ __forceinline__ void sum_columns(const DecodeArgs& a, const Smem& sm, int tile, int lane) {
+// out[t][c .. c+3] for the 32 columns of tile `tile` and all tokens, by the 8 waves of a workgroup:
+// wave w takes tokens 8 w .. 8 w + 7, a lane four columns of one token.  All loads of a kind are
+// issued together.  Sum order: rank ascending, then the shared slabs ascending (as the stand-alone
+// combine); ranks from k_t on carry expert -1.
+__device__ __forceinline__ void sum_columns(const DecodeArgs& a, const Smem& sm, int tile, int wave, int lane) {
   const int cc = tile * 32 + (lane & 7) * 4;
+  const int t = wave * 8 + (lane >> 3);
+  if (t >= a.T || cc >= a.H) return;
   const __amdgpu_buffer_rsrc_t ry = make_rsrc(a.y, kWholeBuffer);
   const __amdgpu_buffer_rsrc_t rs = make_rsrc(a.shared_out, a.shared_out ? kWholeBuffer : 0u);
-  for (int t0 = 0; t0 < a.T; t0 += 8) {
-    const int t = t0 + (lane >> 3);
-    if (t >= a.T || cc >= a.H) continue;
-    int kt = coherent_load_i32(a.k_t, (unsigned)t * 4u);
-    kt = kt < 0 ? 0 : (kt > a.k_big ? a.k_big : kt);
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int j = 0; j < kt; ++j) {
-      const int e = coherent_load_i32(a.topk_idx, (unsigned)(t * a.k_big + j) * 4u);
-      if ((unsigned)e >= (unsigned)a.E) continue;
-      const float wj = __int_as_float(coherent_load_i32(a.topk_w, (unsigned)(t * a.k_big + j) * 4u));
-      const int p = sm.off[e] + __popcll(sm.mask[e] & bits_below(t));
-      const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(ry, (int)(((unsigned)p * a.H + cc) * 4u), 0, kCoherent);
-      acc += wj * __builtin_bit_cast(f32x4, v);
-    }
-    for (int s = 0; s < a.n_slabs; ++s) {
-      const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)((((unsigned)s * a.T + t) * a.H + cc) * 4u), 0, kCoherent);
-      acc += __builtin_bit_cast(f32x4, v);
-    }
-    bf16x4 o = {(__bf16)acc[0], (__bf16)acc[1], (__bf16)acc[2], (__bf16)acc[3]};
-    *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(a.out) + (size_t)t * a.H + cc) = o;
+  const __amdgpu_buffer_rsrc_t ri = make_rsrc(a.topk_idx, kWholeBuffer), rw = make_rsrc(a.topk_w, kWholeBuffer);
+  int e[MOE_MAX_TOPK];
+  float w[MOE_MAX_TOPK];
+#pragma unroll
+  for (int j = 0; j < MOE_MAX_TOPK; ++j) {
+    const unsigned off = j < a.k_big ? (unsigned)(t * a.k_big + j) * 4u : kOob;
+    e[j] = __builtin_amdgcn_raw_buffer_load_b32(ri, (int)off, 0, kCoherent);
+    w[j] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rw, (int)off, 0, kCoherent));
+    if (j >= a.k_big) e[j] = -1;
   }
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  static_assert(MOE_MAX_TOPK % 8 == 0 && kMaxSlabs % 4 == 0, "batches of 8 ranks and 4 slabs");
+#pragma unroll
+  for (int j0 = 0; j0 < MOE_MAX_TOPK; j0 += 8) {
+    if (j0 >= a.k_big) break;
+    i32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const bool ok = (unsigned)e[j0 + j] < (unsigned)a.E;
+      const int ee = ok ? e[j0 + j] : 0;
+      const int p = sm.off[ee] + __popcll(sm.mask[ee] & bits_below(t));
+      v[j] = __builtin_amdgcn_raw_buffer_load_b128(ry, (int)(ok ? ((unsigned)p * a.H + cc) * 4u : kOob), 0, kCoherent);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if ((unsigned)e[j0 + j] < (unsigned)a.E) acc += w[j0 + j] * __builtin_bit_cast(f32x4, v[j]);
+  }
+#pragma unroll
+  for (int s0 = 0; s0 < kMaxSlabs; s0 += 4) {
+    if (s0 >= a.n_slabs) break;
+    i32x4 sv[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      sv[s] = __builtin_amdgcn_raw_buffer_load_b128(
+          rs, (int)(s0 + s < a.n_slabs ? (((unsigned)(s0 + s) * a.T + t) * a.H + cc) * 4u : kOob), 0, kCoherent);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      if (s0 + s < a.n_slabs) acc += __builtin_bit_cast(f32x4, sv[s]);
+  }
+  bf16x4 o = {(__bf16)acc[0], (__bf16)acc[1], (__bf16)acc[2], (__bf16)acc[3]};
+  *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(a.out) + (size_t)t * a.H + cc) = o;
 }
 
 template <int WB>
@@ -376,8 +465,10 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   const int n_groups = a.n_shared + a.E + a.n_slabs + a.E;
   const int gA = a.n_shared;                                  // groups of segment A
 
+  MM_TRACE(0);
   // ---- prologue: expert pointers, segment A of the item list ----
   for (int e = tid; e < a.E; e += kThreadsD) { sm.blob[e] = a.expert_w[e]; sm.mask[e] = 0ull; }
+  for (int i = tid; i < kMaxColTiles / 32; i += kThreadsD) sm.tile_bits[i] = 0u;
   if (tid == 0) {
     int run = 0;
     sm.prefix[0] = 0;
@@ -386,19 +477,31 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
     for (int g = gA; g < n_groups; ++g) sm.prefix[g + 1] = run;
   }
 
-  // ---- selection stage: workgroup b < T routes token b ----
-  if ((int)blockIdx.x < a.T) {
-    const int t = blockIdx.x;
-    float* s_logit = &s_red[0][0][0][0];
+  // ---- selection stage: `route_split` workgroups per token compute its router logits (one pass
+  // of 32 experts each); the one that finishes last selects ----
+  if (tid == 0) sm.dep_seq = 0;
+  // (the last workgroups of the grid: they get the fewest items of segment A, i.e. they would wait
+  // for the selection first of all)
+  const int route_id = G - 1 - (int)blockIdx.x;
+  if (route_id < a.T * a.route_split) {
+    const int t = route_id / a.route_split, part = route_id - t * a.route_split;
+    const __amdgpu_buffer_rsrc_t rl = make_rsrc(a.logits, kWholeBuffer);
     if (!a.logits_given) {
-      gate_logits_token<uint16_t, 2 * kWorkers>(static_cast<const uint16_t*>(a.x) + (size_t)t * a.H,
-                                                static_cast<const uint16_t*>(a.Wg), a.bias, a.H, a.E, wave, lane,
-                                                a.logits + (size_t)t * a.E, s_logit);
-    } else {
-      for (int e = tid; e < a.E; e += kThreadsD) s_logit[e] = a.logits[(size_t)t * a.E + e];
+      const int per = (a.E + a.route_split - 1) / a.route_split;
+      const int e_begin = part * per, e_end = min(a.E, e_begin + per);
+      gate_logits_token<uint16_t, 2 * kWorkers>(
+          static_cast<const uint16_t*>(a.x) + (size_t)t * a.H, static_cast<const uint16_t*>(a.Wg), a.bias, a.H, a.E,
+          e_begin, e_end, wave, lane, [&](int e, float z) {
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(z), rl, (int)((unsigned)(t * a.E + e) * 4u), 0, kCoherent);
+          });
+      compiler_fence();
+      __builtin_amdgcn_s_waitcnt(0);                          // this wave's logits are in memory
+      compiler_fence();
     }
     __syncthreads();
-    if (wave == 0) {
+    if (tid == 0) sm.flag = a.logits_given ? part == 0 : counter_bump(ctr(a.sync, kSyncToken + t)) == a.route_split - 1;
+    __syncthreads();
+    if (sm.flag && wave == 0) {
       RouteParams P;
       P.conf = a.conf; P.gamma = a.gamma; P.T = a.T; P.E = a.E; P.k_big = a.k_big; P.k_little = a.k_little;
       P.renorm = a.renorm; P.idx = nullptr; P.w = nullptr; P.important = nullptr; P.k_t = nullptr;
@@ -406,7 +509,8 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
 #pragma unroll
       for (int c = 0; c < kPerLane; ++c) {
         const int e = lane + 64 * c;
-        raw[c] = (e < a.E) ? s_logit[e] : 0.f;
+        raw[c] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rl, (int)(e < a.E ? (unsigned)(t * a.E + e) * 4u : kOob), 0,
+                                                                     kCoherent));
       }
       const Selection sel = select_token_values(P, t, lane, raw);
       if (lane < a.k_big) {
@@ -414,16 +518,17 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
         coherent_store_i32(a.topk_w, (unsigned)(t * a.k_big + lane) * 4u, __float_as_int(sel.weight));
       }
       if (lane == 0) {
-        coherent_store_i32(a.k_t, (unsigned)t * 4u, sel.k);
+        a.k_t[t] = sel.k;
         a.important[t] = sel.imp ? 1 : 0;
       }
       compiler_fence();
-      __builtin_amdgcn_s_waitcnt(0);                        // the stores have been acknowledged
+      __builtin_amdgcn_s_waitcnt(0);                          // the stores have been acknowledged
       compiler_fence();
-      if (lane == 0) counter_bump(a.sync + kSyncRouteDone);
+      if (lane == 0) counter_bump(ctr(a.sync, kSyncRouteDone));
     }
   }
   __syncthreads();
+  MM_TRACE(1);
   const int total_A = sm.prefix[gA];
 
   // Iteration at which this workgroup's loaders issue their first chunk behind segment A: all A
@@ -436,7 +541,9 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   auto dispatch_block = [&]() {
     const bool reader = wave >= kWorkers;                     // only computer waves touch global memory here
     const int rt = tid - kWorkers * 64;                       // 0..255 among the readers
+    MM_TRACE(2);
     if (rt == 0) counter_wait(a.sync, kSyncRouteDone, a.T, a.spin_limit);
+    MM_TRACE(3);
     for (int e = tid; e < a.E; e += kThreadsD) sm.mask[e] = 0ull;
     lds_barrier();
     compiler_fence();
@@ -447,12 +554,10 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
       ent_e[u] = -1; ent_ok[u] = 0;
       const int i = rt + u * 256;
       if (reader && i < n_ent) {
-        const int t = i / a.k_big, j = i - t * a.k_big;
-        int kt = coherent_load_i32(a.k_t, (unsigned)t * 4u);
-        kt = kt < 0 ? 0 : (kt > a.k_big ? a.k_big : kt);
-        const int e = coherent_load_i32(a.topk_idx, (unsigned)i * 4u);
+        const int t = i / a.k_big;
+        const int e = coherent_load_i32(a.topk_idx, (unsigned)i * 4u);    // -1 from rank k_t on
         ent_e[u] = e;
-        ent_ok[u] = j < kt && (unsigned)e < (unsigned)a.E;
+        ent_ok[u] = (unsigned)e < (unsigned)a.E;
         if (ent_ok[u]) atomicOr(&sm.mask[e], 1ull << t);
       }
     }
@@ -491,6 +596,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
       }
     }
     lds_barrier();
+    MM_TRACE(4);
     total = sm.prefix[n_groups];
     // the dispatch arrays of the C ABI (workgroup 0, computer waves)
     if (blockIdx.x == 0 && reader) {
@@ -519,6 +625,8 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   if (wave < kWorkers) {
     // =================================== loader ===================================
     DItem it = decode_item<WB>(a, sm, blockIdx.x, total, n_groups, wave, lane);
+    DItem nx = it;
+    bool nx_known = false;
     int j = 0, k = 0, drain = 0, s = 0;
     unsigned a_col[4], addr[4];
 #pragma unroll
@@ -530,7 +638,8 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
     __amdgpu_buffer_rsrc_t rs = make_rsrc(it.w0, it.wbytes);
     MM_WAIT_VMCNT(0);
     auto set_item = [&]() {
-      it = decode_item<WB>(a, sm, blockIdx.x + j * G, total, n_groups, wave, lane);
+      it = nx_known ? nx : decode_item<WB>(a, sm, blockIdx.x + j * G, total, n_groups, wave, lane);
+      nx_known = false;
       rs = make_rsrc(it.w0, it.wbytes);
 #pragma unroll
       for (int i = 0; i < 4; ++i) addr[i] = it.a_row[i] + a_col[i] * 16u;
@@ -554,7 +663,13 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
         ++k;
 #pragma unroll
         for (int i = 0; i < 4; ++i) addr[i] += kRowBytes;
-        if (k == it.nch) { ++j; k = 0; set_item(); }        // LDS and registers only: nothing joins the counted loads
+        // the next item is decoded under the loads of this one's first chunk when the list is known
+        // that far (LDS and registers only: nothing joins the counted loads)
+        if (k == 1 && (block_done || (int)blockIdx.x + (j + 1) * G < total_A)) {
+          nx = decode_item<WB>(a, sm, blockIdx.x + (j + 1) * G, total, n_groups, wave, lane);
+          nx_known = true;
+        }
+        if (k == it.nch) { ++j; k = 0; set_item(); }
       }
       ++s;
       return real;
@@ -563,6 +678,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
       if (!block_done && s == s_star) { dispatch_block(); block_done = true; set_item(); }
       const bool real = issue_next();
       MM_WAIT_VMCNT(12);                                    // the chunk issued three iterations ago has landed
+      MM_TRACE_IT(0, s - 1);
       lds_barrier();                                        // "landed"
       lds_barrier();                                        // "free"
       if (!real && block_done && ++drain == 3) break;
@@ -574,6 +690,8 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
     DItem cur = decode_item<WB>(a, sm, blockIdx.x, total, n_groups, c, lane);
     int j = 0, k = 0;
     int pending = 0, started = 0;
+    int pub = -1, pub_down = 0;     // counter this wave still has to bump for outputs it stored (-1: none)
+    int tick = 0, tick_tile = -1;   // a bump of a column counter whose old value has not been looked at yet
     int f_r0 = 0, f_n0 = 0, f_m = 0, f_N = 0, f_ntn = 0, f_down = 0, f_sig = 0;
     void* f_out = nullptr;
     f32x4 sc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}}, f_sc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
@@ -622,7 +740,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
             }
             bf16x4 o = {(__bf16)hv[0], (__bf16)hv[1], (__bf16)hv[2], (__bf16)hv[3]};
             __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(i32x2, o), ro,
-                                                  (int)(((unsigned)r * f_N + i) * 2u), 0, kCoherent);
+                                                  (int)(((unsigned)r * f_N + i) * 2u), 0, kCoherentSt);
           }
         } else {
 #pragma unroll
@@ -631,7 +749,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
             if (col < f_N)
               __builtin_amdgcn_raw_buffer_store_b128(
                   __builtin_bit_cast(i32x4, f32x4{val[rt][0], val[rt][1], val[rt][2], val[rt][3]}), ro,
-                  (int)(((unsigned)r * a.H + col) * 4u), 0, kCoherent);
+                  (int)(((unsigned)r * a.H + col) * 4u), 0, kCoherentSt);
           }
         }
       }
@@ -644,15 +762,30 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
 #pragma unroll
           for (int v = 0; v < 4; ++v) val[rt][v] = s_red[tw][rt][v][lane] + s_red[tw + 2][rt][v][lane];
         store_outputs(val);
-        // publish: stores acknowledged, then the counter
-        compiler_fence();
-        __builtin_amdgcn_s_waitcnt(0);
-        compiler_fence();
-        int old = 0;
-        if (lane == 0) old = counter_bump(a.sync + f_sig);
-        old = uni(old);
-        if (f_down && old + 1 == sm.col_want) sum_columns(a, sm, f_sig - kSyncColDone, lane);   // the step's last y tile of these columns
+        pub = f_sig; pub_down = f_down;                       // published later: see publish()
       }
+    };
+    // Tells the other workgroups that the outputs this wave stored last are in memory.  Called an
+    // iteration after the stores (their acknowledgements have arrived by then), or at once when this
+    // wave is about to wait for a counter itself.
+    auto publish = [&]() {
+      if (tick_tile >= 0) {           // issued an iteration ago: the old value has arrived
+        if (uni(tick) + 1 == sm.col_want && lane == 0)        // it was the step's last y tile of these 32 columns
+          atomicOr(&sm.tile_bits[tick_tile >> 5], 1u << (tick_tile & 31));
+        tick_tile = -1;
+      }
+      if (pub < 0) return;
+      compiler_fence();
+      __builtin_amdgcn_s_waitcnt(0);
+      compiler_fence();
+      if (!pub_down) {
+        if (lane == 0) (void)counter_bump(ctr(a.sync, pub));  // nobody needs the old value: no wait for it
+      } else {
+        tick = 0;
+        if (lane == 0) tick = counter_bump(ctr(a.sync, pub));   // looked at by the next call
+        tick_tile = pub - kSyncColDone;
+      }
+      pub = -1;
     };
     auto consume = [&](int stage) {
       const unsigned st = (unsigned)(stage * kStageBytes);
@@ -686,8 +819,11 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
     };
     // Token rows of chunk (cur, k) into bbuf.  The activations of a down item were written by other
     // workgroups within this kernel: coherent loads.
-    auto load_token_rows = [&]() {
-      MM_WAIT_VMCNT(0);
+    auto load_token_rows = [&](bool behind_stores) {
+      // Nothing of this wave is in flight any more (the previous token rows were consumed): saying so
+      // keeps the compiler from guarding every load below.  Not behind the stores of an epilogue:
+      // waiting for their acknowledgement would stall the wave for a memory round trip.
+      if (!behind_stores) MM_WAIT_VMCNT(0);
       const __amdgpu_buffer_rsrc_t rb = make_rsrc(cur.b, cur.bbytes);
 #pragma unroll
       for (int t = 0; t < kReads; ++t)
@@ -696,24 +832,47 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
           const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * (16 / WB) + h * 8;
           const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
           const int off = (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob);
-          if (cur.down) bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, kCoherent);
+          if (cur.down) bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, kCoherentLd);
           else bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, 0);
         }
     };
-    // An item becomes current: its row scales, and for a down item the activations it contracts
-    // must be complete.
-    auto begin_item = [&]() {
-      load_scales(cur);
-      if (cur.valid && cur.dep >= 0) {
-        if (lane == 0) counter_wait(a.sync, cur.dep, cur.dep_want, a.spin_limit);
-        compiler_fence();
+    // The item after the current one is decoded as soon as the current one has started, and the
+    // loads that look at its dependency are issued then: one item later, when it comes up, the
+    // answer has long arrived (the wave's loads return in order) and is almost always "met".
+    DItem nx = cur;
+    bool nx_known = false;
+    int look = 0;                     // this lane's shard of nx's dependency counter
+    auto peek = [&]() {
+      nx = decode_item<WB>(a, sm, blockIdx.x + (j + 1) * G, total, n_groups, c, lane);
+      nx_known = true;
+      look = (nx.valid && nx.dep >= 0) ? shard_load(a.sync, nx.dep, lane) : 0;
+    };
+    // Blocks until the activations a down item contracts are complete.  One wave per workgroup
+    // polls memory, the others watch its word in LDS.
+    auto wait_dep = [&]() {
+      if (!(cur.valid && cur.dep >= 0)) return;
+      const bool ready = shard_sum(shard_load(a.sync, cur.dep, lane)) >= cur.dep_want;
+      if (!ready) publish();          // the awaited activations may include the ones this wave has just stored
+      if (c == 0) {
+        if (!ready) shard_wait(a.sync, cur.dep, cur.dep_want, a.spin_limit, lane);
+        if (lane == 0) __hip_atomic_store(&sm.dep_seq, j + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      } else if (!ready && lane == 0) {
+        int spins = 0;
+        while (__hip_atomic_load(&sm.dep_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < j + 1) {
+          __builtin_amdgcn_s_sleep(4);
+          if (++spins > 64 * a.spin_limit) { atomicAdd(ctr(a.sync, kSyncErr), 1); break; }
+        }
       }
+      compiler_fence();
     };
 
     for (int s = 0;; ++s) {
       if (!block_done && s == s_star) { dispatch_block(); block_done = true; }
+      if (!nx_known && cur.valid && (block_done || (int)blockIdx.x + (j + 1) * G < total_A)) peek();
       lds_barrier();                                          // "landed"
-      bool stale = false;
+      MM_TRACE_IT(4, s);
+      publish();
+      bool stale = false, late = false;
       if (s >= 3 && cur.valid) {
         if (tw < cur.ntn) consume((s + 1) & (kStages - 1));
         if (++k == cur.nch) {                                 // item done: hand the partial sums over
@@ -726,59 +885,100 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
           f_down = cur.down; f_sig = cur.sig;
           f_sc[0] = sc[0]; f_sc[1] = sc[1];
           pending = 1;
+          MM_TRACE(min(5 + 2 * j, 13));                       // item j consumed
           ++j; k = 0;
           stale = true;
+          // The next item.  If nothing stands in its way (no dependency, or the early look found it
+          // met), its first token rows go out here, in front of the barrier, as within an item.
+          const bool had_look = nx_known;
+          cur = nx_known ? nx : decode_item<WB>(a, sm, blockIdx.x + j * G, total, n_groups, c, lane);
+          nx_known = false;
+          bool ready = cur.valid && cur.dep < 0;
+          if (cur.valid && cur.dep >= 0 && had_look) ready = shard_sum(look) >= cur.dep_want;
+          if (ready) {
+            load_scales(cur);
+            if (cur.dep >= 0 && c == 0 && lane == 0)
+              __hip_atomic_store(&sm.dep_seq, j + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (tw < cur.ntn) load_token_rows(false);
+          } else {
+            late = cur.valid;
+          }
         }
       }
       // token rows of the chunk consumed in the next iteration (same item)
       if (!stale && s >= 2 && cur.valid) {
-        if (!started) { started = 1; begin_item(); }
-        if (tw < cur.ntn) load_token_rows();
+        if (!started) { started = 1; load_scales(cur); wait_dep(); }
+        if (tw < cur.ntn) load_token_rows(false);
       }
       lds_barrier();                                          // "free"; partial sums of an item that ended are complete
       if (pending) { pending = 0; epilogue(); }
-      if (stale) {
-        // the next item: after the epilogue above, because a down item may wait for activations
-        // that this very workgroup has just stored
-        cur = decode_item<WB>(a, sm, blockIdx.x + j * G, total, n_groups, c, lane);
-        started = 1;
-        begin_item();
-        if (cur.valid && tw < cur.ntn) load_token_rows();
+      if (late) {
+        // behind the epilogue above: the item may wait for activations this very workgroup has just stored
+        load_scales(cur);
+        wait_dep();
+        if (tw < cur.ntn) load_token_rows(true);
       }
+      if (stale) { started = 1; MM_TRACE(min(4 + 2 * j, 12)); }
       if (!cur.valid && block_done && s >= 2) break;
+    }
+    publish();
+    publish();                        // ... and the old value of a bump the call above may have issued
+  }
+
+  // ---- the columns whose last y tile this workgroup stored: the final weighted sum ----
+  __syncthreads();
+  MM_TRACE(14);
+  for (int wd = 0; wd < (a.H + 1023) / 1024; ++wd) {
+    unsigned bits = sm.tile_bits[wd];
+    while (bits) {
+      const int tile = wd * 32 + __ffs((int)bits) - 1;
+      bits &= bits - 1;
+      sum_columns(a, sm, tile, wave, lane);
     }
   }
 
   // ---- the last workgroup to leave puts the counters back to zero ----
   __syncthreads();
+  MM_TRACE(15);
   __shared__ int s_last;
   if (tid == 0) {
     compiler_fence();
     __builtin_amdgcn_s_waitcnt(0);
-    s_last = counter_bump(a.sync + kSyncExit) == G - 1;
+    // two levels, so that the G tickets do not all queue on one address
+    const int sub = blockIdx.x & (kShards - 1);
+    const int in_sub = (G - sub + kShards - 1) / kShards;    // workgroups b with b % kShards == sub
+    s_last = 0;
+    if (counter_bump(ctr(a.sync, kSyncExitSub + sub)) == in_sub - 1)
+      s_last = counter_bump(ctr(a.sync, kSyncExit)) == min(G, kShards) - 1;
   }
   __syncthreads();
   if (s_last) {
-    const int n_h = a.n_slabs + a.E, n_c = (a.H + 31) / 32;
-    for (int i = tid; i < n_h; i += kThreadsD) coherent_store_i32(a.sync, (unsigned)(kSyncHDone + i) * 4u, 0);
-    for (int i = tid; i < n_c; i += kThreadsD) coherent_store_i32(a.sync, (unsigned)(kSyncColDone + i) * 4u, 0);
+    const int n_h = (a.n_slabs + a.E) * kShards, n_c = (a.H + 31) / 32;
+    if (tid < kShards) coherent_store_i32(a.sync, (unsigned)(kSyncExitSub + tid) * 4u * kCtrStride, 0);
+    for (int i = tid; i < n_h; i += kThreadsD) coherent_store_i32(a.sync, (unsigned)(kSyncHDone + i) * 4u * kCtrStride, 0);
+    for (int i = tid; i < n_c; i += kThreadsD) coherent_store_i32(a.sync, (unsigned)(kSyncColDone + i) * 4u * kCtrStride, 0);
+    if (tid < kDecodeMaxTokens) coherent_store_i32(a.sync, (unsigned)(kSyncToken + tid) * 4u * kCtrStride, 0);
     if (tid == 0) {
-      coherent_store_i32(a.sync, kSyncRouteDone * 4u, 0);
-      coherent_store_i32(a.sync, kSyncExit * 4u, 0);
+      coherent_store_i32(a.sync, kSyncRouteDone * 4u * kCtrStride, 0);
+      coherent_store_i32(a.sync, kSyncExit * 4u * kCtrStride, 0);
     }
   }
 }
 
 __global__ void decode_sync_clear_kernel(int* sync) {
-  for (int i = threadIdx.x; i < kSyncInts; i += blockDim.x) sync[i] = 0;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < kSyncInts * kCtrStride; i += gridDim.x * blockDim.x) sync[i] = 0;
 }
 
 }  // namespace
 
-size_t decode_sync_bytes() { return align256(sizeof(int) * kSyncInts); }
+#ifdef MOE_DECODE_TRACE
+size_t decode_sync_bytes() { return align256(sizeof(int) * kSyncInts * kCtrStride + 8 * kTraceSlots * 4096); }
+#else
+size_t decode_sync_bytes() { return align256(sizeof(int) * kSyncInts * kCtrStride); }
+#endif
 
 template <int WB>
-static int launch_decode_typed(const DecodeArgs& a, hipStream_t s) {
+static int launch_decode_typed(DecodeArgs& a, hipStream_t s) {
   static std::atomic<int> per_cu_cached{0};
   int per_cu = per_cu_cached.load(std::memory_order_relaxed);
   if (per_cu == 0) {
@@ -789,7 +989,9 @@ static int launch_decode_typed(const DecodeArgs& a, hipStream_t s) {
   }
   // persistent workgroups, all resident at once: the hand-overs inside the kernel rely on it
   const long grid = (long)device_cu_count() * per_cu;
-  if (grid < a.T) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: %ld resident workgroups for %d tokens", grid, a.T);
+  while (a.route_split > 1 && (long)a.T * a.route_split > grid) --a.route_split;
+  if (grid < (long)a.T * a.route_split)
+    return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: %ld resident workgroups for %d tokens x %d router parts", grid, a.T, a.route_split);
   hipLaunchKernelGGL((decode_step_kernel<WB>), dim3((unsigned)grid), dim3(kThreadsD), 0, s, a);
   return hip_fail(hipGetLastError(), "decode_step_kernel launch");
 }
@@ -809,7 +1011,9 @@ int launch_decode_step(const moe_config& c, const DecodeLaunch& L, hipStream_t s
   a.n_slabs = plan.n_slabs;
   for (int i = 0; i < plan.n_slabs; ++i) { a.slab_shared[i] = plan.slab_shared[i]; a.slab_chunk[i] = plan.slab_chunk[i]; }
   a.expert_w = L.expert_w; a.x = L.x; a.Wg = L.Wg; a.bias = L.gate_bias; a.conf = L.conf;
-  a.logits_given = L.logits_given; a.logits = L.logits; a.topk_idx = L.topk_idx; a.topk_w = L.topk_w;
+  a.logits_given = L.logits_given;
+  a.route_split = L.logits_given ? 1 : (c.E + 31) / 32;     // one pass of 8 waves x 4 experts per workgroup
+  a.logits = L.logits; a.topk_idx = L.topk_idx; a.topk_w = L.topk_w;
   a.important = L.important; a.k_t = L.k_t; a.expert_offsets = L.expert_offsets;
   a.sorted_token = L.sorted_token; a.sorted_rank = L.sorted_rank; a.inv_pos = L.inv_pos;
   a.h_routed = L.h_routed; a.y = L.y; a.shared_out = L.shared_out; a.out = L.out;
@@ -820,10 +1024,10 @@ int launch_decode_step(const moe_config& c, const DecodeLaunch& L, hipStream_t s
 }
 
 int launch_decode_sync_clear(void* sync, hipStream_t s) {
-  hipLaunchKernelGGL(decode_sync_clear_kernel, dim3(1), dim3(256), 0, s, static_cast<int*>(sync));
+  hipLaunchKernelGGL(decode_sync_clear_kernel, dim3(64), dim3(256), 0, s, static_cast<int*>(sync));
   return hip_fail(hipGetLastError(), "decode_sync_clear_kernel launch");
 }
 
-int decode_sync_error_word() { return kSyncErr; }
+int decode_sync_error_word() { return kSyncErr * kCtrStride; }
 
 }  // namespace mm

@@ -120,7 +120,9 @@ __global__ __launch_bounds__(kFusedWaves * 64) void gate_route_kernel(const S* _
   __shared__ float s_logit[MOE_MAX_EXPERTS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int t = blockIdx.x, E = P.E;
-  gate_logits_token<S, kFusedWaves>(x + (size_t)t * H, Wg, bias, H, E, wave, lane, logits + (size_t)t * E, s_logit);
+  float* const logits_row = logits + (size_t)t * E;
+  gate_logits_token<S, kFusedWaves>(x + (size_t)t * H, Wg, bias, H, E, 0, E, wave, lane,
+                                    [&](int e, float z) { logits_row[e] = z; s_logit[e] = z; });
   __syncthreads();
   if (wave != 0) return;
   float raw[kPerLane];

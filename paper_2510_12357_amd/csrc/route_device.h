@@ -165,20 +165,20 @@ template <> struct Raw8<float> {
   }
 };
 
-// Router logits of one token, computed by the NWAVES waves of a workgroup: the waves split the
-// experts, every wave sums its experts' dot products with the lanes striding the 8-element chunks of
-// the hidden dimension (chunks lane, lane + 64, ... in ascending order, U chunks per trip with all
-// loads issued before the first FMA) and reduces with the same shuffles everywhere, so a logit has
-// the same bits whichever kernel calls this.  Lane 0 of the wave that owns expert e writes
-// logits_row[e] and s_logit[e].
-template <typename S, int NWAVES>
+// Router logits of one token for the experts [e_begin, e_end), computed by the NWAVES waves of a
+// workgroup: the waves split the experts, every wave sums its experts' dot products with the lanes
+// striding the 8-element chunks of the hidden dimension (chunks lane, lane + 64, ... in ascending
+// order, U chunks per trip with all loads issued before the first FMA) and reduces with the same
+// shuffles everywhere, so a logit has the same bits whichever kernel calls this and however the
+// experts are split.  Lane 0 of the wave that owns expert e calls store(e, logit).
+template <typename S, int NWAVES, typename Store>
 __device__ __forceinline__ void gate_logits_token(const S* __restrict__ xr, const S* __restrict__ Wg,
-                                                  const float* __restrict__ bias, int H, int E, int wave, int lane,
-                                                  float* __restrict__ logits_row, float* s_logit) {
+                                                  const float* __restrict__ bias, int H, int E, int e_begin,
+                                                  int e_end, int wave, int lane, Store store) {
   const int nchunk = H >> 3;
   constexpr int U = sizeof(S) == 2 ? 4 : 2;
   constexpr int TE = 4;                                // experts per pass of a wave
-  for (int e0 = wave * TE; e0 < E; e0 += NWAVES * TE) {
+  for (int e0 = e_begin + wave * TE; e0 < e_end; e0 += NWAVES * TE) {
     float acc[TE];
 #pragma unroll
     for (int a = 0; a < TE; ++a) acc[a] = 0.f;
@@ -210,11 +210,7 @@ __device__ __forceinline__ void gate_logits_token(const S* __restrict__ xr, cons
     for (int a = 0; a < TE; ++a) {
       const float sum = wave_sum(acc[a]);
       const int e = e0 + a;
-      if (lane == 0 && e < E) {
-        const float z = sum + (bias ? bias[e] : 0.f);
-        logits_row[e] = z;
-        s_logit[e] = z;
-      }
+      if (lane == 0 && e < e_end) store(e, sum + (bias ? bias[e] : 0.f));
     }
   }
 }
