@@ -180,7 +180,9 @@ class Alg1Batch:
                 self._prefetch(l)
         for l, (ly, b) in enumerate(zip(dev.layers, self.bufs)):
             if self.caches is None:
-                x = mm.layer_step(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev, ly["table"], ly["shared"])
+                # resident experts: a batch of at most 64 slots is one launch per layer
+                step = mm.layer_decode_step if b.lws is not None else mm.layer_step
+                x = step(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev, ly["table"], ly["shared"])
             else:
                 if self.distance > 0 and l + self.distance < L:
                     self._prefetch(l + self.distance)

@@ -202,12 +202,8 @@ extern "C" int moe_route(const moe_config* cfg, const void* x, const void* Wg, c
   // decode sizes: plain-FMA GEMV spread over many waves; larger T: MFMA router GEMM
   constexpr int kGemvMaxT = 256;
   // decode batches: logits and selection of a token in one workgroup, one launch
-  static int fused_max_t = -1;
-  if (fused_max_t < 0) {
-    fused_max_t = 64;
-    if (const char* env = getenv("MOE_FUSED_ROUTE_MAX_T")) fused_max_t = atoi(env) >= 0 ? atoi(env) : 64;
-  }
-  if (!logits_given && cfg->T <= fused_max_t) {
+  constexpr int kOneLaunchMaxT = 64;
+  if (!logits_given && cfg->T <= kOneLaunchMaxT) {
     ProfScope ps(kProfRouteTopk, s);
     return launch_gate_route(*cfg, x, Wg, gate_bias, conf, logits, topk_idx, topk_w, important, k_t, s);
   }
@@ -327,12 +323,7 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
   hipStream_t s = static_cast<hipStream_t>(stream);
   // Regime: with many tokens per step the experts see enough rows for LDS-tiled MFMA GEMMs;
   // below that the weights are streamed once through the skinny kernel.
-  static int tiled_min_t = -1;
-  if (tiled_min_t < 0) {
-    tiled_min_t = 256;
-    if (const char* env = getenv("MOE_TILED_MIN_T")) tiled_min_t = atoi(env) > 0 ? atoi(env) : 1 << 30;
-  }
-  const bool tiled = cfg->dtype == MOE_BF16 && cfg->T >= tiled_min_t;
+  const bool tiled = cfg->dtype == MOE_BF16 && cfg->T >= kW8MaxT;
   {
     ProfScope ps(kProfFfnGateUp, s);
     rc = tiled ? launch_tiled(kGateUp, a, s) : launch_stream(kGateUp, cfg->dtype, a, s);

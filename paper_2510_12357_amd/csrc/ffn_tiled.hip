@@ -26,7 +26,7 @@
 //     persistent workgroups; the tile list is cut into 8 contiguous ranges, one per XCD, and
 //     the token tiles that share a weight panel are adjacent in the list, so a panel is fetched
 //     from HBM once and re-read from that XCD's L2.
-#include <stdlib.h>
+#include <atomic>
 
 #include "internal.h"
 #include "groups.h"
@@ -332,15 +332,16 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 template <int MODE, typename SH>
 int launch_tiled_shape(const StreamArgs& a, hipStream_t s) {
   constexpr size_t kLds = (size_t)kStages * SH::kStageBytes;
-  static int per_cu = 0;
+  static std::atomic<int> cached{0};
+  int per_cu = cached.load(std::memory_order_relaxed);
   if (per_cu == 0) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_kernel<MODE, SH>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
       return hip_fail(hipGetLastError(), "tiled_kernel: LDS size attribute");
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, tiled_kernel<MODE, SH>, SH::kThreads, kLds) != hipSuccess || n < 1) n = 1;
-    if (const char* env = getenv("MOE_TILED_WG_PER_CU")) { const int v = atoi(env); if (v > 0) n = v; }
     per_cu = n;
+    cached.store(n, std::memory_order_relaxed);
   }
   int grid = device_cu_count() * per_cu;
   grid = grid / 8 * 8;                                      // the XCD walk wants a multiple of 8

@@ -28,7 +28,7 @@
 //   * A long contraction (down projection of a wide shared expert) is cut into K chunks that
 //     become separate groups writing separate output slabs; the combine kernel adds the slabs
 //     in a fixed order.
-#include <stdlib.h>
+#include <atomic>
 
 #include "internal.h"
 #include "groups.h"
@@ -393,12 +393,13 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
   if (items <= 0) return MOE_OK;
   // persistent workgroups: exactly as many as are resident at once, so that the static striding
   // over the item list never leaves a second, partially filled round of workgroups
-  static int per_cu = 0;
+  static std::atomic<int> cached{0};
+  int per_cu = cached.load(std::memory_order_relaxed);
   if (per_cu == 0) {
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, stream_kernel<ET, MODE, NW>, kThreads, 0) != hipSuccess || n < 1) n = 2;
-    if (const char* env = getenv("MOE_STREAM_WG_PER_CU")) { const int v = atoi(env); if (v > 0) n = v; }
     per_cu = n;
+    cached.store(n, std::memory_order_relaxed);
   }
   long grid = (long)device_cu_count() * per_cu;
   if (grid > items) grid = items;
@@ -414,18 +415,11 @@ int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s
     if (mode == kRouter) return launch_typed<BF16, kRouter, 4>(a, s);
     return launch_stream_lds(mode, 1, a, s);
   }
-  if (dtype == MOE_BF16 && mode != kRouter) {
-    // bf16 expert GEMMs stream through LDS (stream_lds.hip); MOE_STREAM_LDS=0 selects the
-    // register-ring kernel of this file instead (read per call, so a test can flip it)
-    const char* env = getenv("MOE_STREAM_LDS");
-    if (!env || atoi(env) != 0) return launch_stream_lds(mode, 2, a, s);
-  }
   if (dtype == MOE_BF16) {
-    switch (mode) {
-      case kRouter: return launch_typed<BF16, kRouter, 4>(a, s);
-      case kGateUp: return launch_typed<BF16, kGateUp, 4>(a, s);
-      case kDown: return launch_typed<BF16, kDown, 4>(a, s);
-    }
+    // the bf16 expert GEMMs stream through LDS (stream_lds.hip); this file's kernel serves the
+    // router GEMM and the fp32 layers
+    if (mode != kRouter) return launch_stream_lds(mode, 2, a, s);
+    return launch_typed<BF16, kRouter, 4>(a, s);
   } else {
     switch (mode) {
       case kRouter: return launch_typed<FP32, kRouter, 4>(a, s);

@@ -40,9 +40,7 @@
 //     inside a chunk is permuted accordingly, and the token rows are loaded with the same
 //     permutation.  The computers widen the codes to bf16 (exact: 3 mantissa bits) in front of
 //     the MFMAs, and the row scale multiplies the fp32 sum in the epilogue.
-#include <stdio.h>
-#include <stdlib.h>
-
+#include <atomic>
 #include <type_traits>
 
 #include "internal.h"
@@ -465,12 +463,13 @@ int launch_lds_typed(const StreamArgs& a, hipStream_t s) {
   const long items = item_upper_bound((StreamMode)MODE, a, kTok);
   if (items <= 0) return MOE_OK;
   // persistent workgroups: exactly as many as are resident at once
-  static int per_cu = 0;
+  static std::atomic<int> cached{0};                      // the same on every device this library runs on (gfx950)
+  int per_cu = cached.load(std::memory_order_relaxed);
   if (per_cu == 0) {
     int n = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, stream_lds_kernel<MODE, WB>, kThreadsL, 0) != hipSuccess || n < 1) n = 1;
-    if (const char* env = getenv("MOE_STREAM_WG_PER_CU")) { const int v = atoi(env); if (v > 0) n = v; }
     per_cu = n;
+    cached.store(n, std::memory_order_relaxed);
   }
   long grid = (long)device_cu_count() * per_cu;
   if (grid > items) grid = items;

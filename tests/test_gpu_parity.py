@@ -186,13 +186,26 @@ def test_many_token_blocks_in_the_streaming_kernels():
     check_layer(cfg_small(T=97, E=6, k_big=4, k_little=2, shared_I=(72,)), seed=6)
 
 
-def test_register_ring_kernels_in_bf16(monkeypatch):
-    # MOE_STREAM_LDS=0 selects the register-ring streaming kernels for bf16 as well (they are
-    # what fp32 always uses); the library reads the variable on every call
-    monkeypatch.setenv("MOE_STREAM_LDS", "0")
-    check_layer(cfg_small(dtype="bf16", fallback_ratio=0.3, gate_bias_std=0.5), seed=1)
-    check_layer(cfg_small(T=200, E=4, k_big=3, k_little=1, shared_I=(40, 24)), seed=5)
-    check_layer(wl.CONFIGS["fine60_decode"].with_(T=8), seed=0)
+def test_dispatch_ignores_an_expert_named_again_by_the_same_token():
+    """moe_route never names an expert twice for one token; for a caller-made selection that does,
+    the documented rule is that the later rank is ignored (no pair, inv_pos = -1)."""
+    for T, E, K in ((40, 6, 4), (700, 9, 5)):
+        g = np.random.default_rng(T)
+        idx = g.integers(0, E, size=(T, K)).astype(np.int32)          # repeats are frequent with E this small
+        k_t = g.integers(1, K + 1, size=T).astype(np.int32)
+        dedup = idx.copy()
+        for t in range(T):
+            for j in range(K):
+                if j >= k_t[t] or idx[t, j] in idx[t, :j]:
+                    dedup[t, j] = -1
+        cfg = wl.LayerConfig("dup", T=T, H=8, E=E, I=8, k_big=K, k_little=1)
+        b = mm.StepBuffers(cfg)
+        mm.moe_dispatch(b.c, torch.from_numpy(idx).cuda(), torch.from_numpy(k_t).cuda(), b.expert_offsets,
+                        b.sorted_token, b.sorted_rank, b.inv_pos, b.dws, b.dws_bytes)
+        torch.cuda.synchronize()
+        off, st, sr, inv = oracle.dispatch(dedup, k_t, E)
+        assert np.array_equal(i32(b.expert_offsets), off) and np.array_equal(i32(b.sorted_token), st)
+        assert np.array_equal(i32(b.sorted_rank), sr) and np.array_equal(i32(b.inv_pos), inv)
 
 
 def test_all_big_and_all_little_and_null_conf():
