@@ -39,7 +39,8 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_gate_logits", "oracle_token_confidence", "oracle_route",
                      "oracle_dispatch", "oracle_dispatch_from", "oracle_combine_add", "oracle_swiglu_rows", "oracle_expert_ffn",
-                     "oracle_combine", "oracle_num_threads", "oracle_swiglu_rows_w8", "oracle_e4m3_decode"):
+                     "oracle_combine", "oracle_num_threads", "oracle_set_num_threads", "oracle_swiglu_rows_w8",
+                     "oracle_e4m3_decode"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -68,6 +69,11 @@ def _check(rc: int, what: str) -> None:
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads of the loops over independent rows from now on (timing only; results do not change)."""
+    _load().oracle_set_num_threads(int(n))
 
 
 def gate_logits(x: np.ndarray, Wg: np.ndarray, bias: Optional[np.ndarray] = None) -> np.ndarray:

@@ -354,6 +354,17 @@ int oracle_combine_add(const double* y, const float* w, const int32_t* inv_pos, 
   return 0;
 }
 
+// Threads the OpenMP loops over independent rows use from now on (timing of the oracle on one
+// core and on all of them; the arithmetic does not depend on it).  n <= 0: leave as is.
+int oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+  return 0;
+}
+
 int oracle_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP
