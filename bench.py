@@ -68,6 +68,10 @@ def workload_config(name: str, ratio: float):
         return wl.CONFIGS["coarse8"].with_(fallback_ratio=ratio)
     if name.startswith("coarse8_decode_b"):
         return wl.CONFIGS["coarse8"].with_(T=int(name.split("_b")[1]), fallback_ratio=ratio)
+    if name == "tiny_fp32":
+        return wl.CONFIGS["tiny_fp32"].with_(fallback_ratio=ratio)
+    if name.startswith("shared2_offload_b"):          # the offload layer's shape with resident experts
+        return wl.CONFIGS["shared2_offload"].with_(T=int(name.split("_b")[1]), fallback_ratio=ratio)
     raise SystemExit(f"unknown workload {name}")
 
 
@@ -292,6 +296,135 @@ def time_offload(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16, pre
                 experts_needed_per_step=(hits + misses) / steps, demand_hit_rate=hits / max(1, hits + misses),
                 waves_per_step=waves / steps, h2d_gb_per_s=nbytes / dt_s / 1e9,
                 h2d_mb_per_step=nbytes / steps / 1e6, prefetch=prefetch)
+
+
+def time_offload_eq1(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16, sigma: float = 0.3):
+    """The paper's claim where it applies: the layer with its routed experts in pinned host memory
+    behind n_slots HBM slots, every step a new token batch.  Measured per step:
+      T        every token with k_big experts, experts loaded on demand (the baseline of Eq. 1)
+      T_l      every token with k_little experts, on demand
+      two-pass the method at layer level: little pass on every token, then the fallback pass that adds
+               the ranks k_little .. k_big-1 for the tokens whose confidence is not above gamma; the
+               fallback pass's experts on demand, or prefetched right after the little pass from noisy
+               router states (the layer's logits + N(0, sigma): the prediction the paper reports as
+               more than 80 % accurate)
+    and from those the measured speedup T / (little + fallback) and Eq. 1's T / (T_l + r T_b) with
+    T_b = T."""
+    from paper_2510_12357_amd import workloads as wl
+    DEMAND, PREFETCH = 0, 1
+    dt = torch.bfloat16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(17)
+
+    def randn(shape, std):
+        return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
+
+    first = random_blob(torch, g, cfg, cfg.I)
+    blob = first.numel()
+    host = torch.empty((cfg.E, blob), dtype=first.dtype).pin_memory()
+    host[0].copy_(first)
+    for e in range(1, cfg.E):
+        host[e].copy_(random_blob(torch, g, cfg, cfg.I))
+    Wg = randn((cfg.E, cfg.H), cfg.gate_std)
+    shared = [random_blob(torch, g, cfg, Is) for Is in cfg.shared_I]
+    nb = 16
+    xs = [randn((cfg.T, cfg.H), 1.0) for _ in range(nb)]
+    never = torch.full((cfg.T,), float("inf"), dtype=torch.float32, device="cuda")
+    slots = torch.zeros((n_slots, blob), dtype=host.dtype, device="cuda")
+    h = mm.moe_cache_create(cfg.E, blob * host.element_size(), n_slots, host, slots)
+    b = mm.StepBuffers(cfg)
+    c_routed_only = mm.make_config(cfg.with_(shared_I=()))      # the fallback pass runs no shared expert
+    K, kl = cfg.k_big, cfg.k_little
+    # the router logits of every batch (untimed): the source of the stale router states
+    logits = []
+    for i in range(nb):
+        mm.moe_route(b.c, xs[i], Wg, None, None, b.logits, False, b.topk_idx, b.topk_w, b.important, b.k_t)
+        torch.cuda.synchronize()
+        logits.append(b.logits.cpu().numpy().copy())
+
+    def little_pass(i):
+        return mm.layer_step_cached(b, xs[i], Wg, None, never, h, shared)[1]
+
+    def fallback_pass(i, conf):
+        mm.moe_route(b.c, xs[i], None, None, conf, b.logits, True, b.topk_idx, b.topk_w, b.important, b.k_t)
+        mm.moe_dispatch_from(b.c, b.topk_idx, b.k_t, kl, b.expert_offsets, b.sorted_token, b.sorted_rank, b.inv_pos,
+                             b.dws, b.dws_bytes)
+        st, _ = mm.moe_expert_ffn_cached(c_routed_only, h, xs[i], b.expert_offsets, b.sorted_token, (), b.y, None,
+                                         b.fws, b.fws_bytes)
+        mm.moe_combine_add(b.c, b.y, b.topk_w, b.inv_pos, b.k_t, kl, b.out)
+        return st
+
+    def timed(step_fn):
+        tot = dict(hits=0, misses=0, bytes=0, pf_copies=0, pf_dropped=0)
+        t0 = 0.0
+        for it in range(warmup + steps):
+            if it == warmup:
+                torch.cuda.synchronize()
+                for k in tot:
+                    tot[k] = 0
+                t0 = time.perf_counter()
+            step_fn(it % nb, tot)
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        need = tot["hits"] + tot["misses"]
+        return dict(us_per_step=dt_s * 1e6 / steps, demand_hit_rate=tot["hits"] / max(1, need),
+                    experts_needed_per_step=need / steps, h2d_mb_per_step=tot["bytes"] / steps / 1e6,
+                    h2d_gb_per_s=tot["bytes"] / dt_s / 1e9, prefetch_copies_per_step=tot["pf_copies"] / steps,
+                    prefetch_dropped_per_step=tot["pf_dropped"] / steps)
+
+    def add(tot, st):
+        tot["hits"] += st.hits; tot["misses"] += st.misses; tot["bytes"] += st.bytes_h2d
+
+    def single(conf):
+        def fn(i, tot):
+            add(tot, mm.layer_step_cached(b, xs[i], Wg, None, conf, h, shared)[1])
+        return fn
+
+    out = dict(tokens=cfg.T, slots=n_slots, blob_mb=blob * host.element_size() / 1e6, router_state_noise=sigma)
+    try:
+        out["all_big"] = timed(single(None))
+        out["all_little"] = timed(single(never))
+        T_, Tl_ = out["all_big"]["us_per_step"], out["all_little"]["us_per_step"]
+        for r in (0.11, 0.21):
+            confs_h = [wl.make_confidence(300 + i, cfg.T, cfg.gamma, r) for i in range(nb)]
+            confs = [torch.from_numpy(c).cuda() for c in confs_h]
+            # predicted experts of the fallback pass per batch: top-k_big of the noisy logits of the
+            # rejected tokens, most likely rank first, each expert once
+            pred, overlap = [], []
+            for i in range(nb):
+                noisy = logits[i] + wl.make_router_noise(900 + i, cfg.T, cfg.E, sigma)
+                seen = []
+                for j in range(K):
+                    for t in np.nonzero(confs_h[i] <= cfg.gamma)[0]:
+                        e = int(np.argsort(-noisy[t], kind="stable")[j])
+                        if e not in seen:
+                            seen.append(e)
+                        true = set(np.argsort(-logits[i][t], kind="stable")[:K].tolist())
+                        if j == 0:
+                            overlap.append(len(true & set(np.argsort(-noisy[t], kind="stable")[:K].tolist())) / K)
+                pred.append(seen)
+
+            def two_pass(prefetch):
+                def fn(i, tot):
+                    add(tot, little_pass(i))
+                    if prefetch and pred[i]:
+                        _, ps = mm.expert_cache_fetch(h, pred[i], PREFETCH)
+                        tot["bytes"] += ps.bytes_h2d; tot["pf_copies"] += ps.misses; tot["pf_dropped"] += ps.dropped
+                    add(tot, fallback_pass(i, confs[i]))
+                return fn
+            d, pf = timed(two_pass(False)), timed(two_pass(True))
+            flagged = float(np.mean([(c <= cfg.gamma).mean() for c in confs_h]))
+            out[f"r_{r}"] = dict(realised_ratio=flagged, two_pass_demand=d, two_pass_prefetch=pf,
+                                 prediction_overlap=float(np.mean(overlap)) if overlap else None,
+                                 speedup_measured_demand=T_ / d["us_per_step"],
+                                 speedup_measured_prefetch=T_ / pf["us_per_step"],
+                                 speedup_eq1=eq1(T_, Tl_, T_, r))
+    finally:
+        mm.moe_cache_sync(h)
+        mm.moe_cache_destroy(h)
+    del host, slots
+    torch.cuda.empty_cache()
+    return out
 
 
 def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 256, ratio: float = 0.2):
@@ -537,6 +670,50 @@ def cpu_baseline(torch, cfg, layers: DeviceLayers, budget_s: float = 12.0):
                 sample=f"{done_tokens} tokens of layer 0 ({n_tok} per call, {t_used:.1f} s, fp64, OpenMP)")
 
 
+def cpu_rows(torch, budget_s: float = 2.5):
+    """The oracle on the host cores for every configuration: one thread and all of them, each on a
+    bounded sample (the tokens it gets through in about budget_s, whole calls)."""
+    import oracle
+
+    def host(t):
+        t = t.detach().cpu()
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).numpy().view(np.uint16)
+        return t.numpy()
+
+    rows = {}
+    all_cores = oracle.num_threads()
+    for name, n_tok in (("tiny_fp32", 64), ("fine60_decode_b1", 1), ("fine60_decode_b64", 16), ("fine64_prefill", 32),
+                        ("shared2_offload_b16", 16), ("coarse8_decode_b1", 1), ("coarse8_prefill", 8)):
+        cfg = workload_config(name, 0.2)
+        layers = DeviceLayers(cfg, 1)
+        x, Wg = host(layers.x[0]), host(layers.Wg[0])
+        bias = None if layers.bias[0] is None else host(layers.bias[0])
+        ew = [host(layers.experts[0][e]) for e in range(cfg.E)]
+        sw = [host(t) for t in layers.shared[0]]
+        conf = host(layers.conf[0])
+        del layers
+        torch.cuda.empty_cache()
+        n_tok = min(n_tok, cfg.T)
+        row = {}
+        for label, threads in (("single_thread", 1), ("all_cores", all_cores)):
+            oracle.set_num_threads(threads)
+            done, used = 0, 0.0
+            while True:
+                t0 = time.perf_counter()
+                oracle.moe_layer(x[:n_tok], Wg, bias, ew, cfg.I, sw, cfg.shared_I, conf[:n_tok], cfg.gamma, cfg.k_big,
+                                 cfg.k_little, cfg.renorm)
+                used += time.perf_counter() - t0
+                done += n_tok
+                if used >= budget_s:
+                    break
+            row[label] = dict(tokens_per_s=done / used, threads=threads,
+                              sample=f"{done} tokens ({n_tok} per call, {used:.1f} s)")
+        rows[name] = row
+        oracle.set_num_threads(all_cores)
+    return dict(kind="oracle (fp64, g++ -O2, OpenMP over independent rows)", rows=rows)
+
+
 def stored_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of
     this workload (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size); None if absent."""
@@ -545,6 +722,18 @@ def stored_traffic(workload: str):
     try:
         m = re.search(r"HBM traffic per launch = ([0-9.]+) MB", open(p).read())
         return float(m.group(1)) * 1e6 if m else None
+    except OSError:
+        return None
+
+
+def traffic_source(workload: str):
+    """Where `traffic` comes from: the committed counter summary and the source revision it names."""
+    import re
+    p = os.path.join(ROOT, "profiles", f"{workload}_hbm_traffic.txt")
+    try:
+        m = re.search(r"source revision: (\S+)", open(p).read())
+        return dict(file=f"profiles/{workload}_hbm_traffic.txt", revision=m.group(1) if m else None,
+                    note="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, not measured by this run")
     except OSError:
         return None
 
@@ -637,6 +826,7 @@ def main():
                         traffic=stored_traffic(args.workload))
     roofline["kernel"] = ("decode_step_kernel (the whole step)" if fused else
                           ("tiled_kernel<kGateUp>" if cfg.T >= 256 else "stream_lds_kernel<kGateUp>") + " (ffn_gate_up)")
+    roofline["traffic_source"] = traffic_source(args.workload)
     roofline["avg_us"] = gu["avg_us"]
     roofline["algorithmic_bytes"] = work["gate_up_bytes"]
 
@@ -655,7 +845,8 @@ def main():
         others = {}
         k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 2)
         names = [n for n in ("fine60_decode_b1", "fine60_decode_b8", "fine60_decode_b32", "fine60_decode_b64",
-                             "fine64_prefill", "fine60_decode_b1_w8", "fine60_decode_b64_w8") if n != args.workload]
+                             "fine64_prefill", "coarse8_prefill", "coarse8_decode_b1", "tiny_fp32",
+                             "fine60_decode_b1_w8", "fine60_decode_b64_w8") if n != args.workload]
         for name in names:
             c2 = workload_config(name, args.ratio)
             r2 = time_workload(mm, torch, c2, k2, w2)
@@ -693,10 +884,17 @@ def main():
         others["shared2_offload_b16"] = dict(demand_only=time_offload(mm, torch, oc, 24, 8),
                                              demand_only_w8=time_offload(mm, torch, oc.with_(dtype="bf16w8"), 24, 8))
         torch.cuda.empty_cache()
+        # Eq. 1 where the paper's claim applies: experts behind the host link, 16 HBM slots; the layer's
+        # own batch of 16 and the single-stream case of the paper's measurements
+        others["offload_eq1"] = dict(b16=time_offload_eq1(mm, torch, oc, 16, 4),
+                                     b1=time_offload_eq1(mm, torch, oc.with_(T=1), 48, 8))
+        torch.cuda.empty_cache()
         # Alg. 1 end to end on a toy language model made of this layer (realised fallback ratio)
         others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 10,
                                               ratio=args.ratio)
         extra["other_workloads"] = others
+        if not args.no_cpu:
+            extra["cpu_oracle_rows"] = cpu_rows(torch)
 
     line = dict(metric="MoE-layer tokens/s (decode b=1..64, prefill 2k) + % HBM/MFMA roofline",
                 value=main_res["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
