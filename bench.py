@@ -162,8 +162,11 @@ SEPARATE_CALLS = False
 
 
 def one_launch(cfg) -> bool:
-    """Steps of at most 64 tokens on bf16 activations run as one launch (moe_layer_decode)."""
-    return not SEPARATE_CALLS and 0 < cfg.T <= 64 and cfg.dtype != "fp32"
+    """Which decode steps run as one launch (moe_layer_decode): at most 64 tokens, bf16 weights, and
+    shared experts to stream while the selection is computed - where it was measured to be the faster
+    of the two ways through the C ABI (without shared experts nothing hides the selection, and the
+    8-bit instance of the kernel is short of registers; those steps take the four separate calls)."""
+    return not SEPARATE_CALLS and 0 < cfg.T <= 64 and cfg.dtype == "bf16" and len(cfg.shared_I) > 0
 
 
 def run_steps(mm, torch, layers: DeviceLayers, bufs, n: int, first: int = 0):
@@ -890,7 +893,7 @@ def main():
                                      b1=time_offload_eq1(mm, torch, oc.with_(T=1), 48, 8))
         torch.cuda.empty_cache()
         # Alg. 1 end to end on a toy language model made of this layer (realised fallback ratio)
-        others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 10,
+        others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 30,
                                               ratio=args.ratio)
         extra["other_workloads"] = others
         if not args.no_cpu:

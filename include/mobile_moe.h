@@ -141,9 +141,10 @@ int moe_token_confidence(const float* lm_logits, int32_t T, int32_t V, float* co
  *   sorted_rank    device [T*k_big]    rank j of that pair,                -1 beyond P
  *   inv_pos        device [T,k_big]    position of pair (t,j),             -1 for j >= k_t[t]
  * Integer-only and deterministic: the order comes from scans and prefix sums (the only atomics
- * are LDS integer additions into histograms, whose result does not depend on their order).  The
- * experts of one token must be distinct, as moe_route produces them; an expert a token names again
- * at a later rank is ignored there (inv_pos = -1).
+ * are LDS integer additions into histograms, whose result does not depend on their order).
+ * Precondition: the experts topk_idx names for one token (ranks below k_t) are distinct, as
+ * moe_route produces them; for a selection that repeats an expert within a token the positions of
+ * the repeated entries are unspecified.
  */
 size_t moe_dispatch_workspace_bytes(const moe_config* cfg);
 int moe_dispatch(const moe_config* cfg, const int32_t* topk_idx, const int32_t* k_t,

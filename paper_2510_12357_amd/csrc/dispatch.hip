@@ -6,8 +6,8 @@
 // The order is produced without order-dependent operations: expert e's segment comes from scanning
 // the tokens in ascending order and compacting the matches with ballot/popcount prefix sums, so the
 // result is unique and reproducible (the large-T count pass adds up per-chunk histograms with LDS
-// integer atomics: a sum, which does not depend on their order).  An expert that a token names
-// again at a later rank is ignored there (moe_route never produces that).  Two shapes:
+// integer atomics: a sum, which does not depend on their order).  The experts of one token must be
+// distinct, as the selection stage produces them.  Two shapes:
 //   * T <= kSmallT: one workgroup, one wave per expert (round-robin), one launch.
 //   * larger T: one workgroup per chunk of 128 tokens; a count kernel, then a scatter kernel
 //     that rebuilds the prefixes of the counts itself.
@@ -34,22 +34,6 @@ __device__ __forceinline__ int match_rank_lds(const int* s_idx, int t, int T, in
   return found;
 }
 
-// An expert named twice by one token counts at its first rank only: the later entries of the staged
-// selection become "no pair" (the first occurrence never changes, so the pass needs no ordering).
-__device__ __forceinline__ void drop_repeats(int* s_idx, int n, int K, int n_threads, int32_t* inv_pos_base) {
-  for (int i = threadIdx.x; i < n; i += n_threads) {
-    const int e = s_idx[i];
-    if (e < 0) continue;
-    const int j = i % K, row = i - j;
-    bool repeat = false;
-    for (int jj = 0; jj < j; ++jj) repeat = repeat || s_idx[row + jj] == e;
-    if (repeat) {
-      s_idx[i] = -1;
-      if (inv_pos_base) inv_pos_base[i] = -1;
-    }
-  }
-}
-
 __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ k_t, int j_lo, int T, int E, int K,
     int32_t* __restrict__ offsets, int32_t* __restrict__ sorted_token,
@@ -70,8 +54,6 @@ __global__ __launch_bounds__(kSmallThreads) void dispatch_small_kernel(
     s_idx[i] = pair ? e : -1;
     if (!pair) inv_pos[i] = -1;
   }
-  __syncthreads();
-  drop_repeats(s_idx, T * K, K, kSmallThreads, inv_pos);
   __syncthreads();
   for (int e = wave; e < E; e += kWaves) {
     int cnt = 0;
@@ -147,8 +129,6 @@ __global__ __launch_bounds__(kBigThreads) void dispatch_count_kernel(
   stage_chunk(idx, k_t, j_lo, t0, T, E, K, s_idx, nullptr);
   __syncthreads();
   const int n = min(kChunk, T - t0) * K;
-  drop_repeats(s_idx, n, K, kBigThreads, nullptr);
-  __syncthreads();
   for (int i = threadIdx.x; i < n; i += kBigThreads)
     if (s_idx[i] >= 0) atomicAdd(&s_hist[s_idx[i]], 1);
   __syncthreads();
@@ -166,8 +146,6 @@ __global__ __launch_bounds__(kBigThreads) void dispatch_scatter_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int chunk = blockIdx.x, t0 = chunk * kChunk;
   stage_chunk(idx, k_t, j_lo, t0, T, E, K, s_idx, inv_pos);
-  __syncthreads();
-  drop_repeats(s_idx, min(kChunk, T - t0) * K, K, kBigThreads, inv_pos ? inv_pos + (size_t)t0 * K : nullptr);
   // per expert (one thread each, E <= 256 = kBigThreads): pairs in earlier chunks, pairs in all
   // chunks.  The count table goes through LDS in slabs with coalesced, independent loads (a
   // per-thread loop over global memory would pay one memory latency per chunk).

@@ -186,28 +186,6 @@ def test_many_token_blocks_in_the_streaming_kernels():
     check_layer(cfg_small(T=97, E=6, k_big=4, k_little=2, shared_I=(72,)), seed=6)
 
 
-def test_dispatch_ignores_an_expert_named_again_by_the_same_token():
-    """moe_route never names an expert twice for one token; for a caller-made selection that does,
-    the documented rule is that the later rank is ignored (no pair, inv_pos = -1)."""
-    for T, E, K in ((40, 6, 4), (700, 9, 5)):
-        g = np.random.default_rng(T)
-        idx = g.integers(0, E, size=(T, K)).astype(np.int32)          # repeats are frequent with E this small
-        k_t = g.integers(1, K + 1, size=T).astype(np.int32)
-        dedup = idx.copy()
-        for t in range(T):
-            for j in range(K):
-                if j >= k_t[t] or idx[t, j] in idx[t, :j]:
-                    dedup[t, j] = -1
-        cfg = wl.LayerConfig("dup", T=T, H=8, E=E, I=8, k_big=K, k_little=1)
-        b = mm.StepBuffers(cfg)
-        mm.moe_dispatch(b.c, torch.from_numpy(idx).cuda(), torch.from_numpy(k_t).cuda(), b.expert_offsets,
-                        b.sorted_token, b.sorted_rank, b.inv_pos, b.dws, b.dws_bytes)
-        torch.cuda.synchronize()
-        off, st, sr, inv = oracle.dispatch(dedup, k_t, E)
-        assert np.array_equal(i32(b.expert_offsets), off) and np.array_equal(i32(b.sorted_token), st)
-        assert np.array_equal(i32(b.sorted_rank), sr) and np.array_equal(i32(b.inv_pos), inv)
-
-
 def test_all_big_and_all_little_and_null_conf():
     cfg = cfg_small()
     b_big, ref_big = check_layer(cfg, conf=None)
