@@ -27,6 +27,7 @@
 //     the token tiles that share a weight panel are adjacent in the list, so a panel is fetched
 //     from HBM once and re-read from that XCD's L2.
 #include <atomic>
+#include <type_traits>
 
 #include "internal.h"
 #include "groups.h"
@@ -70,6 +71,10 @@ template <int OFF0, int OFF1>
 __device__ __forceinline__ void frag_read2(bf16x8& f0, bf16x8& f1, unsigned addr) {
   asm volatile("ds_read_b128 %0, %2 offset:%3\n\tds_read_b128 %1, %2 offset:%4"
                : "=&v"(f0), "=&v"(f1) : "v"(addr), "n"(OFF0), "n"(OFF1) : "memory");
+}
+template <int OFF0>
+__device__ __forceinline__ void frag_read1(bf16x8& f0, unsigned addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(f0) : "v"(addr), "n"(OFF0) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void frag_wait(bf16x8 (&f)[N]) {
@@ -256,48 +261,72 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    auto read_frags = [&](int st, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
-      const unsigned col = (((unsigned)(kk * 2 + (lane >> 5))) ^ fkey) * 16u + (unsigned)(st * SH::kStageBytes);
-      frag_read2<0, kJ>(fa[0], fa[1], a_rd + col);
-      if constexpr (TM == 4) frag_read2<2 * kJ, 3 * kJ>(fa[2], fa[3], a_rd + col);
-      if constexpr (TN == 2) {
-        frag_read2<0, kUp>(fb[0], fb[1], b_rd + col);
-      } else {
-        frag_read2<0, kJ>(fb[0], fb[1], b_rd + col);
-        frag_read2<kUp, kUp + kJ>(fb[2], fb[3], b_rd + col);
-      }
-    };
+    // 32-token blocks of this wave that hold rows of the group: a group's last token tile is
+    // mostly empty when the group is small against BM, and a block without rows is neither read
+    // from LDS nor multiplied (its accumulators stay zero and are not stored).  A wave without any
+    // rows only keeps the barriers.
+    const int rows_w = G.m - m0 - wm * TM * 32;
+    const int n_blk = rows_w <= 0 ? 0 : (rows_w >= TM * 32 ? TM : (rows_w + 31) >> 5);
 
     // Barrier kt says "chunk kt has landed" (the loaders waited for it) and "chunk kt-1 has been
     // read" (it sits in front of the last k-step's MFMAs of chunk kt-1, whose fragments were read
     // one k-step earlier).  The fragments of the first k-step of chunk kt are read right behind
     // it, under those MFMAs.
     constexpr int kParts = BK / 16;
-    bf16x8 fa[2][TM], fb[2][TN];
-    lds_barrier();                                         // barrier 0
-    read_frags(0, 0, fa[0], fb[0]);
-    frag_wait(fa[0]); frag_wait(fb[0]);
-    int st = 0;                                            // stage of chunk kt
-    for (int kt = 0; kt < nk; ++kt) {
-      const int st_nx = st + 1 == kStages ? 0 : st + 1;    // stage of chunk kt+1
-#pragma unroll
-      for (int kk = 0; kk < kParts; ++kk) {
-        const int cur = kk & 1, nxt = (kk + 1) & 1;        // kParts is even: set 0 again holds k-step 0 of the next chunk
-        if (kk + 1 < kParts) {
-          read_frags(st, kk + 1, fa[nxt], fb[nxt]);
+    auto main_loop = [&](auto nb_tag) {
+      constexpr int NB = decltype(nb_tag)::value;          // token blocks in use: 1 .. TM
+      auto read_frags = [&](int st, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+        const unsigned col = (((unsigned)(kk * 2 + (lane >> 5))) ^ fkey) * 16u + (unsigned)(st * SH::kStageBytes);
+        if constexpr (NB == 1) frag_read1<0>(fa[0], a_rd + col);
+        else frag_read2<0, kJ>(fa[0], fa[1], a_rd + col);
+        if constexpr (NB == 3) frag_read1<2 * kJ>(fa[2], a_rd + col);
+        if constexpr (NB == 4) frag_read2<2 * kJ, 3 * kJ>(fa[2], fa[3], a_rd + col);
+        if constexpr (TN == 2) {
+          frag_read2<0, kUp>(fb[0], fb[1], b_rd + col);
         } else {
-          lds_barrier();                                   // barrier kt+1
-          read_frags(st_nx, 0, fa[nxt], fb[nxt]);          // stale data behind the last chunk; never used
+          frag_read2<0, kJ>(fb[0], fb[1], b_rd + col);
+          frag_read2<kUp, kUp + kJ>(fb[2], fb[3], b_rd + col);
         }
+      };
+      bf16x8 fa[2][TM] = {}, fb[2][TN];
+      lds_barrier();                                       // barrier 0
+      read_frags(0, 0, fa[0], fb[0]);
+      frag_wait(fa[0]); frag_wait(fb[0]);
+      int st = 0;                                          // stage of chunk kt
+      for (int kt = 0; kt < nk; ++kt) {
+        const int st_nx = st + 1 == kStages ? 0 : st + 1;  // stage of chunk kt+1
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int kk = 0; kk < kParts; ++kk) {
+          const int cur = kk & 1, nxt = (kk + 1) & 1;      // kParts is even: set 0 again holds k-step 0 of the next chunk
+          if (kk + 1 < kParts) {
+            read_frags(st, kk + 1, fa[nxt], fb[nxt]);
+          } else {
+            lds_barrier();                                 // barrier kt+1
+            read_frags(st_nx, 0, fa[nxt], fb[nxt]);        // stale data behind the last chunk; never used
+          }
 #pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
-        frag_wait(fa[nxt]); frag_wait(fb[nxt]);
-        __builtin_amdgcn_sched_barrier(0);                 // keep the steps apart; free order inside a step
+          for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+          frag_wait(fa[nxt]); frag_wait(fb[nxt]);
+          __builtin_amdgcn_sched_barrier(0);               // keep the steps apart; free order inside a step
+        }
+        st = st_nx;
       }
-      st = st_nx;
+    };
+    if (n_blk == TM) {
+      main_loop(std::integral_constant<int, TM>{});
+    } else if (n_blk == 0) {
+      for (int kt = 0; kt <= nk; ++kt) lds_barrier();      // barriers 0 .. nk, as the other waves pass them
+    } else {
+      if constexpr (TM == 2) {
+        main_loop(std::integral_constant<int, 1>{});
+      } else {
+        if (n_blk == 1) main_loop(std::integral_constant<int, 1>{});
+        else if (n_blk == 2) main_loop(std::integral_constant<int, 2>{});
+        else main_loop(std::integral_constant<int, 3>{});
+      }
     }
 
     // ---- epilogue: accumulator v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 ----

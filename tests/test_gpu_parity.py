@@ -273,24 +273,58 @@ def test_deterministic_across_runs():
 
 
 # ------------------------------------------------------------------ full-size prefill, sampled tokens
+def sampled_tokens(off, st, n_random, seed, T):
+    """Tokens to check one by one: for every expert the first and the last row of its segment and
+    the rows on both sides of each 128-row tile boundary inside it (where the tiled kernels switch
+    tiles and stop computing), plus n_random tokens drawn without replacement."""
+    pick = set(int(t) for t in np.random.default_rng(seed).choice(T, size=min(n_random, T), replace=False))
+    for e in range(len(off) - 1):
+        lo, hi = int(off[e]), int(off[e + 1])
+        rows = {lo, hi - 1}
+        for edge in range(lo + 128, hi, 128):
+            rows.update((edge - 1, edge))
+        for m in (31, 32, 63, 64):                        # the 32-row blocks of the last tile
+            rows.add(lo + (hi - lo - 1) // 128 * 128 + m)
+        pick.update(int(st[p]) for p in rows if lo <= p < hi)
+    return np.array(sorted(pick), np.int64)
+
+
+def check_sampled_prefill(cfg, layer, b, logits, n_random, seed):
+    """Index outputs in full and bit for bit; y rows and layer outputs on the sampled tokens."""
+    idx, w, imp, kt = oracle.route(logits, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, cfg.renorm)
+    off, st, sr, inv = oracle.dispatch(idx, kt, cfg.E)
+    assert np.array_equal(i32(b.topk_idx), idx) and np.array_equal(i32(b.k_t), kt)
+    assert np.array_equal(b.important.cpu().numpy(), imp)
+    assert np.array_equal(i32(b.expert_offsets), off) and np.array_equal(i32(b.sorted_token), st)
+    assert np.array_equal(i32(b.sorted_rank), sr) and np.array_equal(i32(b.inv_pos), inv)
+    tokens = sampled_tokens(off, st, n_random, seed, cfg.T)
+    ref = run_oracle_layer(layer, logits=logits, tokens=tokens)
+    e = rel_err(out_to_f64(b.out)[tokens], ref["out"])
+    assert e <= TOL_OUT, e
+    # expert outputs y (Eq. of Sec. II-A before the weighted sum), row by row: the row of token
+    # tokens[i] at rank j sits at inv[tokens[i], j] on the device and at the sub-layer's own
+    # inv_pos in the oracle's run over the sampled tokens
+    y_gpu = b.y.float().cpu().numpy().astype(np.float64)
+    got, want = [], []
+    for i, t in enumerate(tokens):
+        for j in range(int(kt[t])):
+            got.append(y_gpu[inv[t, j]])
+            want.append(ref["y"][ref["inv_pos"][i, j]])
+    e_y = rel_err(np.stack(got), np.stack(want))
+    assert e_y <= TOL_OUT, e_y
+    return off, tokens
+
+
 def test_fine64_prefill_full_size_sampled():
     cfg = wl.CONFIGS["fine64_prefill"]
     layer = wl.make_layer(cfg, seed=0)
     dl = DeviceLayer(layer)
     logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
     b = run_gpu_layer(dl, logits=logits)
-    idx, w, imp, kt = oracle.route(logits, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, cfg.renorm)
-    off, st, sr, inv = oracle.dispatch(idx, kt, cfg.E)
-    assert np.array_equal(i32(b.topk_idx), idx) and np.array_equal(i32(b.k_t), kt)
-    assert np.array_equal(i32(b.expert_offsets), off) and np.array_equal(i32(b.sorted_token), st)
-    assert np.array_equal(i32(b.inv_pos), inv)
+    off, tokens = check_sampled_prefill(cfg, layer, b, logits, n_random=160, seed=0)
     counts = np.diff(off)
     assert counts.max() > 3 * max(1, counts.min())           # the bias skews the loads
-    tokens = np.random.default_rng(0).choice(cfg.T, size=48, replace=False)
-    tokens.sort()
-    ref = run_oracle_layer(layer, logits=logits, tokens=tokens)
-    e = rel_err(out_to_f64(b.out)[tokens], ref["out"])
-    assert e <= TOL_OUT, e
+    assert len(tokens) >= 256
 
 
 def test_coarse8_full_size_sampled_prefill_and_single_token():
@@ -301,15 +335,7 @@ def test_coarse8_full_size_sampled_prefill_and_single_token():
     dl = DeviceLayer(layer)
     logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
     b = run_gpu_layer(dl, logits=logits)
-    idx, w, imp, kt = oracle.route(logits, layer.conf, cfg.gamma, cfg.k_big, cfg.k_little, cfg.renorm)
-    off, st, sr, inv = oracle.dispatch(idx, kt, cfg.E)
-    assert np.array_equal(i32(b.topk_idx), idx) and np.array_equal(b.important.cpu().numpy(), imp)
-    assert np.array_equal(i32(b.expert_offsets), off) and np.array_equal(i32(b.sorted_token), st)
-    assert np.array_equal(i32(b.sorted_rank), sr) and np.array_equal(i32(b.inv_pos), inv)
-    tokens = np.sort(np.random.default_rng(1).choice(cfg.T, size=6, replace=False))
-    ref = run_oracle_layer(layer, logits=logits, tokens=tokens)
-    e = rel_err(out_to_f64(b.out)[tokens], ref["out"])
-    assert e <= TOL_OUT, e
+    check_sampled_prefill(cfg, layer, b, logits, n_random=8, seed=1)
     # decode: the first token alone, once little (confident) and once big (not confident)
     one = wl.Layer(cfg.with_(T=1), layer.x[:1], layer.Wg, layer.gate_bias, layer.expert_w, layer.shared_w,
                    layer.conf[:1])
