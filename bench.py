@@ -643,10 +643,8 @@ def algorithmic_work(cfg, P: float, D: float):
                 gate_up_flops=gu_flops, down_bytes=dn_bytes)
 
 
-def cpu_baseline(torch, cfg, layers: DeviceLayers, budget_s: float = 12.0):
-    """The oracle as it stands, on the host cores, on the tokens of layer 0 (bounded sample)."""
-    import oracle
-
+def cpu_inputs(torch, cfg, layers: DeviceLayers):
+    """Host copies of layer 0 for the CPU baseline (taken while the device layers still exist)."""
     def host(t):
         t = t.detach().cpu()
         if t.dtype == torch.bfloat16:
@@ -659,6 +657,15 @@ def cpu_baseline(torch, cfg, layers: DeviceLayers, budget_s: float = 12.0):
     ew = [host(layers.experts[0][e]) for e in range(cfg.E)]
     sw = [host(s) for s in layers.shared[0]]
     conf = host(layers.conf[0])
+    return x, Wg, bias, ew, sw, conf
+
+
+def cpu_baseline(cfg, inputs, budget_s: float = 12.0):
+    """The oracle as it stands, on the host cores, on the tokens of layer 0 (bounded sample).  Runs
+    after every GPU measurement: host threads busy with it slow the steps that take decisions on
+    the host."""
+    import oracle
+    x, Wg, bias, ew, sw, conf = inputs
     n_tok = min(cfg.T, 64)
     done_tokens, t_used = 0, 0.0
     while True:
@@ -833,7 +840,7 @@ def main():
     roofline["avg_us"] = gu["avg_us"]
     roofline["algorithmic_bytes"] = work["gate_up_bytes"]
 
-    cpu = None if args.no_cpu else cpu_baseline(torch, cfg, main_res["_layers"])
+    cpu_in = None if args.no_cpu else cpu_inputs(torch, cfg, main_res["_layers"])
 
     step_floor_us = max(work["step_bytes"] / HBM_PEAK_GBS / 1e3, work["step_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e6)
     extra = dict(kernels_us={k: round(v["avg_us"], 2) for k, v in kern.items()},
@@ -896,8 +903,9 @@ def main():
         others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 30,
                                               ratio=args.ratio)
         extra["other_workloads"] = others
-        if not args.no_cpu:
-            extra["cpu_oracle_rows"] = cpu_rows(torch)
+    cpu = None if args.no_cpu else cpu_baseline(cfg, cpu_in)
+    if not (args.no_extra or args.no_cpu):
+        extra["cpu_oracle_rows"] = cpu_rows(torch)
 
     line = dict(metric="MoE-layer tokens/s (decode b=1..64, prefill 2k) + % HBM/MFMA roofline",
                 value=main_res["tokens_per_s"], unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
