@@ -390,6 +390,14 @@ def time_offload_eq1(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16,
         T_, Tl_ = out["all_big"]["us_per_step"], out["all_little"]["us_per_step"]
         for r in (0.11, 0.21):
             confs_h = [wl.make_confidence(300 + i, cfg.T, cfg.gamma, r) for i in range(nb)]
+            # few tokens in all (one per step): exactly round(r * tokens) of them are flagged, the ones
+            # with the lowest drawn confidences, so that the realised ratio is the nominal one
+            flat = np.concatenate(confs_h)
+            n_flag = int(round(r * flat.size))
+            order = np.argsort(flat, kind="stable")
+            flat[order[:n_flag]] = np.minimum(flat[order[:n_flag]], np.float32(cfg.gamma * 0.5))
+            flat[order[n_flag:]] = np.maximum(flat[order[n_flag:]], np.float32((1.0 + cfg.gamma) * 0.5))
+            confs_h = [flat[i * cfg.T:(i + 1) * cfg.T].copy() for i in range(nb)]
             confs = [torch.from_numpy(c).cuda() for c in confs_h]
             # predicted experts of the fallback pass per batch: top-k_big of the noisy logits of the
             # rejected tokens, most likely rank first, each expert once
@@ -421,7 +429,7 @@ def time_offload_eq1(mm, torch, cfg, steps: int, warmup: int, n_slots: int = 16,
                                  prediction_overlap=float(np.mean(overlap)) if overlap else None,
                                  speedup_measured_demand=T_ / d["us_per_step"],
                                  speedup_measured_prefetch=T_ / pf["us_per_step"],
-                                 speedup_eq1=eq1(T_, Tl_, T_, r))
+                                 speedup_eq1=eq1(T_, Tl_, T_, r), speedup_eq1_realised_ratio=eq1(T_, Tl_, T_, flagged))
     finally:
         mm.moe_cache_sync(h)
         mm.moe_cache_destroy(h)
@@ -499,10 +507,14 @@ def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 
 
 
 def time_alg1_offload(mm, torch, cfg, steps: int, warmup: int, L: int, n_slots: int, V: int = 256,
-                      ratio: float = 0.2, distances=(0, 1, 2, 3)):
+                      ratio: float = 0.2, distances=(0, 1, 2, 3), link_gbps: float = 0.0, block_us: float = 0.0,
+                      in_flight=None, yield_to_demand=False):
     """Alg. 1 on a toy language model whose routed experts live in pinned host memory (one cache of
     n_slots per layer): the same run for several prefetch distances d (Sec. III-B: the experts of a
-    rejected slot's big pass are requested d layers ahead of the layer being computed)."""
+    rejected slot's big pass are requested d layers ahead of the layer being computed).
+    link_gbps > 0 emulates a slower host link; block_us > 0 puts that much other device work in
+    front of every MoE layer (a stand-in for the attention of the block, which is what the copies
+    of a prefetch can hide under); in_flight bounds the prefetch copies in flight."""
     import numpy as np
     from paper_2510_12357_amd import workloads as wl
     from paper_2510_12357_amd.alg1_driver import Alg1Batch, LayerCaches, ToyLMDevice
@@ -528,22 +540,55 @@ def time_alg1_offload(mm, torch, cfg, steps: int, warmup: int, L: int, n_slots: 
     head32 = torch.randn((V, cfg.H), generator=g, device="cuda")
     prompts = wl.make_prompt_tokens(5, 1 << 16, V)
 
+    # the stand-in for the rest of a block: square bf16 products, as many as take block_us
+    block_work, block_measured = None, 0.0
+    if block_us > 0:
+        A = torch.randn((2048, 2048), generator=g, device="cuda").to(torch.bfloat16)
+        C = torch.empty_like(A)
+
+        def products(n):
+            for _ in range(n):
+                torch.mm(A, A, out=C)
+        products(20)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        products(200)
+        torch.cuda.synchronize()
+        one = (time.perf_counter() - t0) / 200 * 1e6
+        n_prod = max(1, int(round(block_us / one)))
+        block_measured = n_prod * one
+
+        def block_work():
+            products(n_prod)
+
     def run(d, head, n, warm):
         caches = LayerCaches(host, n_slots)
         try:
-            r = Alg1Batch(ToyLMDevice(cfg, V, embed, head, layers, norm=True), B, prompts, max_new=32, caches=caches.handles,
-                          prefetch_distance=d)
+            if link_gbps > 0:
+                for hnd in caches.handles:
+                    mm.moe_cache_emulate_link(hnd, link_gbps)
+            r = Alg1Batch(ToyLMDevice(cfg, V, embed, head, layers, norm=True, block_work=block_work), B, prompts,
+                          max_new=32, caches=caches.handles, prefetch_distance=d, in_flight_limit=in_flight,
+                          yield_to_demand=yield_to_demand)
             for _ in range(warm):
                 r.step()
             s0 = r.stats()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
+            by_mode = {False: [], True: []}          # one sequence: the time of little and of big passes
             for _ in range(n):
-                r.step()
+                big_now, t1 = bool(r.big[0]), time.perf_counter()
+                r.step()                             # ends with the read-back of the step's confidences
+                by_mode[big_now].append(time.perf_counter() - t1)
             torch.cuda.synchronize()
             dt_s = time.perf_counter() - t0
             s1 = r.stats()
-            return r, {k: s1[k] - s0[k] for k in s1 if k != "fallback_ratio"}, dt_s
+            r.close()
+            diff = {k: s1[k] - s0[k] for k in s1 if k != "fallback_ratio"}
+            if B == 1:
+                diff["little_pass_us"] = 1e6 * float(np.mean(by_mode[False])) if by_mode[False] else None
+                diff["big_pass_us"] = 1e6 * float(np.mean(by_mode[True])) if by_mode[True] else None
+            return r, diff, dt_s
         finally:
             caches.close()
 
@@ -574,7 +619,8 @@ def time_alg1_offload(mm, torch, cfg, steps: int, warmup: int, L: int, n_slots: 
     head = (head32 * hi).to(dt)
 
     out = dict(layers=L, head_scale=hi, slots_per_layer=n_slots, batch_slots=B, vocabulary=V, blob_mb=blob * host[0].element_size() / 1e6,
-               steps=steps, by_distance={})
+               steps=steps, emulated_link_gb_per_s=link_gbps or None, block_work_us_per_layer=block_measured or None,
+               prefetch_copies_in_flight_bound=in_flight, prefetch_yields_to_demand=yield_to_demand, by_distance={})
     for d in distances:
         _, s, dt_s = run(d, head, steps, warmup)
         need = s["demand_hits"] + s["demand_misses"]
@@ -584,6 +630,8 @@ def time_alg1_offload(mm, torch, cfg, steps: int, warmup: int, L: int, n_slots: 
             demand_hit_rate=s["demand_hits"] / max(1, need), experts_needed_per_step=need / steps,
             prefetch_copies_per_step=s["prefetch_copies"] / steps, prefetch_dropped_per_step=s["prefetch_dropped"] / steps,
             h2d_gb_per_s=s["bytes_h2d"] / dt_s / 1e9, h2d_mb_per_step=s["bytes_h2d"] / steps / 1e6)
+        if B == 1:
+            out["by_distance"][str(d)].update(little_pass_us=s["little_pass_us"], big_pass_us=s["big_pass_us"])
     return out
 
 
@@ -780,6 +828,22 @@ def main():
                    light_offload=time_alg1_offload(mm, torch, light, args.steps, args.warmup, L, 48, ratio=args.ratio),
                    shared2_offload_w8=time_alg1_offload(mm, torch, real.with_(dtype="bf16w8"), args.steps, args.warmup, L,
                                                         48, ratio=args.ratio, distances=(0, 1)))
+        res["shared2_offload_yield"] = time_alg1_offload(mm, torch, real, args.steps, args.warmup, L, 48, ratio=args.ratio,
+                                                         distances=(0, 1, 2), yield_to_demand=True)
+        # the paper's setting (Sec. III-B, Fig. 4): one sequence, a cache of a quarter of the experts,
+        # a block's other work in front of every MoE layer, and links of different speeds
+        one = light.with_(T=1)
+        slow = {}
+        for gbps in (0.0, 20.0, 10.0, 5.0):
+            slow[f"link_{gbps:g}" if gbps else "link_native"] = time_alg1_offload(
+                mm, torch, one, 4 * args.steps, args.warmup, 8, 16, ratio=args.ratio, link_gbps=gbps, block_us=300.0)
+        slow["link_10_at_most_4_in_flight"] = time_alg1_offload(
+            mm, torch, one, 4 * args.steps, args.warmup, 8, 16, ratio=args.ratio, link_gbps=10.0, block_us=300.0,
+            in_flight=4)
+        slow["link_10_yield_to_demand"] = time_alg1_offload(
+            mm, torch, one, 4 * args.steps, args.warmup, 8, 16, ratio=args.ratio, link_gbps=10.0, block_us=300.0,
+            yield_to_demand=True)
+        res["single_sequence_with_block_work"] = slow
         print(json.dumps(res))
         return
 

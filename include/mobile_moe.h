@@ -347,9 +347,63 @@ int moe_cache_sync(moe_cache_t* cache);
 int moe_cache_set_prefetch_limit(moe_cache_t* cache, int32_t max_copies_per_call);
 
 /* Measurement aid: emulates a slower host link (the paper's system loads over PCIe 4.0).  Every
- * copy is followed, on its copy stream, by a hold of blob_bytes / gb_per_s, so that a copy stream
- * delivers 1 / (1/link + 1/gb_per_s).  0 = off (the default). */
+ * copy of this cache is followed by a hold of blob_bytes / gb_per_s, and all emulated copies of a
+ * device, whichever cache and copy stream carries them, run one after the other in the order in
+ * which they were issued (one link, one queue), so that the link delivers
+ * 1 / (1/link + 1/gb_per_s).  0 = off (the default). */
 int moe_cache_emulate_link(moe_cache_t* cache, double gb_per_s);
+
+/* ---- Prefetch scheduler over a stack of layers (Sec. III-B) -----------------------------------
+ * When a token's little pass is rejected, the router outputs of that pass are known for all
+ * layers, and the big pass that follows will most likely select the same experts; they are
+ * requested `distance` layers ahead of the layer that is being computed (one layer ahead on a
+ * fast link, two or three on a slow one).  The scheduler owns no cache and no stream: it turns
+ * router logits into one request list per layer and issues expert_cache_fetch(PREFETCH) calls on
+ * the layers' caches at the points of a pass the caller reports.  Host-side object; calls on one
+ * scheduler are not thread-safe. */
+typedef struct moe_prefetcher moe_prefetcher_t;
+
+/* caches: host array of n_layers caches (kept by pointer; they must outlive the scheduler and
+ * all hold the same number of experts).  k_big: experts predicted per rejected token and layer.
+ * Returns NULL on error. */
+moe_prefetcher_t* moe_prefetcher_create(int32_t n_layers, moe_cache_t* const* caches, int32_t k_big);
+void moe_prefetcher_destroy(moe_prefetcher_t* p);
+
+/* Bound on the PREFETCH copies in flight over all layers (the depth of the prefetch queue): an
+ * advance call starts at most as many copies as keep the number of prefetch copies that have not
+ * landed yet within the bound, and drops the rest.  Negative = no bound (the default).  With a
+ * bound, what a call starts depends on how far earlier copies have come. */
+int moe_prefetcher_set_in_flight_limit(moe_prefetcher_t* p, int32_t max_copies_in_flight);
+
+/* With on != 0, a request made while a DEMAND copy of any of the layers is still in flight starts
+ * no copy (it runs under the bound 0: resident experts of the list are kept fresh, missing ones
+ * are dropped), so that a copy the step is waiting for never shares the link with a copy started
+ * on a prediction.  Off by default.  Like the bound above, it makes what a call starts depend on
+ * timing. */
+int moe_prefetcher_set_yield_to_demand(moe_prefetcher_t* p, int32_t on);
+
+/* New prediction from one pass's router states.  layer_logits: host array of n_layers DEVICE
+ * pointers to that pass's router logits [T, E] fp32 (as moe_route wrote them); rejected: host
+ * [n_rejected], the tokens of the pass whose little result was dropped.  Copies the logits to the
+ * host on `stream` and WAITS for them.  The request list of a layer is the rejected tokens'
+ * selection under the layer's own rule (k_big experts; logit descending, expert id ascending, NaN
+ * as -infinity), rank by rank (every token's first choice, then every token's second, ...), each
+ * expert once.  n_rejected == 0 clears the prediction (no copy, no wait). */
+int moe_prefetcher_predict(moe_prefetcher_t* p, const float* const* layer_logits, int32_t T,
+                           const int32_t* rejected, int32_t n_rejected, void* stream);
+
+/* The request list of a layer: ids host [E] out; returns its length (or a negative error). */
+int moe_prefetcher_predicted(moe_prefetcher_t* p, int32_t layer, int32_t* ids);
+
+/* A point of the pass that follows the prediction.  layer == -1: the pass starts (the lists of
+ * layers 0 .. distance-1 are requested); layer == l >= 0: layer l is about to run (the list of
+ * layer l + distance is requested, if there is such a layer).  distance == 0 requests nothing.
+ * Layers with an empty list are skipped.  Per request made, in order: issued_layers[i] (the
+ * layer), limits_used[i] (the bound on copies the call ran under, negative = none) and
+ * issued_stats[i]; each host [n_layers] out or NULL.  compute_stream as in expert_cache_fetch.
+ * Returns the number of requests made (>= 0) or a negative error. */
+int moe_prefetcher_advance(moe_prefetcher_t* p, int32_t layer, int32_t distance, int32_t* issued_layers,
+                           int32_t* limits_used, moe_fetch_stats* issued_stats, void* compute_stream);
 
 #ifdef __cplusplus
 }

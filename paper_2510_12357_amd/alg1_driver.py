@@ -38,14 +38,17 @@ from . import workloads as wl
 class ToyLMDevice:
     """A toy language model on the device: embedding [V,H], head [V,H] (both in the layers' dtype)
     and per layer a dict with Wg, gate_bias (or None), table (int64 device pointers of the E expert
-    blobs) and shared (list of blobs)."""
+    blobs) and shared (list of blobs).  `block_work` (a callable or None) is enqueued once per layer
+    in front of the MoE layer: a stand-in for the rest of a transformer block (attention), which
+    the toy model does not have, for measurements that need its time."""
 
     def __init__(self, cfg: wl.LayerConfig, V: int, embed: torch.Tensor, head: torch.Tensor, layers: list,
-                 norm: bool = False):
+                 norm: bool = False, block_work=None):
         if V > 256:
             raise ValueError("the output head runs on the router kernel: at most 256 tokens in the vocabulary")
         self.cfg, self.V, self.device = cfg, V, embed.device
         self.embed, self.head, self.layers, self.norm = embed, head, layers, norm
+        self.block_work = block_work
         # the head as a "router" over V outputs with one selected entry
         self.head_cfg = wl.LayerConfig("lm_head", T=1, H=cfg.H, E=V, I=16, k_big=1, k_little=1,
                                        dtype="fp32" if cfg.dtype == "fp32" else "bf16", gamma=cfg.gamma)
@@ -111,7 +114,8 @@ class Alg1Batch:
 
     def __init__(self, dev: ToyLMDevice, B: int, prompts: np.ndarray, max_new: int, eos: int = 0,
                  record: Optional[list] = None, always_big: bool = False, caches: Optional[list] = None,
-                 prefetch_distance: int = 0, fetch_log: Optional[list] = None):
+                 prefetch_distance: int = 0, fetch_log: Optional[list] = None, in_flight_limit: Optional[int] = None,
+                 n_slots: Optional[int] = None, yield_to_demand: bool = False):
         self.dev, self.B, self.max_new, self.eos, self.record = dev, B, max_new, eos, record
         if caches is not None and len(caches) != len(dev.layers):
             raise ValueError("one expert cache per layer")
@@ -139,7 +143,15 @@ class Alg1Batch:
         # layer, most likely first), and the counters
         L = len(dev.layers)
         self.predicted: List[List[int]] = [[] for _ in range(L)]
-        self.pb = mm.StepBuffers(dev.cfg, L * B, d) if caches is not None and prefetch_distance > 0 else None
+        self.sched = None
+        if caches is not None and prefetch_distance > 0:
+            self.sched = mm.moe_prefetcher_create(caches, dev.cfg.k_big)
+            if in_flight_limit is not None:
+                mm.moe_prefetcher_set_in_flight_limit(self.sched, in_flight_limit)
+            mm.moe_prefetcher_set_yield_to_demand(self.sched, yield_to_demand)
+        if fetch_log is not None and caches is not None and n_slots is None:
+            raise ValueError("a fetch log records the caches' residency: pass the caches' n_slots")
+        self.n_slots = n_slots
         self.demand_hits = self.demand_misses = self.prefetch_copies = self.prefetch_dropped = 0
         self.bytes_h2d = self.waves = 0
         for b in range(B):
@@ -175,17 +187,18 @@ class Alg1Batch:
         x = dev.embed.index_select(0, self.tok_dev)
         xs = [x]
         L = len(dev.layers)
-        if self.caches is not None and self.distance > 0:
-            for l in range(min(self.distance, L)):
-                self._prefetch(l)
+        if self.sched is not None:
+            self._prefetch(-1)
         for l, (ly, b) in enumerate(zip(dev.layers, self.bufs)):
+            if self.sched is not None:
+                self._prefetch(l)           # layer l is about to run: request what layer l + d will need
+            if dev.block_work is not None:
+                dev.block_work()
             if self.caches is None:
                 # resident experts: a batch of at most 64 slots is one launch per layer
                 step = mm.layer_decode_step if b.lws is not None else mm.layer_step
                 x = step(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev, ly["table"], ly["shared"])
             else:
-                if self.distance > 0 and l + self.distance < L:
-                    self._prefetch(l + self.distance)
                 x, st, waves = mm.layer_step_cached(b, x, ly["Wg"], ly["gate_bias"], self.conf_dev,
                                                     self.caches[l], ly["shared"])
                 self.demand_hits += st.hits
@@ -237,39 +250,33 @@ class Alg1Batch:
 
     # ---- prefetch from the router states of the rejected passes (Sec. III-B)
     def _predict(self, rejected: List[int]) -> None:
-        """The experts the big pass of the slots now in big mode will most likely select, per layer:
-        the layer's own selection rule (k_big experts, logit descending, id ascending) on the router
-        logits of the rejected little pass; most likely rank first, each expert once."""
-        L, B, K = len(self.dev.layers), self.B, self.dev.cfg.k_big
-        self.predicted = [[] for _ in range(L)]
-        if self.pb is None or self.always_big or not rejected:
-            return                          # a slot is in big mode only right after its rejection
-        slots = rejected
-        pb = self.pb
-        # all layers' router logits of the step in one [L*B, E] selection; one copy to the host
-        torch.stack([b.logits for b in self.bufs], out=pb.logits.view(L, B, -1))
-        mm.moe_route(pb.c, None, None, None, None, pb.logits, True, pb.topk_idx, pb.topk_w, pb.important,
-                     pb.k_t, None)
-        idx = pb.topk_idx.cpu().numpy().reshape(L, B, K)
-        for l in range(L):
-            seen = []
-            for j in range(K):
-                for b in slots:
-                    e = int(idx[l, b, j])
-                    if e not in seen:
-                        seen.append(e)
-            self.predicted[l] = seen
-
-    def _prefetch(self, l: int) -> None:
-        ids = self.predicted[l]
-        if not ids:
+        """Hands the router logits of the step's passes and the slots that were rejected to the
+        library's prefetch scheduler, which keeps one request list per layer (the experts the big
+        pass will most likely select, by the layer's own rule, most likely rank first)."""
+        if self.sched is None:
             return
-        slots, st = mm.expert_cache_fetch(self.caches[l], ids, 1)
-        self.prefetch_copies += st.misses
-        self.prefetch_dropped += st.dropped
-        self.bytes_h2d += st.bytes_h2d
-        if self.fetch_log is not None:
-            self.fetch_log.append((self.n_steps, l, list(ids), slots, (st.hits, st.misses, st.dropped)))
+        if self.always_big:
+            rejected = []                   # a slot is in big mode only right after its rejection
+        mm.moe_prefetcher_predict(self.sched, [b.logits for b in self.bufs], self.B, rejected)
+        E = self.dev.cfg.E
+        self.predicted = [mm.moe_prefetcher_predicted(self.sched, l, E) for l in range(len(self.bufs))]
+
+    def _prefetch(self, layer: int) -> None:
+        """Reports a point of the pass (-1: it starts; l: layer l is about to run) to the scheduler."""
+        L = len(self.bufs)
+        for l, limit, st in mm.moe_prefetcher_advance(self.sched, layer, self.distance, L):
+            self.prefetch_copies += st.misses
+            self.prefetch_dropped += st.dropped
+            self.bytes_h2d += st.bytes_h2d
+            if self.fetch_log is not None:
+                self.fetch_log.append((self.n_steps, l, list(self.predicted[l]), limit,
+                                       mm.moe_cache_snapshot(self.caches[l], self.n_slots),
+                                       (st.hits, st.misses, st.dropped)))
+
+    def close(self) -> None:
+        if self.sched is not None:
+            mm.moe_prefetcher_destroy(self.sched)
+            self.sched = None
 
     def stats(self) -> dict:
         return dict(steps=self.n_steps, accepted_tokens=self.n_accepted, fallbacks=self.n_fallbacks,

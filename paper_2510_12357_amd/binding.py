@@ -32,7 +32,9 @@ EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profi
            "moe_layer_decode_status", "moe_layer_decode", "moe_expert_ffn", "moe_expert_ffn_static", "moe_expert_ffn_static_max_bytes",
            "moe_combine", "moe_cache_create", "moe_cache_destroy",
            "moe_cache_expert_table", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot", "moe_cache_sync",
-           "moe_cache_set_prefetch_limit", "moe_cache_emulate_link")
+           "moe_cache_set_prefetch_limit", "moe_cache_emulate_link", "moe_prefetcher_create", "moe_prefetcher_destroy",
+           "moe_prefetcher_set_in_flight_limit", "moe_prefetcher_set_yield_to_demand", "moe_prefetcher_predict", "moe_prefetcher_predicted",
+           "moe_prefetcher_advance")
 
 
 class MoeError(RuntimeError):
@@ -117,6 +119,19 @@ def load_library() -> ctypes.CDLL:
     lib.moe_cache_sync.argtypes = [vp]
     lib.moe_cache_set_prefetch_limit.argtypes = [vp, i32]
     lib.moe_cache_emulate_link.argtypes = [vp, ctypes.c_double]
+    lib.moe_prefetcher_create.argtypes = [i32, ctypes.POINTER(vp), i32]
+    lib.moe_prefetcher_create.restype = vp
+    lib.moe_prefetcher_destroy.argtypes = [vp]
+    lib.moe_prefetcher_destroy.restype = None
+    lib.moe_prefetcher_set_in_flight_limit.argtypes = [vp, i32]
+    lib.moe_prefetcher_set_yield_to_demand.argtypes = [vp, i32]
+    lib.moe_prefetcher_predict.argtypes = [vp, ctypes.POINTER(vp), i32, ctypes.POINTER(i32), i32, vp]
+    lib.moe_prefetcher_predicted.argtypes = [vp, i32, ctypes.POINTER(i32)]
+    lib.moe_prefetcher_advance.argtypes = [vp, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                           ctypes.POINTER(moe_fetch_stats), vp]
+    for name in ("moe_prefetcher_set_in_flight_limit", "moe_prefetcher_set_yield_to_demand", "moe_prefetcher_predict", "moe_prefetcher_predicted",
+                 "moe_prefetcher_advance"):
+        getattr(lib, name).restype = ctypes.c_int
     for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence", "moe_dispatch",
                  "moe_dispatch_from", "moe_combine_add",
                  "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot",
@@ -348,6 +363,53 @@ def moe_cache_set_prefetch_limit(cache: int, max_copies_per_call: int) -> None:
 
 def moe_cache_emulate_link(cache: int, gb_per_s: float) -> None:
     _check(load_library().moe_cache_emulate_link(ctypes.c_void_p(cache), float(gb_per_s)))
+
+
+def moe_prefetcher_create(caches: Sequence[int], k_big: int) -> int:
+    arr = (ctypes.c_void_p * max(1, len(caches)))(*caches)
+    h = load_library().moe_prefetcher_create(len(caches), arr, int(k_big))
+    if not h:
+        raise MoeError(-1, moe_last_error())
+    return int(h)
+
+
+def moe_prefetcher_destroy(p: int) -> None:
+    load_library().moe_prefetcher_destroy(ctypes.c_void_p(p))
+
+
+def moe_prefetcher_set_in_flight_limit(p: int, max_copies_in_flight: int) -> None:
+    _check(load_library().moe_prefetcher_set_in_flight_limit(ctypes.c_void_p(p), int(max_copies_in_flight)))
+
+
+def moe_prefetcher_set_yield_to_demand(p: int, on: bool) -> None:
+    _check(load_library().moe_prefetcher_set_yield_to_demand(ctypes.c_void_p(p), 1 if on else 0))
+
+
+def moe_prefetcher_predict(p: int, layer_logits: Sequence, T: int, rejected: Sequence[int], stream=None) -> None:
+    """layer_logits: one device tensor [T, E] fp32 per layer."""
+    ptrs = (ctypes.c_void_p * max(1, len(layer_logits)))(*[t.data_ptr() for t in layer_logits])
+    n = len(rejected)
+    rej = (ctypes.c_int32 * max(1, n))(*rejected)
+    _check(load_library().moe_prefetcher_predict(ctypes.c_void_p(p), ptrs, int(T), rej, n, _stream(stream)))
+
+
+def moe_prefetcher_predicted(p: int, layer: int, n_experts: int):
+    out = (ctypes.c_int32 * n_experts)()
+    rc = load_library().moe_prefetcher_predicted(ctypes.c_void_p(p), int(layer), out)
+    if rc < 0:
+        _check(rc)
+    return list(out[:rc])
+
+
+def moe_prefetcher_advance(p: int, layer: int, distance: int, n_layers: int, stream=None):
+    """-> [(layer, limit the request ran under, moe_fetch_stats), ...] of the requests made"""
+    ls, lim = (ctypes.c_int32 * n_layers)(), (ctypes.c_int32 * n_layers)()
+    st = (moe_fetch_stats * n_layers)()
+    rc = load_library().moe_prefetcher_advance(ctypes.c_void_p(p), int(layer), int(distance), ls, lim, st,
+                                               _stream(stream))
+    if rc < 0:
+        _check(rc)
+    return [(int(ls[i]), int(lim[i]), st[i]) for i in range(rc)]
 
 
 # ------------------------------------------------------------------------------ plumbing helpers

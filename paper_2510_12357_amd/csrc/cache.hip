@@ -17,10 +17,12 @@
 //                record nothing: the only slots still waiting for their release then belong to
 //                the most recent DEMAND call, which a PREFETCH never evicts.
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "cache_policy.h"
 #include "internal.h"
+#include "prefetch_plan.h"
 
 struct moe_cache {
   mm::CachePolicy policy;
@@ -31,6 +33,7 @@ struct moe_cache {
   const void** d_table = nullptr;          // device, [E]
   std::vector<char> pending_release, has_ready, has_released;
   std::vector<hipEvent_t> ready, released;
+  std::vector<int> prefetched;             // slots whose latest copy was a PREFETCH that may still be in flight
   int prefetch_limit = -1;                 // copies one PREFETCH call may start; < 0: no bound
   double link_gbps = 0.0;                  // > 0: every copy is followed by a timed hold of its stream (slower link)
   int32_t* h_offsets = nullptr;            // pinned host, [E+1]: landing zone of expert_offsets
@@ -53,23 +56,54 @@ __global__ void hold_stream_kernel(long long ticks) {
   for (int i = 0; i < (1 << 22) && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(32);
 }
 
+// The emulated link is one queue for the whole device: every emulated copy, whichever cache and
+// stream carries it, starts when the one issued before it is over (its hold included).
+std::mutex g_link_mutex;
+hipEvent_t g_link_free[16];
+bool g_link_has[16];
+
 int issue_copy(moe_cache& c, int expert, int slot, hipStream_t cs) {
   if (c.has_released[slot]) MM_HIP(hipStreamWaitEvent(cs, c.released[slot], 0));
   if (c.has_ready[slot]) MM_HIP(hipStreamWaitEvent(cs, c.ready[slot], 0));   // an earlier copy into the slot
-  MM_HIP(hipMemcpyAsync(c.dev + (size_t)slot * c.blob_bytes, c.host + (size_t)expert * c.blob_bytes,
-                        c.blob_bytes, hipMemcpyHostToDevice, cs));
   if (c.link_gbps > 0.0) {
-    // a hold of blob / link_gbps behind the copy: the stream then delivers 1 / (1/link + 1/link_gbps)
-    const double want_s = (double)c.blob_bytes / (c.link_gbps * 1e9);
-    const long long ticks = (long long)(want_s * 1e8);
+    // a hold of blob / link_gbps behind the copy: the link then delivers 1 / (1/link + 1/link_gbps)
+    int dev = 0;
+    MM_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 16) return fail(MOE_E_UNSUPPORTED, "link emulation: device %d", dev);
+    const long long ticks = (long long)((double)c.blob_bytes / (c.link_gbps * 1e9) * 1e8);
+    std::lock_guard<std::mutex> lock(g_link_mutex);
+    if (!g_link_has[dev]) {
+      MM_HIP(hipEventCreateWithFlags(&g_link_free[dev], hipEventDisableTiming));
+    } else {
+      MM_HIP(hipStreamWaitEvent(cs, g_link_free[dev], 0));
+    }
+    MM_HIP(hipMemcpyAsync(c.dev + (size_t)slot * c.blob_bytes, c.host + (size_t)expert * c.blob_bytes,
+                          c.blob_bytes, hipMemcpyHostToDevice, cs));
     if (ticks > 0) {
       hipLaunchKernelGGL(hold_stream_kernel, dim3(1), dim3(64), 0, cs, ticks);
       MM_HIP(hipGetLastError());
     }
+    MM_HIP(hipEventRecord(g_link_free[dev], cs));
+    g_link_has[dev] = true;
+  } else {
+    MM_HIP(hipMemcpyAsync(c.dev + (size_t)slot * c.blob_bytes, c.host + (size_t)expert * c.blob_bytes,
+                          c.blob_bytes, hipMemcpyHostToDevice, cs));
   }
   MM_HIP(hipEventRecord(c.ready[slot], cs));
   c.has_ready[slot] = 1;
   return MOE_OK;
+}
+
+// PREFETCH copies of this cache that have not landed yet (the list is pruned on the way).
+int prefetch_in_flight(moe_cache& c) {
+  size_t keep = 0;
+  for (size_t i = 0; i < c.prefetched.size(); ++i) {
+    const int s = c.prefetched[i];
+    if (hipEventQuery(c.ready[s]) == hipErrorNotReady) c.prefetched[keep++] = s;
+  }
+  (void)hipGetLastError();                                // hipErrorNotReady is not a failure
+  c.prefetched.resize(keep);
+  return (int)keep;
 }
 
 // Points the device table at the slots of `ids` (all other experts NULL) on the compute stream,
@@ -89,13 +123,13 @@ int publish(moe_cache& c, const int32_t* ids, int n, hipStream_t cs) {
 // The policy decision of one call plus its copies.  With `publish_now` (DEMAND) the compute
 // stream is made to wait for all of the call's slots and the pointer table is rewritten.
 int fetch_impl(moe_cache& c, const int32_t* ids, int n, int mode, int32_t* slot_of, moe_fetch_stats* stats,
-               hipStream_t cs, bool publish_now) {
+               hipStream_t cs, bool publish_now, int max_copies) {
   std::vector<PolicyCopy> copies;
   PolicyCounts counts = {0, 0, 0};
   std::vector<int32_t> slots_local((size_t)std::max(n, 1));
   int32_t* so = slot_of ? slot_of : slots_local.data();
   const int prc = c.policy.fetch(ids, n, mode == MOE_FETCH_DEMAND ? kPolicyDemand : kPolicyPrefetch,
-                                 c.prefetch_limit, so, &copies, &counts);
+                                 max_copies, so, &copies, &counts);
   switch (prc) {
     case kPolicyOk: break;
     case kPolicyBadId: return fail(MOE_E_BADARG, "expert_cache_fetch: expert id outside [0,%d)", c.policy.n_experts());
@@ -118,6 +152,8 @@ int fetch_impl(moe_cache& c, const int32_t* ids, int n, int mode, int32_t* slot_
   for (const PolicyCopy& cp : copies) {
     const int rc = issue_copy(c, cp.expert, cp.slot, copy_stream);
     if (rc) return rc;
+    if (mode == MOE_FETCH_PREFETCH && std::find(c.prefetched.begin(), c.prefetched.end(), cp.slot) == c.prefetched.end())
+      c.prefetched.push_back(cp.slot);
   }
   if (mode == MOE_FETCH_DEMAND) {
     for (int i = 0; i < n; ++i) c.pending_release[so[i]] = 1;
@@ -220,7 +256,8 @@ extern "C" int expert_cache_fetch(moe_cache_t* c, const int32_t* ids, int32_t n,
     return fail(MOE_E_BADARG, "expert_cache_fetch: null argument or n < 0");
   if (mode != MOE_FETCH_DEMAND && mode != MOE_FETCH_PREFETCH)
     return fail(MOE_E_BADARG, "expert_cache_fetch: mode %d", mode);
-  return fetch_impl(*c, ids, n, mode, slot_of, stats, static_cast<hipStream_t>(compute_stream), true);
+  return fetch_impl(*c, ids, n, mode, slot_of, stats, static_cast<hipStream_t>(compute_stream), true,
+                    c->prefetch_limit);
 }
 
 // One step's execution stage with offloaded experts: the router's decision is brought to the
@@ -268,7 +305,7 @@ extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, cons
     std::vector<char> was_resident(n);
     for (int k = 0; k < n; ++k) was_resident[k] = c->policy.slot_of_expert(ids[k]) >= 0;
     moe_fetch_stats st;
-    rc = fetch_impl(*c, ids, n, MOE_FETCH_DEMAND, slots.data(), &st, s, false);
+    rc = fetch_impl(*c, ids, n, MOE_FETCH_DEMAND, slots.data(), &st, s, false, -1);
     if (rc) return rc;
     sum.hits += st.hits; sum.misses += st.misses; sum.bytes_h2d += st.bytes_h2d;
     // residents of the wave in one launch, then the misses in copy order (ascending id)
@@ -291,4 +328,127 @@ extern "C" int moe_expert_ffn_cached(const moe_config* cfg, moe_cache_t* c, cons
   if (n_waves) *n_waves = waves;
   if (total) *total = sum;
   return MOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Prefetch scheduler over the caches of a stack of layers (Sec. III-B).
+struct moe_prefetcher {
+  mm::PrefetchPlan plan;
+  std::vector<moe_cache*> caches;
+  float* h_logits = nullptr;               // pinned host staging, [n_layers][T][E]
+  size_t h_floats = 0;
+  int in_flight_limit = -1;                // PREFETCH copies in flight over all layers; < 0: no bound
+  bool yield_to_demand = false;            // start no copy while a DEMAND copy of any layer is in flight
+  moe_prefetcher(int L, int E, int k) : plan(L, E, k) {}
+};
+
+extern "C" moe_prefetcher_t* moe_prefetcher_create(int32_t n_layers, moe_cache_t* const* caches, int32_t k_big) {
+  if (n_layers <= 0 || !caches || !caches[0]) {
+    fail(MOE_E_BADARG, "moe_prefetcher_create: n_layers=%d caches=%p", n_layers, (const void*)caches);
+    return nullptr;
+  }
+  const int E = caches[0]->policy.n_experts();
+  for (int l = 0; l < n_layers; ++l)
+    if (!caches[l] || caches[l]->policy.n_experts() != E) {
+      fail(MOE_E_BADARG, "moe_prefetcher_create: cache of layer %d is NULL or holds another number of experts", l);
+      return nullptr;
+    }
+  if (k_big < 1 || k_big > E) {
+    fail(MOE_E_BADARG, "moe_prefetcher_create: k_big=%d with %d experts", k_big, E);
+    return nullptr;
+  }
+  moe_prefetcher* p = new moe_prefetcher(n_layers, E, k_big);
+  p->caches.assign(caches, caches + n_layers);
+  return p;
+}
+
+extern "C" void moe_prefetcher_destroy(moe_prefetcher_t* p) {
+  if (!p) return;
+  if (p->h_logits) (void)hipHostFree(p->h_logits);
+  delete p;
+}
+
+extern "C" int moe_prefetcher_set_in_flight_limit(moe_prefetcher_t* p, int32_t max_copies_in_flight) {
+  if (!p) return fail(MOE_E_BADARG, "moe_prefetcher_set_in_flight_limit: null scheduler");
+  p->in_flight_limit = max_copies_in_flight < 0 ? -1 : max_copies_in_flight;
+  return MOE_OK;
+}
+
+extern "C" int moe_prefetcher_set_yield_to_demand(moe_prefetcher_t* p, int32_t on) {
+  if (!p) return fail(MOE_E_BADARG, "moe_prefetcher_set_yield_to_demand: null scheduler");
+  p->yield_to_demand = on != 0;
+  return MOE_OK;
+}
+
+extern "C" int moe_prefetcher_predict(moe_prefetcher_t* p, const float* const* layer_logits, int32_t T,
+                                      const int32_t* rejected, int32_t n_rejected, void* stream) {
+  if (!p || n_rejected < 0 || T < 0) return fail(MOE_E_BADARG, "moe_prefetcher_predict: null scheduler or negative count");
+  if (n_rejected == 0) { p->plan.clear(); return MOE_OK; }
+  if (!layer_logits || !rejected) return fail(MOE_E_BADARG, "moe_prefetcher_predict: null argument");
+  const int L = p->plan.n_layers(), E = p->plan.n_experts();
+  for (int i = 0; i < n_rejected; ++i)
+    if (rejected[i] < 0 || rejected[i] >= T)
+      return fail(MOE_E_BADARG, "moe_prefetcher_predict: token %d outside [0,%d)", rejected[i], T);
+  for (int l = 0; l < L; ++l)
+    if (!layer_logits[l]) return fail(MOE_E_BADARG, "moe_prefetcher_predict: logits of layer %d are NULL", l);
+  const size_t per_layer = (size_t)T * E, need = per_layer * L;
+  if (need > p->h_floats) {
+    if (p->h_logits) MM_HIP(hipHostFree(p->h_logits));
+    p->h_logits = nullptr;
+    p->h_floats = 0;
+    MM_HIP(hipHostMalloc((void**)&p->h_logits, need * sizeof(float), hipHostMallocDefault));
+    p->h_floats = need;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  for (int l = 0; l < L; ++l)
+    MM_HIP(hipMemcpyAsync(p->h_logits + per_layer * l, layer_logits[l], per_layer * sizeof(float),
+                          hipMemcpyDeviceToHost, s));
+  MM_HIP(hipStreamSynchronize(s));
+  p->plan.predict(p->h_logits, T, rejected, n_rejected);
+  return MOE_OK;
+}
+
+extern "C" int moe_prefetcher_predicted(moe_prefetcher_t* p, int32_t layer, int32_t* ids) {
+  if (!p || !ids || layer < 0 || layer >= p->plan.n_layers())
+    return fail(MOE_E_BADARG, "moe_prefetcher_predicted: null argument or layer %d", layer);
+  const std::vector<int32_t>& v = p->plan.layer(layer);
+  std::copy(v.begin(), v.end(), ids);
+  return (int)v.size();
+}
+
+extern "C" int moe_prefetcher_advance(moe_prefetcher_t* p, int32_t layer, int32_t distance, int32_t* issued_layers,
+                                      int32_t* limits_used, moe_fetch_stats* issued_stats, void* compute_stream) {
+  if (!p || distance < 0 || layer < -1 || layer >= p->plan.n_layers())
+    return fail(MOE_E_BADARG, "moe_prefetcher_advance: null scheduler, layer %d or distance %d", layer, distance);
+  std::vector<int32_t> due((size_t)p->plan.n_layers());
+  const int n_due = p->plan.due(layer, distance, due.data());
+  int n_issued = 0;
+  for (int i = 0; i < n_due; ++i) {
+    const int l = due[i];
+    const std::vector<int32_t>& ids = p->plan.layer(l);
+    if (ids.empty()) continue;
+    moe_cache& c = *p->caches[l];
+    int limit = c.prefetch_limit;
+    if (p->in_flight_limit >= 0) {
+      int flying = 0;
+      for (moe_cache* q : p->caches) flying += prefetch_in_flight(*q);
+      const int room = std::max(0, p->in_flight_limit - flying);
+      limit = limit < 0 ? room : std::min(limit, room);
+    }
+    if (p->yield_to_demand) {
+      bool busy = false;
+      for (moe_cache* q : p->caches) busy = busy || hipStreamQuery(q->demand_stream) == hipErrorNotReady;
+      (void)hipGetLastError();                            // hipErrorNotReady is not a failure
+      if (busy) limit = 0;
+    }
+    moe_fetch_stats st;
+    const int rc = fetch_impl(c, ids.data(), (int)ids.size(), MOE_FETCH_PREFETCH, nullptr, &st,
+                              static_cast<hipStream_t>(compute_stream), false, limit);
+    if (rc) return rc;
+    if (issued_layers) issued_layers[n_issued] = l;
+    if (limits_used) limits_used[n_issued] = limit;
+    if (issued_stats) issued_stats[n_issued] = st;
+    ++n_issued;
+  }
+  return n_issued;
 }

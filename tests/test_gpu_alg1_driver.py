@@ -186,14 +186,16 @@ def pinned_experts(lm):
     return [torch.stack([mm.to_device(b, lm.cfg, "cpu") for b in l.expert_w]).pin_memory() for l in lm.layers]
 
 
-def run_driver(lm, B, steps, max_new, prompts, caches=None, d=0):
+def run_driver(lm, B, steps, max_new, prompts, caches=None, d=0, n_slots=None, in_flight=None, yield_to_demand=False):
     from paper_2510_12357_amd.alg1_driver import Alg1Batch, ToyLMDevice
     rec, log = [], []
     run = Alg1Batch(ToyLMDevice.upload(lm), B, prompts, max_new, record=rec,
-                    caches=None if caches is None else caches.handles, prefetch_distance=d, fetch_log=log)
+                    caches=None if caches is None else caches.handles, prefetch_distance=d, fetch_log=log,
+                    n_slots=n_slots, in_flight_limit=in_flight, yield_to_demand=yield_to_demand)
     for _ in range(steps):
         run.step()
     torch.cuda.synchronize()
+    run.close()
     return run, rec, log
 
 
@@ -215,10 +217,14 @@ def test_offloaded_model_equals_resident_model_and_cache_follows_the_policy():
     assert base.stats()["fallbacks"] >= 5
     host = pinned_experts(lm)
     misses = {}
-    for d in (0, 1, 2, 7):
+    # (distance, bound on prefetch copies in flight, yield to demand copies): in the last two cases
+    # what a request may start depends on how far earlier copies have come; the bound each request
+    # ran under is logged and replayed
+    for d, in_flight, yields in ((0, None, False), (1, None, False), (2, None, False), (7, None, False),
+                                 (2, 3, False), (1, None, True)):
         caches = LayerCaches(host, n_slots)
         try:
-            run, rec, log = run_driver(lm, B, steps, max_new, prompts, caches, d)
+            run, rec, log = run_driver(lm, B, steps, max_new, prompts, caches, d, n_slots, in_flight, yields)
             st = run.stats()
             # ---- bit-identical to the model with all experts resident
             assert run.finished == base.finished and run.tokens == base.tokens
@@ -228,9 +234,13 @@ def test_offloaded_model_equals_resident_model_and_cache_follows_the_policy():
                     assert np.array_equal(g["topk_idx"], g0["topk_idx"])
                     assert torch.equal(g["out"], g0["out"])
             # ---- the predictions: k_big experts of the rejected pass's router logits, most likely rank first
-            by_call = {(s, l): (ids, slots, cnt) for s, l, ids, slots, cnt in log}
+            by_call = {(s, l): (ids, limit, snap, cnt) for s, l, ids, limit, snap, cnt in log}
             assert (len(log) > 0) == (d > 0)
-            for (s, l), (ids, _, _) in by_call.items():
+            for (s, l), (ids, limit, _, _) in by_call.items():
+                if yields:
+                    assert limit in (-1, 0)
+                else:
+                    assert (limit < 0) == (in_flight is None) and limit <= (in_flight if in_flight is not None else 0)
                 rej = [b for b in range(B) if rec[s]["big_in"][b] and not rec[s - 1]["big_in"][b]]
                 assert rej == [b for b in range(B) if rec[s]["big_in"][b]]
                 idx = oracle.route(rec[s - 1]["layers"][l]["logits"][rej], None, c.gamma, c.k_big, c.k_little,
@@ -251,9 +261,9 @@ def test_offloaded_model_equals_resident_model_and_cache_follows_the_policy():
                 model = CacheModel(c.E, n_slots)
                 for s in range(steps):
                     if (s, l) in by_call:
-                        ids, slots, cnt = by_call[(s, l)]
-                        ref_slots, h, m, dr = model.fetch(ids, PREFETCH)
-                        assert slots == ref_slots and cnt == (h, m, dr), (d, s, l)
+                        ids, limit, snap, cnt = by_call[(s, l)]
+                        _, h, m, dr = model.fetch(ids, PREFETCH, None if limit < 0 else limit)
+                        assert snap == model.slot_expert and cnt == (h, m, dr), (d, s, l)
                     g = rec[s]["layers"][l]
                     need = sorted({int(e) for e in g["topk_idx"].ravel() if e >= 0})
                     order = [e for e in need if model.slot_of(e) >= 0] + \
@@ -263,8 +273,9 @@ def test_offloaded_model_equals_resident_model_and_cache_follows_the_policy():
                         hits, miss = hits + h, miss + m
                 assert mm.moe_cache_snapshot(caches.handles[l], n_slots) == model.slot_expert, (d, l)
             assert (st["demand_hits"], st["demand_misses"]) == (hits, miss)
-            misses[d] = miss
-            assert (st["prefetch_copies"] > 0) == (d > 0)
+            if in_flight is None and not yields:
+                misses[d] = miss
+                assert (st["prefetch_copies"] > 0) == (d > 0)
         finally:
             caches.close()
     assert misses[1] < misses[0] and misses[2] < misses[0] and misses[7] < misses[0]
