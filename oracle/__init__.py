@@ -40,7 +40,7 @@ def _load():
         for name in ("oracle_gate_logits", "oracle_token_confidence", "oracle_route",
                      "oracle_dispatch", "oracle_dispatch_from", "oracle_combine_add", "oracle_swiglu_rows", "oracle_expert_ffn",
                      "oracle_combine", "oracle_num_threads", "oracle_set_num_threads", "oracle_swiglu_rows_w8",
-                     "oracle_e4m3_decode"):
+                     "oracle_e4m3_decode", "oracle_swiglu_rows_mx4", "oracle_e2m1_decode", "oracle_e8m0_decode"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -130,6 +130,37 @@ def w8_blob_bytes(H: int, I: int) -> int:
     return 3 * H * I + 4 * (2 * I + H)
 
 
+def mx4_blob_bytes(H: int, I: int) -> int:
+    """Bytes of an expert in MXFP4: 3*H*I codes of 4 bits + one E8M0 scale byte per 32 weights."""
+    return 3 * H * I // 2 + 3 * H * I // 32
+
+
+def e2m1_decode(codes: np.ndarray) -> np.ndarray:
+    """Values of E2M1 codes (OCP microscaling 4-bit element; low four bits of each byte) -> float64."""
+    c = _c(codes, np.uint8).ravel()
+    out = np.empty(c.shape, np.float64)
+    _check(_load().oracle_e2m1_decode(_p(c), c.size, _p(out)), "e2m1_decode")
+    return out.reshape(np.shape(codes))
+
+
+def e8m0_decode(scales: np.ndarray) -> np.ndarray:
+    """Values of E8M0 scales (OCP microscaling: 2^(b - 127), 255 = NaN) -> float64."""
+    c = _c(scales, np.uint8).ravel()
+    out = np.empty(c.shape, np.float64)
+    _check(_load().oracle_e8m0_decode(_p(c), c.size, _p(out)), "e8m0_decode")
+    return out.reshape(np.shape(scales))
+
+
+def _weight_format(blob: np.ndarray, H: int, I: int) -> int:
+    """0: weights in the activations' type; 1: 8-bit codes with row scales; 2: MXFP4.  Byte blobs
+    are told apart by their size."""
+    if blob.dtype != np.uint8:
+        return 0
+    w8, mx = blob.size == w8_blob_bytes(H, I), H % 32 == 0 and I % 32 == 0 and blob.size == mx4_blob_bytes(H, I)
+    assert w8 != mx, "a byte blob must have the size of the 8-bit or of the MXFP4 layout"
+    return 1 if w8 else 2
+
+
 def e4m3_decode(codes: np.ndarray) -> np.ndarray:
     """Values of E4M3 ("e4m3fn", OCP 8-bit floating point) codes -> float64."""
     c = _c(codes, np.uint8).ravel()
@@ -141,17 +172,23 @@ def e4m3_decode(codes: np.ndarray) -> np.ndarray:
 def swiglu_rows(x: np.ndarray, blob: np.ndarray, I: int,
                 tok: Optional[np.ndarray] = None) -> np.ndarray:
     """One expert (blob = [W_gate I*H | W_up I*H | W_down H*I] flat) on rows ``tok`` of x
-    (all rows in order when ``tok`` is None).  A uint8 blob holds 8-bit weights: E4M3 codes in
-    the same order, then the fp32 row scales [gate I | up I | down H].  -> float64 [n,H]"""
+    (all rows in order when ``tok`` is None).  A uint8 blob holds 8-bit weights (E4M3 codes in
+    the same order, then the fp32 row scales [gate I | up I | down H]) or MXFP4 weights (codes two
+    per byte in the same order, then one E8M0 scale per 32 weights), told apart by its size.
+    -> float64 [n,H]"""
     x, blob = _c(x), _c(blob)
     T, H = x.shape
     tk = None if tok is None else _c(tok, np.int32)
     n = T if tk is None else tk.shape[0]
     y = np.empty((n, H), np.float64)
-    if blob.dtype == np.uint8:
-        assert blob.size == w8_blob_bytes(H, I)
+    fmt = _weight_format(blob, H, I)
+    if fmt == 1:
         _check(_load().oracle_swiglu_rows_w8(_p(x), _dtype_code(x), H, I, _p(blob), _p(tk), n, _p(y)),
                "swiglu_rows_w8")
+        return y
+    if fmt == 2:
+        _check(_load().oracle_swiglu_rows_mx4(_p(x), _dtype_code(x), H, I, _p(blob), _p(tk), n, _p(y)),
+               "swiglu_rows_mx4")
         return y
     assert blob.size == 3 * H * I and _dtype_code(blob) == _dtype_code(x)
     _check(_load().oracle_swiglu_rows(_p(x), _dtype_code(x), H, I, _p(blob), _p(tk), n, _p(y)),
@@ -166,10 +203,10 @@ def expert_ffn(x: np.ndarray, expert_w: Sequence[np.ndarray], I: int, expert_off
     T, H = x.shape
     E = len(expert_w)
     blobs = [_c(b) for b in expert_w]
-    w8 = len(blobs) > 0 and blobs[0].dtype == np.uint8
+    w8 = _weight_format(blobs[0], H, I) if blobs else 0
     for b in blobs:
         if w8:
-            assert b.dtype == np.uint8 and b.size == w8_blob_bytes(H, I)
+            assert _weight_format(b, H, I) == w8
         else:
             assert b.size == 3 * H * I and _dtype_code(b) == _dtype_code(x)
     ptrs = (ctypes.c_void_p * E)(*[b.ctypes.data for b in blobs])

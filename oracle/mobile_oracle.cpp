@@ -58,6 +58,27 @@ inline double e4m3_value(uint8_t b) {
   return sign ? -v : v;
 }
 
+// 4-bit float E2M1 of the OCP microscaling formats (the element type of MXFP4): 1 sign, 2 exponent
+// (bias 1), 1 mantissa bit; no infinities, no NaN; exponent field 0 is subnormal (0 or 0.5).
+inline double e2m1_value(unsigned code) {
+  const int sign = (code >> 3) & 1, e = (code >> 1) & 3, m = code & 1;
+  const double v = e == 0 ? 0.5 * m : std::ldexp(1.0 + 0.5 * m, e - 1);
+  return sign ? -v : v;
+}
+
+// E8M0, the scale type of the microscaling formats: an unsigned exponent with bias 127; 255 is NaN.
+inline double e8m0_value(uint8_t b) {
+  return b == 255 ? std::numeric_limits<double>::quiet_NaN() : std::ldexp(1.0, (int)b - 127);
+}
+
+// Element k of a row of MXFP4 data: codes two per byte (even k in the low four bits), one scale
+// per block of 32 consecutive k.
+inline double mx4_elem(const uint8_t* codes, const uint8_t* scales, size_t row, size_t k, size_t K) {
+  const uint8_t byte = codes[(row * K + k) >> 1];
+  const unsigned code = (k & 1) ? (byte >> 4) : (byte & 15);
+  return e8m0_value(scales[(row * K + k) >> 5]) * e2m1_value(code);
+}
+
 // NaN router scores take part in selection and softmax as minus infinity.
 inline double clean_logit(float v) {
   return std::isnan(v) ? -std::numeric_limits<double>::infinity() : (double)v;
@@ -296,6 +317,57 @@ int oracle_swiglu_rows_w8(const void* x, int xdtype, int H, int I, const void* b
   return 0;
 }
 
+// The same feed-forward with the expert's weights in MXFP4 (OCP microscaling: 4-bit E2M1 elements
+// that share one E8M0 scale per block of 32 along the contraction; weight-only, activations in
+// `xdtype`):
+//   blob = [Q_gate I x H/2 | Q_up I x H/2 | Q_down H x I/2] bytes of two codes (even k low),
+//          followed by the scales [S_gate I x H/32 | S_up I x H/32 | S_down H x I/32], one byte each;
+//   W[r][k] = e8m0(S[r][k / 32]) * e2m1(Q[r][k]).  H and I are multiples of 32.
+int oracle_swiglu_rows_mx4(const void* x, int xdtype, int H, int I, const void* blob,
+                           const int32_t* tok, int n, double* y) {
+  if (!x || !blob || !y || H <= 0 || I <= 0 || n < 0 || H % 32 || I % 32) return -1;
+  const uint8_t* q = static_cast<const uint8_t*>(blob);
+  const size_t HI = (size_t)H * I;
+  const uint8_t* Qgate = q;
+  const uint8_t* Qup = q + HI / 2;
+  const uint8_t* Qdown = q + HI;
+  const uint8_t* Sgate = q + 3 * HI / 2;
+  const uint8_t* Sup = Sgate + HI / 32;
+  const uint8_t* Sdown = Sup + HI / 32;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int r = 0; r < n; ++r) {
+    const size_t t = tok ? (size_t)tok[r] : (size_t)r;
+    std::vector<double> a(I);
+    for (int i = 0; i < I; ++i) {
+      double g = 0.0, u = 0.0;
+      for (int h = 0; h < H; ++h) {
+        const double xv = load_elem(x, t * H + h, xdtype);
+        g += mx4_elem(Qgate, Sgate, i, h, H) * xv;
+        u += mx4_elem(Qup, Sup, i, h, H) * xv;
+      }
+      a[i] = g / (1.0 + std::exp(-g)) * u;
+    }
+    for (int c = 0; c < H; ++c) {
+      double acc = 0.0;
+      for (int i = 0; i < I; ++i) acc += mx4_elem(Qdown, Sdown, c, i, I) * a[i];
+      y[(size_t)r * H + c] = acc;
+    }
+  }
+  return 0;
+}
+
+// Values of n E2M1 codes (one per byte, low four bits) and of n E8M0 scales.
+int oracle_e2m1_decode(const uint8_t* codes, int n, double* out) {
+  if (!codes || !out || n < 0) return -1;
+  for (int i = 0; i < n; ++i) out[i] = e2m1_value(codes[i] & 15u);
+  return 0;
+}
+int oracle_e8m0_decode(const uint8_t* scales, int n, double* out) {
+  if (!scales || !out || n < 0) return -1;
+  for (int i = 0; i < n; ++i) out[i] = e8m0_value(scales[i]);
+  return 0;
+}
+
 int oracle_e4m3_decode(const uint8_t* codes, int n, double* out) {
   if (!codes || !out || n < 0) return -1;
   for (int i = 0; i < n; ++i) out[i] = e4m3_value(codes[i]);
@@ -304,16 +376,18 @@ int oracle_e4m3_decode(const uint8_t* codes, int n, double* out) {
 
 // Execution stage over the dispatched pairs: expert e processes positions
 // offsets[e] .. offsets[e+1]-1.  expert_w[e] points at expert e's blob (host memory).
-// w8 != 0: the blobs hold 8-bit weights with row scales (oracle_swiglu_rows_w8).
+// w8 == 1: the blobs hold 8-bit weights with row scales (oracle_swiglu_rows_w8); w8 == 2: MXFP4
+// weights (oracle_swiglu_rows_mx4).
 int oracle_expert_ffn(const void* x, int dtype, int H, int I, int E, const int32_t* offsets,
                       const int32_t* sorted_token, const void* const* expert_w, int w8, double* y) {
   if (!offsets || !sorted_token || !expert_w) return -1;
   for (int e = 0; e < E; ++e) {
     const int b = offsets[e], n = offsets[e + 1] - b;
     if (n == 0) continue;
-    int rc = w8 ? oracle_swiglu_rows_w8(x, dtype, H, I, expert_w[e], sorted_token + b, n, y + (size_t)b * H)
-                : oracle_swiglu_rows(x, dtype, H, I, expert_w[e], sorted_token + b, n,
-                                y + (size_t)b * H);
+    int rc = w8 == 2 ? oracle_swiglu_rows_mx4(x, dtype, H, I, expert_w[e], sorted_token + b, n, y + (size_t)b * H)
+             : w8 ? oracle_swiglu_rows_w8(x, dtype, H, I, expert_w[e], sorted_token + b, n, y + (size_t)b * H)
+                  : oracle_swiglu_rows(x, dtype, H, I, expert_w[e], sorted_token + b, n,
+                                       y + (size_t)b * H);
     if (rc) return rc;
   }
   return 0;

@@ -29,7 +29,8 @@ class LayerConfig:
     k_little: int               # experts of every other token (K/2)
     shared_I: Tuple[int, ...] = ()   # always-on shared experts (intermediate sizes)
     dtype: str = "bf16"         # storage type of x and all weights: "bf16" | "fp32" | "bf16w8" (bf16
-                                # activations and router, expert weights in 8 bits with row scales)
+                                # activations and router, expert weights in 8 bits with row scales) |
+                                # "bf16mx4" (bf16 activations and router, expert weights in MXFP4)
     renorm: bool = False        # renormalise routing weights over the selected experts
     gamma: float = 0.7          # fallback threshold
     gate_std: float = 0.02
@@ -73,10 +74,10 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def _store(a: np.ndarray, dtype: str) -> np.ndarray:
-    """Activations, router weights, embeddings: "bf16w8" stores them as bf16."""
+    """Activations, router weights, embeddings: "bf16w8" and "bf16mx4" store them as bf16."""
     if dtype == "fp32":
         return np.ascontiguousarray(a, dtype=np.float32)
-    if dtype in ("bf16", "bf16w8"):
+    if dtype in ("bf16", "bf16w8", "bf16mx4"):
         return f32_to_bf16_bits(a)
     raise ValueError(dtype)
 
@@ -106,6 +107,47 @@ def quantize_blob_w8(w: np.ndarray, H: int, I: int) -> np.ndarray:
         codes.append(f32_to_e4m3_bits(m / s[:, None]).ravel())
         scales.append(s)
     return np.concatenate(codes + [np.concatenate(scales).view(np.uint8)])
+
+
+def mx4_blob_bytes(H: int, I: int) -> int:
+    return 3 * H * I // 2 + 3 * H * I // 32
+
+
+_E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], np.float64)   # magnitudes of codes 0..7
+
+
+def quantize_rows_mx4(m: np.ndarray):
+    """[rows, K] fp32 (K a multiple of 32) -> (codes uint8 [rows, K/2], scales uint8 [rows, K/32]) in
+    the OCP microscaling layout MXFP4: per block of 32 along K one power-of-two scale (E8M0 byte =
+    exponent + 127, chosen so that the block's largest magnitude lands in the top binade of the
+    4-bit element) and 32 E2M1 codes, nearest value, ties to the even code, saturating; two codes
+    per byte, even k in the low four bits.  Only makes up 4-bit expert weights for the benchmarks
+    and tests; any rounding would do."""
+    m = np.asarray(m, np.float64)
+    rows, K = m.shape
+    assert K % 32 == 0
+    blk = m.reshape(rows, K // 32, 32)
+    amax = np.abs(blk).max(axis=2)
+    exp = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 2.0, 0.0)
+    exp = np.clip(exp, -127, 127)
+    v = np.abs(blk) / np.exp2(exp)[:, :, None]
+    d = np.abs(v[..., None] - _E2M1_GRID)                      # distance to the 8 magnitudes
+    best = d.argmin(axis=3)                                    # first minimum = lower code
+    tie_up = (best < 7) & (np.take_along_axis(d, np.minimum(best + 1, 7)[..., None], 3)[..., 0]
+                           == np.take_along_axis(d, best[..., None], 3)[..., 0]) & (best % 2 == 1)
+    code = (best + tie_up).astype(np.uint8) | ((blk < 0).astype(np.uint8) << 3)
+    code = code.reshape(rows, K)
+    packed = (code[:, 0::2] | (code[:, 1::2] << 4)).astype(np.uint8)
+    return packed, (exp + 127).astype(np.uint8)
+
+
+def quantize_blob_mx4(w: np.ndarray, H: int, I: int) -> np.ndarray:
+    """[W_gate I*H | W_up I*H | W_down H*I] in fp32 -> the MXFP4 blob: the packed codes of the three
+    matrices in the same order, then their scales [gate I*H/32 | up I*H/32 | down H*I/32]."""
+    w = np.asarray(w, np.float32)
+    mats = [w[:I * H].reshape(I, H), w[I * H:2 * I * H].reshape(I, H), w[2 * I * H:].reshape(H, I)]
+    q = [quantize_rows_mx4(m) for m in mats]
+    return np.concatenate([c.ravel() for c, _ in q] + [s.ravel() for _, s in q])
 
 
 def as_f32(a: np.ndarray) -> np.ndarray:
@@ -175,6 +217,8 @@ def make_expert_blob(cfg: LayerConfig, seed: int, e: int, I: Optional[int] = Non
     w = _normal(seed, tid, (3 * cfg.H * I,), cfg.w_std)
     if cfg.dtype == "bf16w8":
         return quantize_blob_w8(w, cfg.H, I)
+    if cfg.dtype == "bf16mx4":
+        return quantize_blob_mx4(w, cfg.H, I)
     return _store(w, cfg.dtype)
 
 
