@@ -32,6 +32,10 @@
  *     expert weights are stored in 8 bits with one fp32 scale per weight row, which halves the
  *     bytes a decode step streams from HBM.  It needs H, I and every shared_I to be multiples
  *     of 16.
+ *     dtype MOE_BF16_MXFP4 (decode regime only, T < 256; not in the paper): as MOE_BF16, but
+ *     the expert weights are stored in the OCP microscaling format MXFP4 (4-bit elements with one
+ *     power-of-two scale per 32 weights along the contraction): 4.25 bits per weight.  It needs
+ *     H, I and every shared_I to be multiples of 32; moe_layer_decode does not take it.
  *   - Shape limits: H % 8 == 0, I % 8 == 0, every shared_I % 8 == 0, 1 <= k_little <= k_big
  *     <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS, n_shared <= MOE_MAX_SHARED,
  *     T * k_big < 2^31 / max(H, I).  Violations give MOE_E_SHAPE / MOE_E_UNSUPPORTED.
@@ -43,7 +47,14 @@
  *     "e4m3fn": 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities), followed by
  *     the fp32 row scales [ s_gate : I | s_up : I | s_down : H ];  W[r][k] = s[r] * e4m3(Q[r][k]).
  *     The codes are widened exactly to bf16, the products accumulate in fp32, and the row's scale
- *     multiplies the sum.  moe_expert_blob_bytes gives the size of a blob.
+ *     multiplies the sum.
+ *     MOE_BF16_MXFP4: the three matrices hold one E2M1 code per weight (1 sign, 2 exponent bits
+ *     with bias 1, 1 mantissa bit: 0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives), two per byte
+ *     with the weight of the even k in the low four bits, followed by the scales
+ *     [ S_gate : I x H/32 | S_up : I x H/32 | S_down : H x I/32 ], one E8M0 byte each (2^(b-127);
+ *     255 = NaN);  W[r][k] = e8m0(S[r][k/32]) * e2m1(Q[r][k]).  Code times scale is widened
+ *     exactly to bf16 (as long as it stays in bf16's range), the products accumulate in fp32.
+ *     moe_expert_blob_bytes gives the size of a blob.
  */
 #ifndef MOBILE_MOE_H_
 #define MOBILE_MOE_H_
@@ -59,7 +70,7 @@ extern "C" {
 #define MOE_MAX_EXPERTS 256
 #define MOE_MAX_TOPK 16
 
-enum { MOE_BF16 = 0, MOE_FP32 = 1, MOE_BF16_W8 = 2 };
+enum { MOE_BF16 = 0, MOE_FP32 = 1, MOE_BF16_W8 = 2, MOE_BF16_MXFP4 = 3 };
 
 enum {
   MOE_OK = 0,
@@ -82,7 +93,8 @@ typedef struct moe_config {
   int32_t n_shared; /* always-on shared experts (weight 1, every token); 0 = none           */
   int32_t shared_I[MOE_MAX_SHARED]; /* their intermediate sizes                             */
   int32_t dtype;    /* MOE_BF16 | MOE_FP32: storage of x, Wg, expert blobs, out;
-                       MOE_BF16_W8: bf16 x, Wg, out with 8-bit expert blobs                 */
+                       MOE_BF16_W8: bf16 x, Wg, out with 8-bit expert blobs;
+                       MOE_BF16_MXFP4: bf16 x, Wg, out with MXFP4 expert blobs               */
   int32_t renorm;   /* 0: routing weight = softmax over all E; 1: renormalised over the k_t
                        selected experts                                                     */
   float gamma;      /* fallback threshold of Alg. 1 (paper default 0.7)                     */

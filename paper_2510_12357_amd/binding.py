@@ -18,7 +18,7 @@ from .workloads import LayerConfig
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmobile_moe.so")
 
-MOE_BF16, MOE_FP32, MOE_BF16_W8 = 0, 1, 2
+MOE_BF16, MOE_FP32, MOE_BF16_W8, MOE_BF16_MXFP4 = 0, 1, 2, 3
 MOE_FETCH_DEMAND, MOE_FETCH_PREFETCH = 0, 1
 MOE_MAX_SHARED = 4
 MOE_OK = 0
@@ -153,7 +153,7 @@ def make_config(cfg: LayerConfig, T: Optional[int] = None) -> moe_config:
     c.n_shared = len(cfg.shared_I)
     for i, v in enumerate(cfg.shared_I):
         c.shared_I[i] = v
-    c.dtype = {"bf16": MOE_BF16, "fp32": MOE_FP32, "bf16w8": MOE_BF16_W8}[cfg.dtype]
+    c.dtype = {"bf16": MOE_BF16, "fp32": MOE_FP32, "bf16w8": MOE_BF16_W8, "bf16mx4": MOE_BF16_MXFP4}[cfg.dtype]
     c.renorm = int(cfg.renorm)
     c.gamma = cfg.gamma
     return c
@@ -454,7 +454,7 @@ class StepBuffers:
         self.fws = torch.empty((self.fws_bytes,), dtype=torch.uint8, device=device)
         self.ev_in, self.ev_shared = torch.cuda.Event(), torch.cuda.Event()
         # workspace of moe_layer_decode (steps of at most 64 tokens, bf16 activations), cleared once
-        self.lws_bytes = moe_layer_decode_workspace_bytes(self.c) if 0 < T <= 64 and cfg.dtype != "fp32" else 0
+        self.lws_bytes = moe_layer_decode_workspace_bytes(self.c) if 0 < T <= 64 and cfg.dtype in ("bf16", "bf16w8") else 0
         self.lws = None
         if self.lws_bytes:
             self.lws = torch.empty((self.lws_bytes,), dtype=torch.uint8, device=device)

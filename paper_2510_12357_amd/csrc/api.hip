@@ -80,7 +80,8 @@ constexpr int kW8MaxT = 256;
 
 int validate_config(const moe_config* c) {
   if (!c) return fail(MOE_E_BADARG, "config is NULL");
-  if (c->dtype != MOE_BF16 && c->dtype != MOE_FP32 && c->dtype != MOE_BF16_W8) return fail(MOE_E_BADARG, "dtype %d", c->dtype);
+  if (c->dtype != MOE_BF16 && c->dtype != MOE_FP32 && c->dtype != MOE_BF16_W8 && c->dtype != MOE_BF16_MXFP4)
+    return fail(MOE_E_BADARG, "dtype %d", c->dtype);
   if (c->T < 0 || c->H <= 0 || c->E <= 0 || c->I <= 0) return fail(MOE_E_SHAPE, "T=%d H=%d E=%d I=%d", c->T, c->H, c->E, c->I);
   if (c->k_little < 1 || c->k_little > c->k_big || c->k_big > c->E)
     return fail(MOE_E_SHAPE, "need 1 <= k_little (%d) <= k_big (%d) <= E (%d)", c->k_little, c->k_big, c->E);
@@ -109,6 +110,14 @@ int validate_config(const moe_config* c) {
     bool ok = c->H % 16 == 0 && c->I % 16 == 0;
     for (int s = 0; s < c->n_shared; ++s) ok = ok && c->shared_I[s] % 16 == 0;
     if (!ok) return fail(MOE_E_UNSUPPORTED, "8-bit expert weights need H, I and every shared_I to be multiples of 16");
+  }
+  if (c->dtype == MOE_BF16_MXFP4) {
+    if (c->T >= kW8MaxT)
+      return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights are for the decode regime: T=%d, limit %d", c->T, kW8MaxT - 1);
+    // a scale block is 32 weights along the contraction, and the kernel moves one block at a time
+    bool ok = c->H % 32 == 0 && c->I % 32 == 0;
+    for (int s = 0; s < c->n_shared; ++s) ok = ok && c->shared_I[s] % 32 == 0;
+    if (!ok) return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights need H, I and every shared_I to be multiples of 32");
   }
   if (!(c->gamma == c->gamma)) return fail(MOE_E_BADARG, "gamma is NaN");
   return MOE_OK;
@@ -366,6 +375,7 @@ int validate_decode(const moe_config* cfg) {
   int rc = validate_config(cfg);
   if (rc) return rc;
   if (cfg->dtype == MOE_FP32) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: bf16 activations only (use the separate calls for fp32)");
+  if (cfg->dtype == MOE_BF16_MXFP4) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: bf16 or 8-bit expert weights only (use the separate calls for MXFP4)");
   if (cfg->T > kDecodeMaxTokens) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: T=%d above %d tokens (use the separate calls)", cfg->T, kDecodeMaxTokens);
   if ((long long)cfg->T * cfg->k_big * cfg->H * 4 >= (1ll << 31)) return fail(MOE_E_UNSUPPORTED, "moe_layer_decode: y reaches 2 GiB");
   return MOE_OK;

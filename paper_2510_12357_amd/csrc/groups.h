@@ -48,8 +48,10 @@ struct Group {
   const void* w0;   // first weight matrix, already advanced to the K chunk
   const void* b;    // B rows, already advanced to the K chunk (and to row0 for routed kDown)
   void* out;        // h rows / y rows / slab base, already advanced to row0 where it applies
-  const float* scale;  // 8-bit weights only: fp32 scale of weight row n at scale[n] (gate/up: the
-                       // up rows' scales follow at scale[N + n]); unused otherwise
+  const void* scale;   // 8-bit weights: fp32 scale of weight row n at ((const float*)scale)[n] (gate/up:
+                       // the up rows' scales follow at [N + n]).  MXFP4: E8M0 byte of weight row n and
+                       // block j of this group's K at ((const uint8_t*)scale)[n * (ldw / 32) + j]
+                       // (gate/up: the up rows follow as rows N + n).  Unused otherwise.
 };
 
 // What resolving a group has to read from memory; the rest of a Group follows from the kernel
@@ -82,13 +84,18 @@ __device__ __forceinline__ GroupSrc load_group_src(const StreamArgs& a, int g) {
   return s;
 }
 
-// S: storage type of the activations (and of the router matrix); WB: bytes per expert weight
-// (sizeof(S), or 1 for 8-bit weights with the fp32 row scales [gate | up | down] behind the three
-// matrices of a blob).  ldw counts elements for both the weight rows and the B rows.
+// Bytes of n expert weights in format WB: WB bytes each, or half a byte for WB == 0 (MXFP4).
+template <int WB>
+__device__ __forceinline__ constexpr size_t w_bytes(size_t n) { return WB ? n * (size_t)WB : n / 2; }
+
+// S: storage type of the activations (and of the router matrix); WB: format of the expert weights:
+// bytes per weight (sizeof(S), or 1 for 8-bit codes with the fp32 row scales [gate | up | down]
+// behind the three matrices of a blob), or 0 for MXFP4 (two codes per byte, the block scales
+// [gate | up | down] behind the three matrices).  ldw counts elements for both the weight rows and
+// the B rows.
 template <typename S, int MODE, int WB = (int)sizeof(S)>
 __device__ __forceinline__ Group make_group(const StreamArgs& a, int g, const GroupSrc& src) {
   constexpr unsigned esz = sizeof(S);
-  constexpr unsigned wsz = (unsigned)WB;
   Group G;
   G.gather = 0; G.row0 = src.row0; G.m = src.m; G.scale = nullptr;
   const char* blob = static_cast<const char*>(src.blob);
@@ -103,38 +110,39 @@ __device__ __forceinline__ Group make_group(const StreamArgs& a, int g, const Gr
     int s = g, chunk = 0;
     if (MODE == kDown) { s = a.slab_shared[g]; chunk = a.slab_chunk[g]; }
     const int Is = a.shared_I[s];
-    const float* scales = reinterpret_cast<const float*>(blob + 3 * (size_t)Is * a.H * wsz);
+    const char* scales = blob + w_bytes<WB>(3 * (size_t)Is * a.H);
     if (MODE == kGateUp) {
       G.N = Is; G.K = a.H; G.ldw = a.H;
       G.w0 = blob; G.b = a.x; G.out = a.h_shared[s];
-      G.wbytes = 2u * Is * a.H * wsz; G.bbytes = (unsigned)a.T * a.H * esz;
+      G.wbytes = (unsigned)w_bytes<WB>(2 * (size_t)Is * a.H); G.bbytes = (unsigned)a.T * a.H * esz;
       G.scale = scales;
     } else {
       const int kb = chunk * a.shared_kchunk[s];
       G.N = a.H; G.K = min(a.shared_kchunk[s], Is - kb); G.ldw = Is;
-      G.w0 = blob + (2 * (size_t)Is * a.H + kb) * wsz;
+      G.w0 = blob + w_bytes<WB>(2 * (size_t)Is * a.H + kb);
       G.b = static_cast<const S*>(a.h_shared[s]) + kb;
       G.out = a.shared_out + (size_t)g * a.T * a.H;
-      G.wbytes = ((unsigned)a.H * Is - kb) * wsz; G.bbytes = ((unsigned)a.T * Is - kb) * esz;
-      G.scale = scales + 2 * (size_t)Is;
+      G.wbytes = (unsigned)w_bytes<WB>((size_t)a.H * Is - kb); G.bbytes = ((unsigned)a.T * Is - kb) * esz;
+      // the down scales follow the 2 Is gate and up rows: Is floats each (8-bit), H / 32 bytes each (MXFP4)
+      G.scale = WB ? scales + 4 * 2 * (size_t)Is : scales + 2 * (size_t)Is * (a.H / 32) + kb / 32;
     }
     return G;
   }
   const int b0 = src.row0;
-  const float* scales = reinterpret_cast<const float*>(blob + 3 * (size_t)a.I * a.H * wsz);
+  const char* scales = blob + w_bytes<WB>(3 * (size_t)a.I * a.H);
   if (MODE == kGateUp) {
     G.N = a.I; G.K = a.H; G.ldw = a.H; G.gather = 1;
     G.w0 = blob; G.b = a.x;
     G.out = static_cast<S*>(a.h_routed) + (size_t)b0 * a.I;
-    G.wbytes = 2u * a.I * a.H * wsz; G.bbytes = (unsigned)a.T * a.H * esz;
+    G.wbytes = (unsigned)w_bytes<WB>(2 * (size_t)a.I * a.H); G.bbytes = (unsigned)a.T * a.H * esz;
     G.scale = scales;
   } else {
     G.N = a.H; G.K = a.I; G.ldw = a.I;
-    G.w0 = blob + 2 * (size_t)a.I * a.H * wsz;
+    G.w0 = blob + w_bytes<WB>(2 * (size_t)a.I * a.H);
     G.b = static_cast<const S*>(a.h_routed) + (size_t)b0 * a.I;
     G.out = a.y + (size_t)b0 * a.H;
-    G.wbytes = (unsigned)a.H * a.I * wsz; G.bbytes = (unsigned)G.m * a.I * esz;
-    G.scale = scales + 2 * (size_t)a.I;
+    G.wbytes = (unsigned)w_bytes<WB>((size_t)a.H * a.I); G.bbytes = (unsigned)G.m * a.I * esz;
+    G.scale = WB ? scales + 4 * 2 * (size_t)a.I : scales + 2 * (size_t)a.I * (a.H / 32);
   }
   return G;
 }

@@ -33,10 +33,16 @@ int device_cu_count();
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 // bytes of an activation / router-matrix element, and of an expert weight
 inline size_t elem_bytes(int dtype) { return dtype == MOE_FP32 ? 4 : 2; }
-inline size_t weight_bytes(int dtype) { return dtype == MOE_FP32 ? 4 : (dtype == MOE_BF16_W8 ? 1 : 2); }
-// one expert: [W_gate I x H | W_up I x H | W_down H x I] (+ the fp32 row scales of 8-bit weights)
+// one expert: [W_gate I x H | W_up I x H | W_down H x I] (+ the fp32 row scales of 8-bit weights,
+// or the block scales of MXFP4 weights: one byte per 32 weights)
 inline size_t expert_blob_bytes(int dtype, int H, int I) {
-  return (size_t)3 * H * I * weight_bytes(dtype) + (dtype == MOE_BF16_W8 ? (size_t)4 * (2 * (size_t)I + H) : 0);
+  const size_t n = (size_t)3 * H * I;
+  switch (dtype) {
+    case MOE_FP32: return n * 4;
+    case MOE_BF16_W8: return n + (size_t)4 * (2 * (size_t)I + H);
+    case MOE_BF16_MXFP4: return n / 2 + n / 32;
+    default: return n * 2;
+  }
 }
 
 // ---- skinny grouped GEMM  D[r][n] = sum_k W[n][k] * B[r][k]  (weights streamed once) --------
@@ -82,7 +88,8 @@ struct StreamArgs {
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s);
 // kGateUp / kDown on bf16 activations with the weights (2 bytes: bf16, 1 byte: E4M3 + row
 // scales) streamed through an LDS ring (stream_lds.hip)
-int launch_stream_lds(StreamMode mode, int weight_bytes, const StreamArgs& a, hipStream_t s);
+// weight_format: 2 = bf16, 1 = 8-bit codes with row scales, 0 = MXFP4
+int launch_stream_lds(StreamMode mode, int weight_format, const StreamArgs& a, hipStream_t s);
 
 // ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime, bf16) -------------------------
 int launch_tiled(StreamMode mode, const StreamArgs& a, hipStream_t s);

@@ -410,10 +410,10 @@ int launch_typed(const StreamArgs& a, hipStream_t s) {
 }  // namespace
 
 int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s) {
-  if (dtype == MOE_BF16_W8) {
+  if (dtype == MOE_BF16_W8 || dtype == MOE_BF16_MXFP4) {
     // the router matrix of such a layer is bf16; its expert weights exist for the LDS kernel only
     if (mode == kRouter) return launch_typed<BF16, kRouter, 4>(a, s);
-    return launch_stream_lds(mode, 1, a, s);
+    return launch_stream_lds(mode, dtype == MOE_BF16_W8 ? 1 : 0, a, s);
   }
   if (dtype == MOE_BF16) {
     // the bf16 expert GEMMs stream through LDS (stream_lds.hip); this file's kernel serves the

@@ -40,6 +40,11 @@
 //     inside a chunk is permuted accordingly, and the token rows are loaded with the same
 //     permutation.  The computers widen the codes to bf16 (exact: 3 mantissa bits) in front of
 //     the MFMAs, and the row scale multiplies the fp32 sum in the epilogue.
+//   * MXFP4 weights (WB = 0: OCP microscaling, 4-bit E2M1 codes with one E8M0 scale per 32 k):
+//     1024 k per chunk; a 16-byte column holds the 32 codes of one scale block, i.e. the weights
+//     of four MFMA k-steps, with the k order inside a chunk permuted accordingly.  The computers
+//     load the scale byte of every (row, block) they read along with the token rows and widen
+//     code x scale to bf16 in one instruction (exact) in front of the MFMAs.
 #include <atomic>
 #include <type_traits>
 
@@ -64,6 +69,14 @@ constexpr int kThreadsL = 2 * kWorkers * 64;
 constexpr int kTok = 32;                     // token rows per item, at most (two tiles of 16)
 constexpr int kKParts = 2;                   // worker waves that split the k-steps of one token tile
 constexpr int kReads = kRowBytes / 16 / 4 / kKParts;   // fragment reads (16-byte columns) per worker, row tile and chunk
+
+// Weight formats (template parameter WB): 2 = bf16, 1 = 8-bit codes, 0 = MXFP4 (half a byte).
+template <int WB> struct Fmt {
+  static constexpr int kPerChunk = WB ? kRowBytes / WB : kRowBytes * 2;   // k per chunk (512-byte row)
+  static constexpr int kPerColumn = WB ? 16 / WB : 32;                    // k per 16-byte column
+  static constexpr int kSteps = kPerColumn / 8;                           // MFMA k-steps fed by one column
+  static __device__ __forceinline__ unsigned row_bytes(int k) { return WB ? (unsigned)k * WB : (unsigned)k / 2u; }
+};
 
 // vmcnt(n): bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima (no wait)
 #define MM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
@@ -92,7 +105,7 @@ struct Item {
   int gather, row0;
   unsigned ldwb;    // bytes between rows of W
   unsigned ldbb;    // bytes between rows of B
-  const float* scale;   // 8-bit weights: row scales of the group (see Group::scale)
+  const void* scale;    // 8-bit weights: row scales of the group; MXFP4: its block scales (see Group::scale)
   unsigned wbytes, bbytes;
   const void* w0;
   const void* b;
@@ -119,7 +132,7 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   GroupSrc src = s_src[g];
   src.m = uni(src.m); src.row0 = uni(src.row0); src.blob = uni(src.blob);
   const Group G = make_group<uint16_t, MODE, WB>(a, g, src);
-  constexpr int KC = kRowBytes / WB;
+  constexpr int KC = Fmt<WB>::kPerChunk;
   // Items of a group, in blocks of 8 row tiles: all token blocks of row tile (8 b + i) are
   // 8 items apart, i.e. they run at the same time on workgroups of the same XCD.
   const int local = item - uni(s_prefix[g]);
@@ -141,7 +154,7 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   it.nch = (it.K + KC - 1) / KC;
   it.ntn = clampi((it.m - it.r0 + 15) >> 4, 1, kTok / 16);
   it.gather = G.gather; it.row0 = G.row0;
-  it.ldwb = (unsigned)G.ldw * (unsigned)WB;
+  it.ldwb = Fmt<WB>::row_bytes(G.ldw);
   it.ldbb = (unsigned)G.ldw * 2u;
   it.scale = G.scale;
   // an item that does not exist keeps valid pointers and empty buffers: every load is out of range
@@ -186,10 +199,25 @@ __device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
   return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
 }
 
+// 8 E2M1 codes (one dword, k ascending with the nibble address) times the block scale (a power of
+// two as fp32) -> 8 bf16, exactly while the products stay in bf16's range.
+__device__ __forceinline__ bf16x8 widen_mx4(int codes, float scale) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 0);
+  const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 1);
+  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 2);
+  const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 3);
+  return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+// An E8M0 byte as fp32: 2^(b - 127); 0 is the subnormal 2^-127, 255 is NaN.
+__device__ __forceinline__ float e8m0_to_f32(unsigned b) {
+  return __uint_as_float(b == 0 ? 0x00400000u : (b == 255 ? 0x7fc00000u : b << 23));
+}
+
 template <int MODE, int WB>
 __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4))) void stream_lds_kernel(const StreamArgs a) {
-  constexpr int KC = kRowBytes / WB;         // k per chunk
-  constexpr int kHalves = 2 / WB;            // MFMA k-steps fed by one 16-byte column: 1 (bf16) or 2 (8-bit)
+  constexpr int KC = Fmt<WB>::kPerChunk;     // k per chunk
+  constexpr int kHalves = Fmt<WB>::kSteps;   // MFMA k-steps fed by one 16-byte column: 1 (bf16), 2 (8-bit), 4 (MXFP4)
   // One LDS object, ring first (1 KB aligned: every load instruction fills one aligned KB).
   __shared__ __attribute__((aligned(1024))) Smem sm;
   char* const s_ring = sm.ring;
@@ -258,7 +286,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
         // last, partial chunk, or no chunk: lanes out of range fill their part of the stage with zeros
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int kk = k * KC + (int)a_col[i] * (16 / WB);
+          const int kk = k * KC + (int)a_col[i] * Fmt<WB>::kPerColumn;
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16,
                                                    (int)((real && kk < it.K) ? addr[i] : kOob), 0, 0, 0);
         }
@@ -308,7 +336,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     for (int rt = 0; rt < 2; ++rt) {
       const int n = (MODE == kGateUp) ? it.n0 + 4 * q : it.n0 + rt * 16 + 4 * q;
       const bool ok = it.valid && n < it.N;                 // N is a multiple of 16: all four or none
-      const float* p = it.scale + ((MODE == kGateUp && rt == 1) ? it.N + n : n);
+      const float* p = static_cast<const float*>(it.scale) + ((MODE == kGateUp && rt == 1) ? it.N + n : n);
       sc[rt] = ok ? *reinterpret_cast<const f32x4*>(p) : f32x4{0, 0, 0, 0};
     }
   };
@@ -325,6 +353,11 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   for (int t = 0; t < kReads; ++t)
 #pragma unroll
     for (int h = 0; h < kHalves; ++h) bbuf[t][h] = i32x4{0, 0, 0, 0};
+  unsigned sbuf[2][kReads];         // MXFP4: scale byte of this lane's block per row tile and read
+#pragma unroll
+  for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+    for (int t = 0; t < kReads; ++t) sbuf[rt][t] = 127u;
   f32x4 acc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
 
   // Scale (8-bit weights), activate and store this lane's 2 x 4 sums of the item that ended.
@@ -392,13 +425,22 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
         const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][0]);
         acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
         acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
-      } else {
+      } else if (WB == 1) {
         const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
 #pragma unroll
         for (int h = 0; h < kHalves; ++h) {
           const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
           acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w0[2 * h], w0[2 * h + 1]), bv, acc[0], 0, 0, 0);
           acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w1[2 * h], w1[2 * h + 1]), bv, acc[1], 0, 0, 0);
+        }
+      } else {
+        const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
+        const float s0 = e8m0_to_f32(sbuf[0][t]), s1 = e8m0_to_f32(sbuf[1][t]);
+#pragma unroll
+        for (int h = 0; h < kHalves; ++h) {
+          const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
+          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_mx4(w0[h], s0), bv, acc[0], 0, 0, 0);
+          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_mx4(w1[h], s1), bv, acc[1], 0, 0, 0);
         }
       }
     }
@@ -415,10 +457,28 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
 #pragma unroll
       for (int h = 0; h < kHalves; ++h) {
         // the k behind 16-byte column (kp + 2t) * 4 + q of the weight rows (second half: h = 1)
-        const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * (16 / WB) + h * 8;
+        const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * Fmt<WB>::kPerColumn + h * 8;
         const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
         bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
       }
+    if (WB == 0) {
+      // the scale bytes of the blocks this lane reads in that chunk: weight rows n0 + 16 rt + c16
+      // (gate/up: gate row n0 + c16 and the same up row), block (chunk's first block) + column;
+      // rows and blocks that do not exist read as 0 (out-of-range offset), their codes are zeros
+      const __amdgpu_buffer_rsrc_t rsc = make_rsrc(cur.scale, 0x7fffffffu);
+      const unsigned per_row = (unsigned)cur.ldwb >> 4;           // bytes of a weight row / 16 = its blocks of 32 codes
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        const int n = (MODE == kGateUp) ? cur.n0 + c16 : cur.n0 + rt * 16 + c16;
+        const unsigned row = (MODE == kGateUp && rt == 1) ? (unsigned)(cur.N + n) : (unsigned)n;
+#pragma unroll
+        for (int t = 0; t < kReads; ++t) {
+          const int blk = k * (KC / 32) + (kp + t * kKParts) * 4 + q;
+          const bool ok = cur.valid && n < cur.N && blk * 32 < cur.K;
+          sbuf[rt][t] = (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsc, (int)(ok ? row * per_row + (unsigned)blk : kOob), 0, 0);
+        }
+      }
+    }
   };
 
   // One iteration.
@@ -479,15 +539,18 @@ int launch_lds_typed(const StreamArgs& a, hipStream_t s) {
 
 }  // namespace
 
-int launch_stream_lds(StreamMode mode, int weight_bytes, const StreamArgs& a, hipStream_t s) {
-  if (weight_bytes == 2) {
+int launch_stream_lds(StreamMode mode, int weight_format, const StreamArgs& a, hipStream_t s) {
+  if (weight_format == 2) {
     if (mode == kGateUp) return launch_lds_typed<kGateUp, 2>(a, s);
     if (mode == kDown) return launch_lds_typed<kDown, 2>(a, s);
-  } else if (weight_bytes == 1) {
+  } else if (weight_format == 1) {
     if (mode == kGateUp) return launch_lds_typed<kGateUp, 1>(a, s);
     if (mode == kDown) return launch_lds_typed<kDown, 1>(a, s);
+  } else if (weight_format == 0) {
+    if (mode == kGateUp) return launch_lds_typed<kGateUp, 0>(a, s);
+    if (mode == kDown) return launch_lds_typed<kDown, 0>(a, s);
   }
-  return fail(MOE_E_BADARG, "bad stream mode / weight width");
+  return fail(MOE_E_BADARG, "bad stream mode / weight format");
 }
 
 }  // namespace mm

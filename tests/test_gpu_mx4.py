@@ -1,0 +1,91 @@
+"""Expert weights in MXFP4 (E2M1 codes with one E8M0 scale per 32 weights along the contraction,
+bf16 activations) on the GPU against the oracle, through the same C-ABI calls as the bf16 layer."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_12357_amd import binding as mm
+from paper_2510_12357_amd import workloads as wl
+from gpu_util import TOL_OUT, DeviceLayer, out_to_f64, rel_err, run_gpu_layer, run_oracle_layer
+from test_gpu_parity import check_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def cfg_mx(**kw):
+    # several row tiles with a ragged last one, K with a partial last chunk, E not a multiple of 16
+    base = dict(name="mx4_small", T=37, H=288, E=10, I=160, k_big=4, k_little=2, shared_I=(96,),
+                dtype="bf16mx4", gate_std=0.3, w_std=0.1, gate_bias_std=0.5)
+    base.update(kw)
+    return wl.LayerConfig(**base)
+
+
+@pytest.mark.parametrize("r", [0.0, 0.3, 1.0])
+def test_small_ragged_layer(r):
+    check_layer(cfg_mx(fallback_ratio=r), seed=1)
+
+
+def test_long_contractions_and_many_token_blocks():
+    # K beyond one 1024-wide chunk in both projections, several token blocks per expert
+    check_layer(cfg_mx(T=200, H=2080, E=4, I=1312, k_big=3, k_little=1, shared_I=(2400, 64)), seed=2)
+    check_layer(cfg_mx(T=97, H=512, E=6, I=1024, k_big=4, k_little=2, shared_I=()), seed=3)
+
+
+@pytest.mark.parametrize("T", [1, 8, 64])
+def test_fine60_decode_full_size(T):
+    check_layer(wl.CONFIGS["fine60_decode"].with_(T=T, dtype="bf16mx4"), seed=0)
+
+
+def test_every_code_and_a_range_of_scales_reach_the_sum():
+    """One expert whose W_gate rows hold all 16 codes in every position of a block, under block
+    scales from 2^-20 to 2^6: the layer output equals the oracle's, i.e. the kernel's widening agrees
+    with the format for every code, and its scales sit with the right rows and blocks."""
+    cfg = cfg_mx(T=16, H=256, E=2, I=32, k_big=1, k_little=1, shared_I=())
+    layer = wl.make_layer(cfg, seed=5)
+    HI = cfg.H * cfg.I
+    for e in range(cfg.E):
+        b = layer.expert_w[e]
+        codes = (np.arange(cfg.I * cfg.H).reshape(cfg.I, cfg.H) * 7 + np.arange(cfg.I)[:, None] * 3 + e) % 16
+        b[:HI // 2] = (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8).ravel()
+        # the gate scales: a different power of two per (row, block), small enough that silu(g) * u
+        # stays in a range where bf16 storage of h is harmless
+        sc = b[3 * HI // 2:3 * HI // 2 + HI // 32].reshape(cfg.I, cfg.H // 32)
+        sc[:] = (107 + (np.arange(cfg.I)[:, None] * 5 + np.arange(cfg.H // 32)[None, :] * 3 + e) % 27).astype(np.uint8)
+    dl = DeviceLayer(layer)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    b = run_gpu_layer(dl, conf=dl.conf, logits=logits)
+    ref = run_oracle_layer(layer, logits=logits)
+    assert rel_err(b.y[:int(ref["expert_offsets"][-1])].cpu().numpy(), ref["y"]) <= TOL_OUT
+    assert rel_err(out_to_f64(b.out), ref["out"]) <= TOL_OUT
+
+
+def test_little_pass_then_fallback_pass():
+    cfg = cfg_mx(T=48, shared_I=(96,))
+    layer = wl.make_layer(cfg, seed=8)
+    dl = DeviceLayer(layer)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    b = mm.StepBuffers(cfg)
+    b.logits.copy_(torch.from_numpy(logits))
+    ones = torch.full((cfg.T,), 2.0, device="cuda")
+    mm.layer_step(b, dl.x, dl.Wg, dl.gate_bias, ones, dl.table, dl.shared, logits_given=True)
+    mm.fallback_step(b, dl.x, dl.conf, dl.table)
+    torch.cuda.synchronize()
+    ref = run_oracle_layer(layer, logits=logits)
+    assert rel_err(out_to_f64(b.out), ref["out"]) <= TOL_OUT
+
+
+def test_limits_and_blob_size():
+    cfg = cfg_mx()
+    c = mm.make_config(cfg)
+    assert mm.moe_expert_blob_bytes(c, cfg.I) == wl.mx4_blob_bytes(cfg.H, cfg.I) == wl.make_expert_blob(cfg, 0, 0).size
+    assert mm.moe_expert_blob_bytes(c, cfg.shared_I[0]) == wl.mx4_blob_bytes(cfg.H, cfg.shared_I[0])
+    lib = mm.load_library()
+    for bad in (cfg.with_(T=256), cfg.with_(H=272), cfg.with_(I=144), cfg.with_(shared_I=(80,))):
+        cb = mm.make_config(bad)
+        rc = lib.moe_combine(ctypes.byref(cb), None, None, None, None, None, None, None)
+        assert rc == -3, (bad, rc)
+    # the one-launch decode step does not take the format
+    assert mm.StepBuffers(cfg.with_(T=8)).lws is None
