@@ -60,6 +60,8 @@ def workload_config(name: str, ratio: float):
     from paper_2510_12357_amd import workloads as wl
     if name.startswith("fine60_decode_b") and name.endswith("_w8"):     # expert weights in 8 bits (not in the paper)
         return wl.CONFIGS["fine60_decode"].with_(T=int(name[:-3].split("_b")[1]), fallback_ratio=ratio, dtype="bf16w8")
+    if name.startswith("fine60_decode_b") and name.endswith("_mx4"):    # expert weights in MXFP4 (not in the paper)
+        return wl.CONFIGS["fine60_decode"].with_(T=int(name[:-4].split("_b")[1]), fallback_ratio=ratio, dtype="bf16mx4")
     if name.startswith("fine60_decode_b"):
         return wl.CONFIGS["fine60_decode"].with_(T=int(name.split("_b")[1]), fallback_ratio=ratio)
     if name == "fine64_prefill":
@@ -78,6 +80,12 @@ def workload_config(name: str, ratio: float):
 def random_blob(torch, g, cfg, I: int):
     """One expert blob on the device: random weights in the layer's storage type; 8-bit blobs are E4M3
     codes (torch's float8_e4m3fn cast) followed by the fp32 row scales that map a row's peak to 448."""
+    if cfg.dtype == "bf16mx4":
+        # MXFP4: random codes, block scales 2^-9 .. 2^-6 (weights of the usual size); timing input only
+        n = 3 * cfg.H * I
+        codes = torch.randint(0, 256, (n // 2,), generator=g, device="cuda", dtype=torch.int32).to(torch.uint8)
+        scales = torch.randint(118, 122, (n // 32,), generator=g, device="cuda", dtype=torch.int32).to(torch.uint8)
+        return torch.cat([codes, scales])
     w = torch.randn((3 * cfg.H * I,), generator=g, device="cuda", dtype=torch.float32) * cfg.w_std
     if cfg.dtype != "bf16w8":
         return w.to(torch.float32 if cfg.dtype == "fp32" else torch.bfloat16)
@@ -99,8 +107,9 @@ class DeviceLayers:
         g = torch.Generator(device="cuda")
         g.manual_seed(seed)
         dt = torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
-        w8 = cfg.dtype == "bf16w8"
-        blob = wl.w8_blob_bytes(cfg.H, cfg.I) if w8 else 3 * cfg.H * cfg.I
+        w8 = cfg.dtype in ("bf16w8", "bf16mx4")          # byte blobs
+        blob = (wl.w8_blob_bytes(cfg.H, cfg.I) if cfg.dtype == "bf16w8" else
+                wl.mx4_blob_bytes(cfg.H, cfg.I) if cfg.dtype == "bf16mx4" else 3 * cfg.H * cfg.I)
 
         def randn(shape, std):
             return (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * std).to(dt)
@@ -129,8 +138,12 @@ class DeviceLayers:
     def bytes_per_layer(self) -> int:
         c = self.cfg
         eb = 4 if c.dtype == "fp32" else 2
-        wb = {"fp32": 4, "bf16": 2, "bf16w8": 1}[c.dtype]
+        wb = WEIGHT_BYTES[c.dtype]
         return wb * (c.E * 3 * c.H * c.I + sum(3 * c.H * i for i in c.shared_I)) + eb * c.E * c.H
+
+
+# bytes per expert weight; MXFP4: half a byte per code + one scale byte per 32
+WEIGHT_BYTES = {"fp32": 4, "bf16": 2, "bf16w8": 1, "bf16mx4": 0.5 + 1.0 / 32}
 
 
 def eq1(T: float, T_l: float, T_b: float, r: float) -> float:
@@ -139,7 +152,7 @@ def eq1(T: float, T_l: float, T_b: float, r: float) -> float:
 
 
 def auto_layers(cfg) -> int:
-    wb = {"fp32": 4, "bf16": 2, "bf16w8": 1}[cfg.dtype]
+    wb = WEIGHT_BYTES[cfg.dtype]
     per = wb * (cfg.E * 3 * cfg.H * cfg.I + sum(3 * cfg.H * i for i in cfg.shared_I))
     # enough distinct weights that a layer is evicted from the 256 MB last-level cache before
     # it is reused, within a budget of ~12 GB
@@ -677,7 +690,7 @@ def algorithmic_work(cfg, P: float, D: float):
     """Bytes and flops one step must move / do (weights of the D touched experts once, the shared
     experts, the router, activations in and out; flops of the P pair FFNs, shared FFNs, router)."""
     eb = 4 if cfg.dtype == "fp32" else 2                              # activations, router matrix
-    wb = {"fp32": 4, "bf16": 2, "bf16w8": 1}[cfg.dtype]                # expert weights (row scales not counted)
+    wb = WEIGHT_BYTES[cfg.dtype]                                       # expert weights (8-bit row scales not counted)
     H, I, T, E = cfg.H, cfg.I, cfg.T, cfg.E
     sh = sum(cfg.shared_I)
     step_bytes = wb * (D * 3 * H * I + 3 * H * sh) + eb * E * H + 2 * eb * T * H
@@ -920,7 +933,8 @@ def main():
         k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 2)
         names = [n for n in ("fine60_decode_b1", "fine60_decode_b8", "fine60_decode_b32", "fine60_decode_b64",
                              "fine64_prefill", "coarse8_prefill", "coarse8_decode_b1", "tiny_fp32",
-                             "fine60_decode_b1_w8", "fine60_decode_b64_w8") if n != args.workload]
+                             "fine60_decode_b1_w8", "fine60_decode_b64_w8", "fine60_decode_b1_mx4",
+                             "fine60_decode_b64_mx4") if n != args.workload]
         for name in names:
             c2 = workload_config(name, args.ratio)
             r2 = time_workload(mm, torch, c2, k2, w2)

@@ -35,7 +35,7 @@
  *     dtype MOE_BF16_MXFP4 (decode regime only, T < 256; not in the paper): as MOE_BF16, but
  *     the expert weights are stored in the OCP microscaling format MXFP4 (4-bit elements with one
  *     power-of-two scale per 32 weights along the contraction): 4.25 bits per weight.  It needs
- *     H, I and every shared_I to be multiples of 32; moe_layer_decode does not take it.
+ *     H, I and every shared_I to be multiples of 128; moe_layer_decode does not take it.
  *   - Shape limits: H % 8 == 0, I % 8 == 0, every shared_I % 8 == 0, 1 <= k_little <= k_big
  *     <= min(E, MOE_MAX_TOPK), E <= MOE_MAX_EXPERTS, n_shared <= MOE_MAX_SHARED,
  *     T * k_big < 2^31 / max(H, I).  Violations give MOE_E_SHAPE / MOE_E_UNSUPPORTED.

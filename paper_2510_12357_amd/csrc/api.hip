@@ -114,10 +114,11 @@ int validate_config(const moe_config* c) {
   if (c->dtype == MOE_BF16_MXFP4) {
     if (c->T >= kW8MaxT)
       return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights are for the decode regime: T=%d, limit %d", c->T, kW8MaxT - 1);
-    // a scale block is 32 weights along the contraction, and the kernel moves one block at a time
-    bool ok = c->H % 32 == 0 && c->I % 32 == 0;
-    for (int s = 0; s < c->n_shared; ++s) ok = ok && c->shared_I[s] % 32 == 0;
-    if (!ok) return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights need H, I and every shared_I to be multiples of 32");
+    // a scale block is 32 weights along the contraction; the kernel fetches the scale bytes of a
+    // row 16 at a time with 4-byte aligned loads, so a row must hold a multiple of 4 of them
+    bool ok = c->H % 128 == 0 && c->I % 128 == 0;
+    for (int s = 0; s < c->n_shared; ++s) ok = ok && c->shared_I[s] % 128 == 0;
+    if (!ok) return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights need H, I and every shared_I to be multiples of 128");
   }
   if (!(c->gamma == c->gamma)) return fail(MOE_E_BADARG, "gamma is NaN");
   return MOE_OK;
@@ -130,7 +131,10 @@ SlabPlan slab_plan(const moe_config& c) {
     const int Is = c.shared_I[s];
     int n = (Is + target - 1) / target;
     if (n > kMaxKSplit) n = kMaxKSplit;
-    int chunk = ((Is + n - 1) / n + 31) / 32 * 32;
+    // MXFP4: a chunk starts on a multiple of 128 weights, so that the scale bytes of a row (one
+    // per 32 weights) stay 4-byte aligned behind it
+    const int round = c.dtype == MOE_BF16_MXFP4 ? 128 : 32;
+    int chunk = ((Is + n - 1) / n + round - 1) / round * round;
     n = (Is + chunk - 1) / chunk;
     P.kchunk[s] = chunk;
     for (int k = 0; k < n; ++k) {

@@ -42,9 +42,11 @@
 //     the MFMAs, and the row scale multiplies the fp32 sum in the epilogue.
 //   * MXFP4 weights (WB = 0: OCP microscaling, 4-bit E2M1 codes with one E8M0 scale per 32 k):
 //     1024 k per chunk; a 16-byte column holds the 32 codes of one scale block, i.e. the weights
-//     of four MFMA k-steps, with the k order inside a chunk permuted accordingly.  The computers
-//     load the scale byte of every (row, block) they read along with the token rows and widen
-//     code x scale to bf16 in one instruction (exact) in front of the MFMAs.
+//     of four MFMA k-steps, with the k order inside a chunk permuted accordingly.  The scale
+//     bytes of a chunk (32 rows x 32 blocks = 1 KB) are fetched by one computer wave with one
+//     load instruction, one chunk ahead, and handed to the others through a double-buffered KB
+//     of LDS (byte loads from global memory by every lane cost more than the weight stream);
+//     code x scale is widened to bf16 in one instruction (exact) in front of the MFMAs.
 #include <atomic>
 #include <type_traits>
 
@@ -60,21 +62,29 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((address_space(3))) void lds_void;
 
-constexpr int kRowBytes = 512;               // bytes of one weight row per chunk: 256 k in bf16, 512 k in 8 bits
-constexpr int kRows = 32;                    // weight rows per item
-constexpr int kStageBytes = kRows * kRowBytes;
+constexpr int kStageBytes = 16384;           // one stage of the ring = one chunk of an item: rows x bytes per row
 constexpr int kStages = 4;
 constexpr int kWorkers = 4;                  // loader waves = computer waves
 constexpr int kThreadsL = 2 * kWorkers * 64;
 constexpr int kTok = 32;                     // token rows per item, at most (two tiles of 16)
 constexpr int kKParts = 2;                   // worker waves that split the k-steps of one token tile
-constexpr int kReads = kRowBytes / 16 / 4 / kKParts;   // fragment reads (16-byte columns) per worker, row tile and chunk
 
-// Weight formats (template parameter WB): 2 = bf16, 1 = 8-bit codes, 0 = MXFP4 (half a byte).
+// Weight formats (template parameter WB): 2 = bf16, 1 = 8-bit codes, 0 = MXFP4 (half a byte), and
+// the shape of a stage that goes with them.  The fewer bytes a weight has, the more k a row of
+// given bytes covers, and every 8 k of a token tile cost the computers one load of token rows
+// whatever the weights weigh; MXFP4 therefore takes items of 64 rows x 256 bytes (512 k) instead
+// of 32 rows x 512 bytes, which halves the token-row loads per weight byte.
 template <int WB> struct Fmt {
-  static constexpr int kPerChunk = WB ? kRowBytes / WB : kRowBytes * 2;   // k per chunk (512-byte row)
-  static constexpr int kPerColumn = WB ? 16 / WB : 32;                    // k per 16-byte column
-  static constexpr int kSteps = kPerColumn / 8;                           // MFMA k-steps fed by one column
+  static constexpr int kRows = WB == 0 ? 64 : 32;                 // weight rows per item
+  static constexpr int kRowBytes = kStageBytes / kRows;           // bytes of one weight row per chunk
+  static constexpr int kTiles = kRows / 16;                       // MFMA row tiles per item
+  static constexpr int kCols = kRowBytes / 16;                    // 16-byte columns of a row in a stage
+  static constexpr int kRowsPerIns = 1024 / kRowBytes;            // rows one load instruction fills
+  static constexpr int kReads = kCols / 4 / kKParts;              // fragment reads per worker, row tile and chunk
+  static constexpr int kPerColumn = WB ? 16 / WB : 32;            // k per 16-byte column
+  static constexpr int kPerChunk = kCols * kPerColumn;            // k per chunk
+  static constexpr int kSteps = kPerColumn / 8;                   // MFMA k-steps fed by one column
+  static constexpr int kOutRows = kRows;                          // output rows per down item; gate/up: half
   static __device__ __forceinline__ unsigned row_bytes(int k) { return WB ? (unsigned)k * WB : (unsigned)k / 2u; }
 };
 
@@ -106,6 +116,7 @@ struct Item {
   unsigned ldwb;    // bytes between rows of W
   unsigned ldbb;    // bytes between rows of B
   const void* scale;    // 8-bit weights: row scales of the group; MXFP4: its block scales (see Group::scale)
+  unsigned sbytes;      // MXFP4: bytes readable from scale
   unsigned wbytes, bbytes;
   const void* w0;
   const void* b;
@@ -136,7 +147,7 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   // Items of a group, in blocks of 8 row tiles: all token blocks of row tile (8 b + i) are
   // 8 items apart, i.e. they run at the same time on workgroups of the same XCD.
   const int local = item - uni(s_prefix[g]);
-  const int per = MODE == kGateUp ? 16 : 32;
+  constexpr int per = MODE == kGateUp ? Fmt<WB>::kRows / 2 : Fmt<WB>::kRows;
   const int rows = (G.N + per - 1) / per;
   const int tgs = max(1, (G.m + kTok - 1) / kTok);
   int tg = 0, row_item = local;     // one token block (the usual case at decode): nothing to divide
@@ -157,17 +168,19 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   it.ldwb = Fmt<WB>::row_bytes(G.ldw);
   it.ldbb = (unsigned)G.ldw * 2u;
   it.scale = G.scale;
+  // MXFP4: the scale rows of the group (gate and up for gate/up) end with the last row's last block
+  it.sbytes = (WB == 0 && it.valid) ? (unsigned)((MODE == kGateUp ? 2 : 1) * G.N - 1) * ((unsigned)G.ldw >> 5) + ((unsigned)G.K >> 5) : 0u;
   // an item that does not exist keeps valid pointers and empty buffers: every load is out of range
   it.wbytes = it.valid ? G.wbytes : 0u; it.bbytes = it.valid ? G.bbytes : 0u;
   it.w0 = it.valid ? G.w0 : a.x; it.b = it.valid ? G.b : a.x; it.out = G.out;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int row_local = 2 * ((wave % kWorkers) * 4 + i) + (lane >> 5);
+    const int row_local = Fmt<WB>::kRowsPerIns * ((wave % kWorkers) * 4 + i) + lane / Fmt<WB>::kCols;
     unsigned off;
     int n;
-    if (MODE == kGateUp) {
-      n = it.n0 + (row_local & 15);
-      off = (unsigned)n * it.ldwb + ((row_local >> 4) ? (unsigned)G.N * it.ldwb : 0u);   // W_up follows W_gate
+    if (MODE == kGateUp) {       // the first half of an item's rows are gate rows, the second half the same up rows
+      n = it.n0 + (row_local % per);
+      off = (unsigned)n * it.ldwb + ((row_local >= per) ? (unsigned)G.N * it.ldwb : 0u);   // W_up follows W_gate
     } else {
       n = it.n0 + row_local;
       off = (unsigned)n * it.ldwb;
@@ -185,11 +198,18 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
 }
 
 
+template <int WB>
 struct Smem {
   char ring[kStages * kStageBytes];
-  float red[kWorkers][2][4][64];       // K-split partial sums; the item counts during set-up
+  // K-split partial sums (the item counts during set-up).  Two row tiles: every computer writes its
+  // sums; four row tiles: only the computers of the second k part do, the others add their own
+  float red[Fmt<WB>::kTiles > 2 ? 2 : kWorkers][Fmt<WB>::kTiles][4][64];
   GroupSrc src[kMaxGroups];
   int prefix[kMaxGroups + 1];
+  // MXFP4: the scale bytes of the chunk being consumed, double-buffered by iteration parity:
+  // [row of the item][kp][q][t] for block (kp + 2 t) * 4 + q of the chunk, so that the bytes a
+  // computing lane needs for one row sit side by side
+  unsigned char mx_scale[WB == 0 ? 2 : 1][WB == 0 ? Fmt<WB>::kRows * Fmt<WB>::kCols : 16];
 };
 
 // 8 E4M3 codes (two dwords, k ascending with the byte address) -> 8 bf16, exactly.
@@ -216,12 +236,15 @@ __device__ __forceinline__ float e8m0_to_f32(unsigned b) {
 
 template <int MODE, int WB>
 __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4))) void stream_lds_kernel(const StreamArgs a) {
-  constexpr int KC = Fmt<WB>::kPerChunk;     // k per chunk
-  constexpr int kHalves = Fmt<WB>::kSteps;   // MFMA k-steps fed by one 16-byte column: 1 (bf16), 2 (8-bit), 4 (MXFP4)
+  typedef Fmt<WB> F;
+  constexpr int KC = F::kPerChunk;           // k per chunk
+  constexpr int kHalves = F::kSteps;         // MFMA k-steps fed by one 16-byte column: 1 (bf16), 2 (8-bit), 4 (MXFP4)
+  constexpr int kTiles = F::kTiles, kReads = F::kReads, kRowBytes = F::kRowBytes;
+  constexpr bool kOwnSums = kTiles > 2;      // the computers of k part 0 add their own sums to those of part 1
   // One LDS object, ring first (1 KB aligned: every load instruction fills one aligned KB).
-  __shared__ __attribute__((aligned(1024))) Smem sm;
+  __shared__ __attribute__((aligned(1024))) Smem<WB> sm;
   char* const s_ring = sm.ring;
-  float (&s_red)[kWorkers][2][4][64] = sm.red;
+  auto& s_red = sm.red;
   GroupSrc* const s_src = sm.src;
   int* const s_prefix = sm.prefix;
 
@@ -234,7 +257,8 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   for (int g = tid; g < n_groups; g += kThreadsL) {
     const GroupSrc src = load_group_src<MODE>(a, g);
     const Group G = make_group<uint16_t, MODE, WB>(a, g, src);
-    const int rows = (G.N + (MODE == kGateUp ? 16 : 32) - 1) / (MODE == kGateUp ? 16 : 32);
+    constexpr int per = MODE == kGateUp ? F::kRows / 2 : F::kRows;
+    const int rows = (G.N + per - 1) / per;
     const int tgs = (G.m + kTok - 1) / kTok;
     s_src[g] = src;
     s_cnt[g] = rows * tgs;
@@ -267,8 +291,8 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     unsigned a_col[4], addr[4];     // logical 16-byte column per load instruction; running offsets
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int row_local = 2 * (wave * 4 + i) + (lane >> 5);
-      a_col[i] = (unsigned)((lane & 31) ^ (row_local & 15));
+      const int row_local = F::kRowsPerIns * (wave * 4 + i) + lane / F::kCols;
+      a_col[i] = (unsigned)((lane % F::kCols) ^ (row_local & 15));
       addr[i] = it.a_row[i] + a_col[i] * 16u;               // kOob + small stays out of range
     }
     __amdgpu_buffer_rsrc_t rs = make_rsrc(it.w0, it.wbytes);
@@ -286,7 +310,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
         // last, partial chunk, or no chunk: lanes out of range fill their part of the stage with zeros
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int kk = k * KC + (int)a_col[i] * Fmt<WB>::kPerColumn;
+          const int kk = k * KC + (int)a_col[i] * F::kPerColumn;
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16,
                                                    (int)((real && kk < it.K) ? addr[i] : kOob), 0, 0, 0);
         }
@@ -326,65 +350,108 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   int need_nx = 0;                  // nx is stale (cur just moved on)
   int f_r0 = 0, f_n0 = 0, f_m = 0, f_N = 0, f_ntn = 0;
   void* f_out = nullptr;
+  // Row tiles of an item: gate/up items hold kTiles / 2 tiles of gate rows and then the same tiles
+  // of up rows; down items kTiles tiles of consecutive rows.
+  constexpr int kHalfTiles = kTiles / 2;
   // 8-bit weights: the row scales this lane's outputs need, loaded when an item starts (sc) and
   // kept for the item whose epilogue is pending (f_sc), so that no epilogue waits for memory
-  f32x4 sc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}}, f_sc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
+  f32x4 sc[kTiles], f_sc[kTiles];
+#pragma unroll
+  for (int rt = 0; rt < kTiles; ++rt) { sc[rt] = f32x4{0, 0, 0, 0}; f_sc[rt] = f32x4{0, 0, 0, 0}; }
   auto load_scales = [&](const Item& it) {
     if (WB != 1) return;
-    // gate rows n0 + 4q + v and the same up rows (N further on); down rows n0 + 16 rt + 4q + v
+    // gate rows n0 + 16 rt + 4q + v and the same up rows (N further on); down rows n0 + 16 rt + 4q + v
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      const int n = (MODE == kGateUp) ? it.n0 + 4 * q : it.n0 + rt * 16 + 4 * q;
+    for (int rt = 0; rt < kTiles; ++rt) {
+      const bool up = MODE == kGateUp && rt >= kHalfTiles;
+      const int n = it.n0 + (up ? rt - kHalfTiles : rt) * 16 + 4 * q;
       const bool ok = it.valid && n < it.N;                 // N is a multiple of 16: all four or none
-      const float* p = static_cast<const float*>(it.scale) + ((MODE == kGateUp && rt == 1) ? it.N + n : n);
+      const float* p = static_cast<const float*>(it.scale) + (up ? it.N + n : n);
       sc[rt] = ok ? *reinterpret_cast<const f32x4*>(p) : f32x4{0, 0, 0, 0};
     }
   };
   load_scales(cur);
   const unsigned ring_base = (unsigned)(size_t)s_ring;
-  const unsigned b_lane = (unsigned)(kp * 64 + q * 16);     // this lane's bytes into a chunk of a token row
   unsigned rd_off[kReads];          // LDS offsets of this lane's fragments inside a stage (row tile 0)
 #pragma unroll
   for (int t = 0; t < kReads; ++t)
     rd_off[t] = ring_base + (unsigned)c16 * kRowBytes + (unsigned)((((kp + t * kKParts) * 4 + q) ^ c16) * 16);
-  // token rows of one chunk: for read t, the 8 k (bf16) or 2 x 8 k (8-bit) behind column (kp + 2t) * 4 + q
+  // token rows of one chunk: for read t, the kHalves x 8 k behind column (kp + 2t) * 4 + q
   i32x4 bbuf[kReads][kHalves];
 #pragma unroll
   for (int t = 0; t < kReads; ++t)
 #pragma unroll
     for (int h = 0; h < kHalves; ++h) bbuf[t][h] = i32x4{0, 0, 0, 0};
-  unsigned sbuf[2][kReads];         // MXFP4: scale byte of this lane's block per row tile and read
+  // MXFP4: computer 3 moves the scale bytes.  Lane l fetches the 16 blocks of item row l of the
+  // chunk with one 16-byte load, one chunk ahead, and writes them to LDS in front of the "landed"
+  // barrier of the iteration that consumes the chunk.
+  static_assert(WB != 0 || (F::kRows == 64 && F::kCols == 16), "the scale mover is written for 64 rows of 16 blocks");
+  i32x4 mx_regs = i32x4{0, 0, 0, 0};
+  int mx_loaded = 0;
+  auto load_mx_scales = [&]() {
+    const __amdgpu_buffer_rsrc_t rsc = make_rsrc(cur.scale, cur.sbytes);
+    int n;
+    unsigned row;
+    if (MODE == kGateUp) { n = cur.n0 + (lane & 31); row = (unsigned)n + ((lane >> 5) ? (unsigned)cur.N : 0u); }
+    else { n = cur.n0 + lane; row = (unsigned)n; }
+    const int blk0 = k * F::kCols;                                 // first block of the chunk, in the group's K
+    const int nvalid = clampi((cur.K >> 5) - blk0, 0, 16);         // blocks of the row that exist from there on
+    const bool ok = cur.valid && n < cur.N && nvalid > 0;
+    i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsc, (int)(ok ? row * ((unsigned)cur.ldwb >> 4) + (unsigned)blk0 : kOob), 0, 0);
+    // bytes behind the row's last block belong to the next row: cleared (their codes are zeros,
+    // and zero times a NaN scale would not be)
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
+    for (int d = 0; d < 4; ++d) {
+      const int vb = clampi(nvalid - 4 * d, 0, 4);
+      v[d] &= vb == 4 ? -1 : (int)((1u << (8 * vb)) - 1u);
+    }
+    mx_regs = v;
+    mx_loaded = 1;
+  };
+  // byte j of a row's 16 is block j = (kp + 2t) * 4 + q; the computing lanes read [kp][q][t]
+  auto store_mx_scales = [&](unsigned char* buf) {
+    unsigned out[4] = {0, 0, 0, 0};
 #pragma unroll
-    for (int t = 0; t < kReads; ++t) sbuf[rt][t] = 127u;
-  f32x4 acc[2] = {f32x4{0, 0, 0, 0}, f32x4{0, 0, 0, 0}};
+    for (int jb = 0; jb < 16; ++jb) {
+      const int pos = ((jb >> 2) & 1) * 8 + (jb & 3) * 2 + (jb >> 3);
+      const unsigned byte = ((unsigned)mx_regs[jb >> 2] >> (8 * (jb & 3))) & 0xffu;
+      out[pos >> 2] |= byte << (8 * (pos & 3));
+    }
+    *reinterpret_cast<i32x4*>(buf + lane * 16) = i32x4{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+  };
 
-  // Scale (8-bit weights), activate and store this lane's 2 x 4 sums of the item that ended.
-  auto store_outputs = [&](float (&val)[2][4]) {
+  f32x4 acc[kTiles];                // the sums of an item stay here until its epilogue, one barrier after its last chunk
+#pragma unroll
+  for (int rt = 0; rt < kTiles; ++rt) acc[rt] = f32x4{0, 0, 0, 0};
+
+  // Scale (8-bit weights), activate and store this lane's kTiles x 4 sums of the item that ended.
+  auto store_outputs = [&](float (&val)[kTiles][4]) {
     if (WB == 1) {
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+      for (int rt = 0; rt < kTiles; ++rt)
 #pragma unroll
         for (int v = 0; v < 4; ++v) val[rt][v] *= f_sc[rt][v];
     }
     const int r = f_r0 + tw * 16 + c16;
     if (r < f_m) {
       if (MODE == kGateUp) {
-        const int i = f_n0 + 4 * q;
-        if (i < f_N) {
-          float hv[4];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const float gte = val[0][v];
-            hv[v] = gte / (1.f + __expf(-gte)) * val[1][v];
+        for (int rt = 0; rt < kHalfTiles; ++rt) {
+          const int i = f_n0 + rt * 16 + 4 * q;
+          if (i < f_N) {
+            float hv[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+              const float gte = val[rt][v];
+              hv[v] = gte / (1.f + __expf(-gte)) * val[rt + kHalfTiles][v];
+            }
+            bf16x4 o = {(__bf16)hv[0], (__bf16)hv[1], (__bf16)hv[2], (__bf16)hv[3]};
+            *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(f_out) + (size_t)r * f_N + i) = o;
           }
-          bf16x4 o = {(__bf16)hv[0], (__bf16)hv[1], (__bf16)hv[2], (__bf16)hv[3]};
-          *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(f_out) + (size_t)r * f_N + i) = o;
         }
       } else {
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
+        for (int rt = 0; rt < kTiles; ++rt) {
           const int col = f_n0 + rt * 16 + 4 * q;
           if (col < f_N)
             *reinterpret_cast<f32x4*>(static_cast<float*>(f_out) + (size_t)r * a.H + col) =
@@ -394,53 +461,85 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     }
   };
   auto epilogue = [&]() {
-    // computers 0 and 1 finish token tiles 0 and 1: add the two k parts, activate, store
+    // computers 0 and 1 finish token tiles 0 and 1: add the two k parts (part 0 first), activate, store
     if (kp == 0 && tw < f_ntn) {
-      float val[2][4];
+      float val[kTiles][4];
 #pragma unroll
-      for (int rt = 0; rt < 2; ++rt)
+      for (int rt = 0; rt < kTiles; ++rt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) val[rt][v] = s_red[tw][rt][v][lane] + s_red[tw + 2][rt][v][lane];
+        for (int v = 0; v < 4; ++v) {
+          if constexpr (kOwnSums) val[rt][v] = acc[rt][v] + s_red[tw][rt][v][lane];
+          else val[rt][v] = s_red[tw][rt][v][lane] + s_red[tw + 2][rt][v][lane];
+        }
       store_outputs(val);
     }
   };
 
   // Fragments of the chunk in stage `stage`, MFMAs against the token rows in bbuf.
-  auto consume = [&](int stage) {
+  auto consume = [&](int stage, const unsigned char* mx_sc) {
     const unsigned st = (unsigned)(stage * kStageBytes);
-    bf16x8 f0[kReads], f1[kReads];                           // row tile 0 / 1, one 16-byte column each
-    static_assert(kReads == 4, "the fragment reads below are written for four columns per wave and row tile");
-    asm volatile(
-        "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:8192\n"
-        "ds_read_b128 %2, %9\n ds_read_b128 %3, %9 offset:8192\n"
-        "ds_read_b128 %4, %10\n ds_read_b128 %5, %10 offset:8192\n"
-        "ds_read_b128 %6, %11\n ds_read_b128 %7, %11 offset:8192\n"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(f0[0]), "=&v"(f1[0]), "=&v"(f0[1]), "=&v"(f1[1]), "=&v"(f0[2]), "=&v"(f1[2]), "=&v"(f0[3]), "=&v"(f1[3])
-        : "v"(rd_off[0] + st), "v"(rd_off[1] + st), "v"(rd_off[2] + st), "v"(rd_off[3] + st)
-        : "memory");
+    bf16x8 f[kTiles][kReads];                               // row tile, 16-byte column
+    constexpr int kT = 16 * kRowBytes;                      // bytes between row tiles
+    if constexpr (kTiles == 2) {
+      static_assert(kTiles != 2 || kReads == 4, "two row tiles: four columns per wave and tile");
+      asm volatile(
+          "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:%12\n"
+          "ds_read_b128 %2, %9\n ds_read_b128 %3, %9 offset:%12\n"
+          "ds_read_b128 %4, %10\n ds_read_b128 %5, %10 offset:%12\n"
+          "ds_read_b128 %6, %11\n ds_read_b128 %7, %11 offset:%12\n"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(f[0][0]), "=&v"(f[1][0]), "=&v"(f[0][1]), "=&v"(f[1][1]), "=&v"(f[0][2]), "=&v"(f[1][2]),
+            "=&v"(f[0][3]), "=&v"(f[1][3])
+          : "v"(rd_off[0] + st), "v"(rd_off[1] + st), "v"(rd_off[2] + st), "v"(rd_off[3] + st), "n"(kT)
+          : "memory");
+    } else {
+      static_assert(kTiles == 2 || (kTiles == 4 && kReads == 2), "four row tiles: two columns per wave and tile");
+      asm volatile(
+          "ds_read_b128 %0, %8\n ds_read_b128 %1, %8 offset:%10\n"
+          "ds_read_b128 %2, %8 offset:%11\n ds_read_b128 %3, %8 offset:%12\n"
+          "ds_read_b128 %4, %9\n ds_read_b128 %5, %9 offset:%10\n"
+          "ds_read_b128 %6, %9 offset:%11\n ds_read_b128 %7, %9 offset:%12\n"
+          "s_waitcnt lgkmcnt(0)"
+          : "=&v"(f[0][0]), "=&v"(f[1][0]), "=&v"(f[2][0]), "=&v"(f[3][0]), "=&v"(f[0][1]), "=&v"(f[1][1]),
+            "=&v"(f[2][1]), "=&v"(f[3][1])
+          : "v"(rd_off[0] + st), "v"(rd_off[1 % kReads] + st), "n"(kT), "n"(2 * kT), "n"(3 * kT)
+          : "memory");
+    }
+    unsigned mx_s[kTiles];                                  // MXFP4: this lane's scale bytes (t = 0, 1) per row tile
+    if constexpr (WB == 0) {
+#pragma unroll
+      for (int rt = 0; rt < kTiles; ++rt)
+        mx_s[rt] = *reinterpret_cast<const unsigned short*>(mx_sc + (rt * 16 + c16) * 16 + kp * 8 + q * 2);
+    }
 #pragma unroll
     for (int t = 0; t < kReads; ++t) {
-      if (WB == 2) {
+      if constexpr (WB == 2) {
         const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][0]);
-        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0[t], bv, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1[t], bv, acc[1], 0, 0, 0);
-      } else if (WB == 1) {
-        const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
+#pragma unroll
+        for (int rt = 0; rt < kTiles; ++rt)
+          acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[rt][t], bv, acc[rt], 0, 0, 0);
+      } else if constexpr (WB == 1) {
 #pragma unroll
         for (int h = 0; h < kHalves; ++h) {
           const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
-          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w0[2 * h], w0[2 * h + 1]), bv, acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w1[2 * h], w1[2 * h + 1]), bv, acc[1], 0, 0, 0);
+#pragma unroll
+          for (int rt = 0; rt < kTiles; ++rt) {
+            const i32x4 w = __builtin_bit_cast(i32x4, f[rt][t]);
+            acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_e4m3(w[2 * h], w[2 * h + 1]), bv, acc[rt], 0, 0, 0);
+          }
         }
       } else {
-        const i32x4 w0 = __builtin_bit_cast(i32x4, f0[t]), w1 = __builtin_bit_cast(i32x4, f1[t]);
-        const float s0 = e8m0_to_f32(sbuf[0][t]), s1 = e8m0_to_f32(sbuf[1][t]);
+        float sv[kTiles];
+#pragma unroll
+        for (int rt = 0; rt < kTiles; ++rt) sv[rt] = e8m0_to_f32((mx_s[rt] >> (8 * t)) & 0xffu);
 #pragma unroll
         for (int h = 0; h < kHalves; ++h) {
           const bf16x8 bv = __builtin_bit_cast(bf16x8, bbuf[t][h]);
-          acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_mx4(w0[h], s0), bv, acc[0], 0, 0, 0);
-          acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_mx4(w1[h], s1), bv, acc[1], 0, 0, 0);
+#pragma unroll
+          for (int rt = 0; rt < kTiles; ++rt) {
+            const i32x4 w = __builtin_bit_cast(i32x4, f[rt][t]);
+            acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen_mx4(w[h], sv[rt]), bv, acc[rt], 0, 0, 0);
+          }
         }
       }
     }
@@ -456,44 +555,32 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     for (int t = 0; t < kReads; ++t)
 #pragma unroll
       for (int h = 0; h < kHalves; ++h) {
-        // the k behind 16-byte column (kp + 2t) * 4 + q of the weight rows (second half: h = 1)
-        const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * Fmt<WB>::kPerColumn + h * 8;
+        // the k behind 16-byte column (kp + 2t) * 4 + q of the weight rows (k-step h of that column)
+        const int kk = k * KC + ((kp + t * kKParts) * 4 + q) * F::kPerColumn + h * 8;
         const bool ok = cur.valid && kk < cur.K && cur.boff != kOob;
         bbuf[t][h] = __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(ok ? cur.boff + (unsigned)kk * 2u : kOob), 0, 0);
       }
-    if (WB == 0) {
-      // the scale bytes of the blocks this lane reads in that chunk: weight rows n0 + 16 rt + c16
-      // (gate/up: gate row n0 + c16 and the same up row), block (chunk's first block) + column;
-      // rows and blocks that do not exist read as 0 (out-of-range offset), their codes are zeros
-      const __amdgpu_buffer_rsrc_t rsc = make_rsrc(cur.scale, 0x7fffffffu);
-      const unsigned per_row = (unsigned)cur.ldwb >> 4;           // bytes of a weight row / 16 = its blocks of 32 codes
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        const int n = (MODE == kGateUp) ? cur.n0 + c16 : cur.n0 + rt * 16 + c16;
-        const unsigned row = (MODE == kGateUp && rt == 1) ? (unsigned)(cur.N + n) : (unsigned)n;
-#pragma unroll
-        for (int t = 0; t < kReads; ++t) {
-          const int blk = k * (KC / 32) + (kp + t * kKParts) * 4 + q;
-          const bool ok = cur.valid && n < cur.N && blk * 32 < cur.K;
-          sbuf[rt][t] = (unsigned)__builtin_amdgcn_raw_buffer_load_b8(rsc, (int)(ok ? row * per_row + (unsigned)blk : kOob), 0, 0);
-        }
-      }
-    }
   };
 
   // One iteration.
   auto step = [&](int s) -> bool {
+    if (WB == 0 && c == 3 && mx_loaded) {                   // the scales of the chunk consumed below
+      store_mx_scales(sm.mx_scale[s & 1]);
+      mx_loaded = 0;
+    }
     lds_barrier();                                          // "landed": the chunk issued three iterations ago
     if (s >= 3 && cur.valid) {
-      if (tw < cur.ntn) consume((s + 1) & (kStages - 1));
+      if (tw < cur.ntn) consume((s + 1) & (kStages - 1), sm.mx_scale[s & 1]);
       if (++k == cur.nch) {         // item done: hand the partial sums over, move on
+        if (!kOwnSums || kp == 1) {
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
+          for (int rt = 0; rt < kTiles; ++rt)
 #pragma unroll
-          for (int v = 0; v < 4; ++v) s_red[c][rt][v][lane] = acc[rt][v];
-        acc[0] = f32x4{0, 0, 0, 0}; acc[1] = f32x4{0, 0, 0, 0};
+            for (int v = 0; v < 4; ++v) s_red[kOwnSums ? tw : c][rt][v][lane] = acc[rt][v];
+        }
+#pragma unroll
+        for (int rt = 0; rt < kTiles; ++rt) f_sc[rt] = sc[rt];
         f_r0 = cur.r0; f_n0 = cur.n0; f_m = cur.m; f_N = cur.N; f_ntn = cur.ntn; f_out = cur.out;
-        f_sc[0] = sc[0]; f_sc[1] = sc[1];
         pending = 1;
         cur = nx; ++j; k = 0;
         need_nx = 1;
@@ -504,9 +591,15 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
     // is (cur, k): the one after the chunk just consumed; a wave whose token tile is empty loads
     // nothing (its MFMAs are skipped as well).
     if (s >= 2 && tw < cur.ntn) load_token_rows();
+    if (WB == 0 && c == 3 && s >= 2) load_mx_scales();      // after the token rows: they start with a wait for everything in flight
     lds_barrier();                                          // "free"; partial sums of an item that ended are complete
     // what follows runs while the loaders wait for their next chunk
-    if (pending) { pending = 0; epilogue(); }
+    if (pending) {
+      pending = 0;
+      epilogue();
+#pragma unroll
+      for (int rt = 0; rt < kTiles; ++rt) acc[rt] = f32x4{0, 0, 0, 0};    // the next chunk is consumed in the next iteration
+    }
     if (need_nx) {
       need_nx = 0;
       load_scales(cur);

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 def cfg_mx(**kw):
     # several row tiles with a ragged last one, K with a partial last chunk, E not a multiple of 16
-    base = dict(name="mx4_small", T=37, H=288, E=10, I=160, k_big=4, k_little=2, shared_I=(96,),
+    base = dict(name="mx4_small", T=37, H=384, E=10, I=256, k_big=4, k_little=2, shared_I=(128,),
                 dtype="bf16mx4", gate_std=0.3, w_std=0.1, gate_bias_std=0.5)
     base.update(kw)
     return wl.LayerConfig(**base)
@@ -30,7 +30,7 @@ def test_small_ragged_layer(r):
 
 def test_long_contractions_and_many_token_blocks():
     # K beyond one 1024-wide chunk in both projections, several token blocks per expert
-    check_layer(cfg_mx(T=200, H=2080, E=4, I=1312, k_big=3, k_little=1, shared_I=(2400, 64)), seed=2)
+    check_layer(cfg_mx(T=200, H=2176, E=4, I=1408, k_big=3, k_little=1, shared_I=(2432, 128)), seed=2)
     check_layer(cfg_mx(T=97, H=512, E=6, I=1024, k_big=4, k_little=2, shared_I=()), seed=3)
 
 
@@ -43,7 +43,7 @@ def test_every_code_and_a_range_of_scales_reach_the_sum():
     """One expert whose W_gate rows hold all 16 codes in every position of a block, under block
     scales from 2^-20 to 2^6: the layer output equals the oracle's, i.e. the kernel's widening agrees
     with the format for every code, and its scales sit with the right rows and blocks."""
-    cfg = cfg_mx(T=16, H=256, E=2, I=32, k_big=1, k_little=1, shared_I=())
+    cfg = cfg_mx(T=16, H=256, E=2, I=128, k_big=1, k_little=1, shared_I=())
     layer = wl.make_layer(cfg, seed=5)
     HI = cfg.H * cfg.I
     for e in range(cfg.E):
@@ -63,7 +63,7 @@ def test_every_code_and_a_range_of_scales_reach_the_sum():
 
 
 def test_little_pass_then_fallback_pass():
-    cfg = cfg_mx(T=48, shared_I=(96,))
+    cfg = cfg_mx(T=48, shared_I=(128,))
     layer = wl.make_layer(cfg, seed=8)
     dl = DeviceLayer(layer)
     logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
@@ -83,7 +83,7 @@ def test_limits_and_blob_size():
     assert mm.moe_expert_blob_bytes(c, cfg.I) == wl.mx4_blob_bytes(cfg.H, cfg.I) == wl.make_expert_blob(cfg, 0, 0).size
     assert mm.moe_expert_blob_bytes(c, cfg.shared_I[0]) == wl.mx4_blob_bytes(cfg.H, cfg.shared_I[0])
     lib = mm.load_library()
-    for bad in (cfg.with_(T=256), cfg.with_(H=272), cfg.with_(I=144), cfg.with_(shared_I=(80,))):
+    for bad in (cfg.with_(T=256), cfg.with_(H=288), cfg.with_(I=160), cfg.with_(shared_I=(96,))):
         cb = mm.make_config(bad)
         rc = lib.moe_combine(ctypes.byref(cb), None, None, None, None, None, None, None)
         assert rc == -3, (bad, rc)
