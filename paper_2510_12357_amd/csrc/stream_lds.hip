@@ -13,8 +13,8 @@
 // A workgroup has two kinds of waves:
 //   * waves 0..3, loaders: issue the global->LDS loads of the weight chunks and nothing else.  A
 //     work item is 32 weight rows (16 gate + 16 up rows, or 32 down rows) x all of K for up to 32
-//     token rows, cut into chunks of 256 k; one chunk = 32 rows x 512 B = one 16 KB stage = 4 load
-//     instructions per loader.  The chunks of all items of the workgroup form one stream, so the
+//     token rows, cut into chunks of 256 k (bf16; the narrower formats take 64 rows, see below);
+//     one chunk = 32 rows x 512 B = one 16 KB stage = 4 load instructions per loader.  The chunks of all items of the workgroup form one stream, so the
 //     ring never drains at an item boundary.  A loader issues exactly 4 loads per iteration (a
 //     slot without a chunk issues 4 loads with out-of-range offsets, which the hardware turns
 //     into zero fills without memory traffic), so its hand-counted s_waitcnt vmcnt(12) means:
@@ -35,15 +35,15 @@
 //   * Groups with more than 32 token rows become several items that read the same weights; the
 //     item order places them 8 items apart, i.e. on workgroups of the same XCD at the same time,
 //     so that the repeats hit in that XCD's L2.
-//   * 8-bit weights (WB = 1): the same stages and loads carry 512 k per chunk.  A 16-byte column
+//   * 8-bit weights (WB = 1): a stage is 64 rows x 256 bytes (256 k per chunk; see Fmt).  A 16-byte column
 //     then holds 16 consecutive k of a row, i.e. the weights of two MFMA k-steps; the k order
 //     inside a chunk is permuted accordingly, and the token rows are loaded with the same
 //     permutation.  The computers widen the codes to bf16 (exact: 3 mantissa bits) in front of
 //     the MFMAs, and the row scale multiplies the fp32 sum in the epilogue.
 //   * MXFP4 weights (WB = 0: OCP microscaling, 4-bit E2M1 codes with one E8M0 scale per 32 k):
-//     1024 k per chunk; a 16-byte column holds the 32 codes of one scale block, i.e. the weights
+//     64 rows x 256 bytes per stage, 512 k per chunk; a 16-byte column holds the 32 codes of one scale block, i.e. the weights
 //     of four MFMA k-steps, with the k order inside a chunk permuted accordingly.  The scale
-//     bytes of a chunk (32 rows x 32 blocks = 1 KB) are fetched by one computer wave with one
+//     bytes of a chunk (64 rows x 16 blocks = 1 KB) are fetched by one computer wave with one
 //     load instruction, one chunk ahead, and handed to the others through a double-buffered KB
 //     of LDS (byte loads from global memory by every lane cost more than the weight stream);
 //     code x scale is widened to bf16 in one instruction (exact) in front of the MFMAs.
@@ -72,10 +72,11 @@ constexpr int kKParts = 2;                   // worker waves that split the k-st
 // Weight formats (template parameter WB): 2 = bf16, 1 = 8-bit codes, 0 = MXFP4 (half a byte), and
 // the shape of a stage that goes with them.  The fewer bytes a weight has, the more k a row of
 // given bytes covers, and every 8 k of a token tile cost the computers one load of token rows
-// whatever the weights weigh; MXFP4 therefore takes items of 64 rows x 256 bytes (512 k) instead
-// of 32 rows x 512 bytes, which halves the token-row loads per weight byte.
+// whatever the weights weigh; the 8-bit and 4-bit formats therefore take items of 64 rows x 256
+// bytes (256 / 512 k) instead of 32 rows x 512 bytes, which halves the token-row loads per weight
+// byte.
 template <int WB> struct Fmt {
-  static constexpr int kRows = WB == 0 ? 64 : 32;                 // weight rows per item
+  static constexpr int kRows = WB == 2 ? 32 : 64;                 // weight rows per item
   static constexpr int kRowBytes = kStageBytes / kRows;           // bytes of one weight row per chunk
   static constexpr int kTiles = kRows / 16;                       // MFMA row tiles per item
   static constexpr int kCols = kRowBytes / 16;                    // 16-byte columns of a row in a stage
