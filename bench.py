@@ -506,7 +506,12 @@ def time_alg1_toy(mm, torch, cfg, steps: int, warmup: int, L: int = 4, V: int = 
         acc, fall = run.n_accepted - a0, run.n_fallbacks - f0
         return dict(tokens_per_s=acc / dt_s, us_per_step=dt_s / (run.n_steps - n0) * 1e6, accepted_tokens=acc,
                     fallback_ratio=fall / max(acc, 1))
-    method, plain = timed(False), timed(True)
+    # each variant twice, the faster run kept: the first steps after other measurements have shown
+    # launch delays that have nothing to do with the step
+    def best(always_big):
+        r1, r2 = timed(always_big), timed(always_big)
+        return r1 if r1["us_per_step"] <= r2["us_per_step"] else r2
+    method, plain = best(False), best(True)
     # Eq. 1 with per-slot pass times: a step costs about the same in either mode here (weights
     # resident), so T = T_b = the all-big step and T_l = a step of little passes only
     r = method["fallback_ratio"]
@@ -964,22 +969,25 @@ def main():
         # the paper's two-pass sequence at layer level (fallback pass = only the ranks above k_little)
         others["two_pass"] = {name: time_two_pass(mm, torch, workload_config(name, args.ratio), k2, w2)
                               for name in ("fine60_decode_b1", "fine60_decode_b64")}
+        # Alg. 1 end to end on a toy language model made of this layer (realised fallback ratio); timed
+        # before the offload measurements, whose pinned arenas are released in the background and slow
+        # the launches of whatever runs next
+        others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 30,
+                                              ratio=args.ratio)
         # fallback fetch path: routed experts in pinned host memory, 16 HBM slots (host-link bound)
         from paper_2510_12357_amd import workloads as wl
         oc = wl.CONFIGS["shared2_offload"].with_(fallback_ratio=args.ratio)
         # (prefetching the next batch's experts cannot help a single layer whose demand misses already
         # saturate the link: there is no other layer's compute to hide the copies under)
         others["shared2_offload_b16"] = dict(demand_only=time_offload(mm, torch, oc, 24, 8),
-                                             demand_only_w8=time_offload(mm, torch, oc.with_(dtype="bf16w8"), 24, 8))
+                                             demand_only_w8=time_offload(mm, torch, oc.with_(dtype="bf16w8"), 24, 8),
+                                             demand_only_mx4=time_offload(mm, torch, oc.with_(dtype="bf16mx4"), 24, 8))
         torch.cuda.empty_cache()
         # Eq. 1 where the paper's claim applies: experts behind the host link, 16 HBM slots; the layer's
         # own batch of 16 and the single-stream case of the paper's measurements
         others["offload_eq1"] = dict(b16=time_offload_eq1(mm, torch, oc, 16, 4),
                                      b1=time_offload_eq1(mm, torch, oc.with_(T=1), 48, 8))
         torch.cuda.empty_cache()
-        # Alg. 1 end to end on a toy language model made of this layer (realised fallback ratio)
-        others["alg1_toy_lm"] = time_alg1_toy(mm, torch, workload_config("fine60_decode_b64", args.ratio), 60, 30,
-                                              ratio=args.ratio)
         extra["other_workloads"] = others
     cpu = None if args.no_cpu else cpu_baseline(cfg, cpu_in)
     if not (args.no_extra or args.no_cpu):
