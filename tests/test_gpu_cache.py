@@ -205,3 +205,70 @@ def test_prefetch_limit_and_slower_link_emulation():
                 assert torch.equal(dev[s].cpu(), host[e])
     finally:
         mm.moe_cache_destroy(h)
+
+
+def test_prefetch_scheduler_calls():
+    """moe_prefetcher_*: request lists equal the oracle's big-mode selection of the rejected tokens
+    (rank by rank, each expert once), the schedule issues the layers it should, a bound of zero
+    copies in flight starts nothing, and bad arguments are refused."""
+    E, n_slots, blob, L, T, K = 24, 8, 2048, 3, 5, 4
+    made = [make_cache(E, blob, n_slots, seed=10 + l) for l in range(L)]
+    handles = [m[0] for m in made]
+    rng = np.random.default_rng(3)
+    logits = np.round(rng.standard_normal((L, T, E)).astype(np.float32) * 2) / 2      # ties among the logits
+    logits[1, 2, 5] = np.nan
+    dev_logits = [torch.from_numpy(logits[l]).cuda() for l in range(L)]
+    p = mm.moe_prefetcher_create(handles, K)
+    try:
+        rejected = [1, 2, 4]
+        mm.moe_prefetcher_predict(p, dev_logits, T, rejected)
+        want = []
+        for l in range(L):
+            idx = oracle.route(logits[l][rejected], None, 0.5, K, 2, False)[0]
+            seen = []
+            for j in range(K):
+                for e in idx[:, j]:
+                    if int(e) not in seen:
+                        seen.append(int(e))
+            want.append(seen)
+            assert mm.moe_prefetcher_predicted(p, l, E) == seen
+        # distance 2: the start of a pass requests layers 0 and 1, "layer 0 is about to run" layer 2
+        models = [CacheModel(E, n_slots) for _ in range(L)]
+        issued = mm.moe_prefetcher_advance(p, -1, 2, L)
+        assert [l for l, _, _ in issued] == [0, 1] and all(lim == -1 for _, lim, _ in issued)
+        issued += mm.moe_prefetcher_advance(p, 0, 2, L)
+        assert [l for l, _, _ in issued] == [0, 1, 2]
+        assert mm.moe_prefetcher_advance(p, 1, 2, L) == [] and mm.moe_prefetcher_advance(p, 0, 0, L) == []
+        for l, _, st in issued:
+            ref = models[l].fetch(want[l], PREFETCH)
+            assert (st.hits, st.misses, st.dropped) == (ref[1], ref[2], ref[3]) and st.misses == min(len(want[l]), n_slots)
+            assert mm.moe_cache_snapshot(handles[l], n_slots) == models[l].slot_expert
+        for h, host, dev in made:
+            mm.moe_cache_sync(h)
+        for l, (h, host, dev) in enumerate(made):
+            for s, e in enumerate(models[l].slot_expert):
+                if e >= 0:
+                    assert torch.equal(dev[s].cpu(), host[e])
+        # a new prediction under "no prefetch copy in flight at all": resident experts hit, the rest is dropped
+        mm.moe_prefetcher_set_in_flight_limit(p, 0)
+        mm.moe_prefetcher_predict(p, dev_logits, T, [0, 3])
+        (l0, lim, st), = mm.moe_prefetcher_advance(p, -1, 1, L)
+        ref = models[0].fetch(mm.moe_prefetcher_predicted(p, 0, E), PREFETCH, 0)
+        assert (l0, lim) == (0, 0) and (st.hits, st.misses, st.dropped) == (ref[1], 0, ref[3]) and st.bytes_h2d == 0
+        # no rejection: the prediction is cleared and nothing is requested
+        mm.moe_prefetcher_predict(p, dev_logits, T, [])
+        assert mm.moe_prefetcher_predicted(p, 1, E) == [] and mm.moe_prefetcher_advance(p, -1, 3, L) == []
+        # refused arguments
+        for bad in (lambda: mm.moe_prefetcher_predict(p, dev_logits, T, [T]),
+                    lambda: mm.moe_prefetcher_advance(p, L, 1, L),
+                    lambda: mm.moe_prefetcher_advance(p, 0, -1, L),
+                    lambda: mm.moe_prefetcher_predicted(p, -1, E)):
+            with pytest.raises(mm.MoeError) as ei:
+                bad()
+            assert ei.value.code == -1
+        with pytest.raises(mm.MoeError):
+            mm.moe_prefetcher_create(handles, E + 1)
+    finally:
+        mm.moe_prefetcher_destroy(p)
+        for h, _, _ in made:
+            mm.moe_cache_destroy(h)
