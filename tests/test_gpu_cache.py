@@ -140,6 +140,14 @@ def test_offloaded_layer_with_8_bit_experts():
     assert D > 5 and stats[0][1] == D and stats[0][2] == -(-D // 5)
 
 
+def test_offloaded_layer_with_mxfp4_experts():
+    cfg = wl.LayerConfig("off_mx4", T=16, H=256, E=12, I=128, k_big=4, k_little=2, shared_I=(128,), dtype="bf16mx4",
+                         gate_std=0.3, w_std=0.1, fallback_ratio=0.3)
+    stats, ref = run_offloaded(cfg, n_slots=5, seed=3)
+    D = int((np.diff(ref["expert_offsets"]) > 0).sum())
+    assert D > 5 and stats[0][1] == D and stats[0][2] == -(-D // 5)
+
+
 def test_prefetch_between_demand_and_ffn_launch():
     """A PREFETCH call may come between a DEMAND call and the launch of the kernels that read its
     slots: the next DEMAND call's copies into those slots still wait for these kernels.  The kernels
