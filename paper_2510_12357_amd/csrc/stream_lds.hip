@@ -124,8 +124,15 @@ struct Item {
   void* out;
   // ---- per lane ----
   unsigned a_row[4];    // loaders: byte offset of the weight row behind each of the wave's 4 load instructions
-  unsigned boff;        // computers: byte offset of this lane's token row (kOob: none)
+  // computers: this lane's token row.  decode_item leaves the row number here (for a routed
+  // gate/up item it comes from sorted_token, i.e. from memory) and resolve_row turns it into a byte
+  // offset when the item becomes the current one, chunks later: no wave waits for that load.
+  unsigned boff;        // byte offset of the row (kOob: none)
 };
+
+__device__ __forceinline__ void resolve_row(Item& it, int T) {
+  it.boff = it.boff == kOob ? kOob : (unsigned)clampi((int)it.boff, 0, T - 1) * it.ldbb;
+}
 
 template <int MODE, int WB>
 __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int total, int n_groups,
@@ -191,9 +198,7 @@ __device__ __forceinline__ Item decode_item(const StreamArgs& a, int j, int tota
   {
     const int r = it.r0 + (wave & 1) * 16 + (lane & 15);
     const bool val = it.valid && r < it.m;
-    int row = r;
-    if (it.gather) row = val ? clampi(a.sorted_token[it.row0 + r], 0, a.T - 1) : 0;
-    it.boff = val ? (unsigned)row * it.ldbb : kOob;
+    it.boff = val ? (it.gather ? (unsigned)a.sorted_token[it.row0 + r] : (unsigned)r) : kOob;
   }
   return it;
 }
@@ -345,6 +350,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   // =================================== computer ===================================
   const int c = wave - kWorkers, tw = c & 1, kp = c >> 1;
   Item cur = decode_item<MODE, WB>(a, 0, total, n_groups, s_prefix, s_src, c, lane);
+  resolve_row(cur, a.T);
   Item nx = decode_item<MODE, WB>(a, 1, total, n_groups, s_prefix, s_src, c, lane);
   int j = 0, k = 0;                 // item ordinal and chunk being consumed
   int pending = 0;                  // the previous item's partial sums wait for their epilogue
@@ -354,21 +360,22 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
   // Row tiles of an item: gate/up items hold kTiles / 2 tiles of gate rows and then the same tiles
   // of up rows; down items kTiles tiles of consecutive rows.
   constexpr int kHalfTiles = kTiles / 2;
-  // 8-bit weights: the row scales this lane's outputs need, loaded when an item starts (sc) and
-  // kept for the item whose epilogue is pending (f_sc), so that no epilogue waits for memory
-  f32x4 sc[kTiles], f_sc[kTiles];
+  // 8-bit weights: the row scales this lane's outputs need, loaded when an item starts, so that no
+  // epilogue waits for memory (the next item's are loaded behind the epilogue of this one)
+  f32x4 sc[kTiles];
 #pragma unroll
-  for (int rt = 0; rt < kTiles; ++rt) { sc[rt] = f32x4{0, 0, 0, 0}; f_sc[rt] = f32x4{0, 0, 0, 0}; }
+  for (int rt = 0; rt < kTiles; ++rt) sc[rt] = f32x4{0, 0, 0, 0};
   auto load_scales = [&](const Item& it) {
     if (WB != 1) return;
-    // gate rows n0 + 16 rt + 4q + v and the same up rows (N further on); down rows n0 + 16 rt + 4q + v
+    // gate rows n0 + 16 rt + 4q + v and the same up rows (N further on); down rows n0 + 16 rt + 4q + v.
+    // Buffer loads: rows that do not exist read zeros without a select that would wait for the load.
+    const __amdgpu_buffer_rsrc_t rsc = make_rsrc(it.scale, it.valid ? (unsigned)((MODE == kGateUp ? 2 : 1) * it.N) * 4u : 0u);
 #pragma unroll
     for (int rt = 0; rt < kTiles; ++rt) {
       const bool up = MODE == kGateUp && rt >= kHalfTiles;
       const int n = it.n0 + (up ? rt - kHalfTiles : rt) * 16 + 4 * q;
       const bool ok = it.valid && n < it.N;                 // N is a multiple of 16: all four or none
-      const float* p = static_cast<const float*>(it.scale) + (up ? it.N + n : n);
-      sc[rt] = ok ? *reinterpret_cast<const f32x4*>(p) : f32x4{0, 0, 0, 0};
+      sc[rt] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rsc, (int)(ok ? (unsigned)(up ? it.N + n : n) * 4u : kOob), 0, 0));
     }
   };
   load_scales(cur);
@@ -431,7 +438,7 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
 #pragma unroll
       for (int rt = 0; rt < kTiles; ++rt)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) val[rt][v] *= f_sc[rt][v];
+        for (int v = 0; v < 4; ++v) val[rt][v] *= sc[rt][v];
     }
     const int r = f_r0 + tw * 16 + c16;
     if (r < f_m) {
@@ -579,11 +586,10 @@ __global__ __launch_bounds__(kThreadsL) __attribute__((amdgpu_waves_per_eu(4, 4)
 #pragma unroll
             for (int v = 0; v < 4; ++v) s_red[kOwnSums ? tw : c][rt][v][lane] = acc[rt][v];
         }
-#pragma unroll
-        for (int rt = 0; rt < kTiles; ++rt) f_sc[rt] = sc[rt];
         f_r0 = cur.r0; f_n0 = cur.n0; f_m = cur.m; f_N = cur.N; f_ntn = cur.ntn; f_out = cur.out;
         pending = 1;
         cur = nx; ++j; k = 0;
+        resolve_row(cur, a.T);
         need_nx = 1;
       }
     }
