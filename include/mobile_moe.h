@@ -28,9 +28,9 @@
  *     enqueued asynchronously on it; no call synchronises with the host except where stated.
  *   - Tensors are row-major and dense.  dtype MOE_BF16: activations / weights are bf16,
  *     products accumulate in fp32.  dtype MOE_FP32: fp32 storage and arithmetic.
- *     dtype MOE_BF16_W8 (decode regime only, T < 256; not in the paper): as MOE_BF16, but the
- *     expert weights are stored in 8 bits with one fp32 scale per weight row, which halves the
- *     bytes a decode step streams from HBM.  It needs H, I and every shared_I to be multiples
+ *     dtype MOE_BF16_W8 (not in the paper): as MOE_BF16, but the expert weights are stored in
+ *     8 bits with one fp32 scale per weight row, which halves the bytes a decode step streams
+ *     from HBM and the memory a layer takes.  It needs H, I and every shared_I to be multiples
  *     of 16.
  *     dtype MOE_BF16_MXFP4 (decode regime only, T < 256; not in the paper): as MOE_BF16, but
  *     the expert weights are stored in the OCP microscaling format MXFP4 (4-bit elements with one

@@ -75,8 +75,9 @@ int device_cu_count() {
   return cached_cu;
 }
 
-// Steps of this many tokens and more run the LDS-tiled kernels, which read bf16 weights only.
-constexpr int kW8MaxT = 256;
+// Steps of this many tokens and more run the LDS-tiled kernels (bf16 and 8-bit weights; MXFP4
+// weights exist for the streaming kernel only).
+constexpr int kTiledMinT = 256;
 
 int validate_config(const moe_config* c) {
   if (!c) return fail(MOE_E_BADARG, "config is NULL");
@@ -104,16 +105,14 @@ int validate_config(const moe_config* c) {
   if (biggest >= (1ll << 31) || act >= (1ll << 31) || gate >= (1ll << 31))
     return fail(MOE_E_UNSUPPORTED, "a tensor of this layer reaches 2 GiB (expert blob, activations or gate matrix)");
   if (c->dtype == MOE_BF16_W8) {
-    if (c->T >= kW8MaxT)
-      return fail(MOE_E_UNSUPPORTED, "8-bit expert weights are for the decode regime: T=%d, limit %d", c->T, kW8MaxT - 1);
-    // the kernel moves 16 codes of a weight row at a time
+    // the kernels move 16 codes of a weight row at a time
     bool ok = c->H % 16 == 0 && c->I % 16 == 0;
     for (int s = 0; s < c->n_shared; ++s) ok = ok && c->shared_I[s] % 16 == 0;
     if (!ok) return fail(MOE_E_UNSUPPORTED, "8-bit expert weights need H, I and every shared_I to be multiples of 16");
   }
   if (c->dtype == MOE_BF16_MXFP4) {
-    if (c->T >= kW8MaxT)
-      return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights are for the decode regime: T=%d, limit %d", c->T, kW8MaxT - 1);
+    if (c->T >= kTiledMinT)
+      return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights are for the decode regime: T=%d, limit %d", c->T, kTiledMinT - 1);
     // a scale block is 32 weights along the contraction; the kernel fetches the scale bytes of a
     // row 16 at a time with 4-byte aligned loads, so a row must hold a multiple of 4 of them
     bool ok = c->H % 128 == 0 && c->I % 128 == 0;
@@ -336,14 +335,15 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
   hipStream_t s = static_cast<hipStream_t>(stream);
   // Regime: with many tokens per step the experts see enough rows for LDS-tiled MFMA GEMMs;
   // below that the weights are streamed once through the skinny kernel.
-  const bool tiled = cfg->dtype == MOE_BF16 && cfg->T >= kW8MaxT;
+  const bool tiled = (cfg->dtype == MOE_BF16 || cfg->dtype == MOE_BF16_W8) && cfg->T >= kTiledMinT;
+  const int wfmt = cfg->dtype == MOE_BF16_W8 ? 1 : 2;
   {
     ProfScope ps(kProfFfnGateUp, s);
-    rc = tiled ? launch_tiled(kGateUp, a, s) : launch_stream(kGateUp, cfg->dtype, a, s);
+    rc = tiled ? launch_tiled(kGateUp, wfmt, a, s) : launch_stream(kGateUp, cfg->dtype, a, s);
     if (rc) return rc;
   }
   ProfScope ps(kProfFfnDown, s);
-  return tiled ? launch_tiled(kDown, a, s) : launch_stream(kDown, cfg->dtype, a, s);
+  return tiled ? launch_tiled(kDown, wfmt, a, s) : launch_stream(kDown, cfg->dtype, a, s);
 }
 
 extern "C" int moe_combine(const moe_config* cfg, const float* y, const float* topk_w,

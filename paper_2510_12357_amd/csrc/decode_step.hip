@@ -391,12 +391,6 @@ __device__ __forceinline__ DItem decode_item(const DecodeArgs& a, const Smem& sm
   return it;
 }
 
-// 8 E4M3 codes (two dwords, k ascending with the byte address) -> 8 bf16, exactly.
-__device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
-  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
-  const auto c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
-  return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
-}
 
 // out[t][c .. c+3] for the 32 columns of tile `tile` and all tokens, by the 8 waves of a workgroup:
 // wave w takes tokens 8 w .. 8 w + 7, a lane four columns of one token.  All loads of a kind are

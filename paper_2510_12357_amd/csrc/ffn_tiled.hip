@@ -26,6 +26,15 @@
 //     persistent workgroups; the tile list is cut into 8 contiguous ranges, one per XCD, and
 //     the token tiles that share a weight panel are adjacent in the list, so a panel is fetched
 //     from HBM once and re-read from that XCD's L2.
+//   * 8-bit weights (WB = 1: E4M3 codes with one fp32 scale per weight row): the weight rows of a
+//     tile are 64 bytes in LDS (half the loads and half the LDS of a bf16 panel), 16 rows per load
+//     instruction, swizzled with the key (row >> 2) & 3 so that a 16-byte fragment read of 16 rows
+//     hits every bank once.  One such read holds a lane's codes of two k-steps, so the k order
+//     inside a chunk is permuted: k-step 2p + e takes, for the lanes of half h, the 8 k behind
+//     32 p + 16 h + 8 e, and the token fragments are read with the same permutation.  A computing
+//     wave widens the codes of the next k-step to bf16 (exact) between the MFMAs of the current one,
+//     and the row scale multiplies the fp32 sum in the epilogue.  Tokens, tile shape, pipeline and
+//     tile order are those of the bf16 kernel.
 #include <atomic>
 #include <type_traits>
 
@@ -57,6 +66,19 @@ static_assert(BK == 32 || BK == 64, "K chunk of 32 or 64");
 static_assert(MOE_TILED_STAGES >= 3, "the pipeline needs at least three stages");
 // swizzle key of a tile row: rows that share 256 bytes of LDS get the same key, the next ones the next
 __device__ __forceinline__ constexpr int row_key(int row) { return (row >> kKeyShift) & (kCols - 1); }
+
+// Weight rows of a tile in LDS, by weight format (WB bytes per weight).
+template <int WB>
+struct WFmt {
+  static_assert(WB == 1 || WB == 2, "bf16 or 8-bit weights");
+  static constexpr int kRowB = BK * WB;              // bytes of a weight tile row
+  static constexpr int kCols = kRowB / 16;           // its 16-byte columns
+  static constexpr int kRowsPerIns = 1024 / kRowB;   // tile rows that one load instruction fills
+  static constexpr int kPerCol = 16 / WB;            // weights per 16-byte column
+  // 64-byte rows: four rows share 256 bytes of LDS, and 16 consecutive rows get every key once per
+  // residue of the row number mod 4
+  static __device__ __forceinline__ constexpr int key(int row) { return WB == 2 ? row_key(row) : (row >> 2) & (kCols - 1); }
+};
 
 // vmcnt(n): bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima (no wait)
 #define MM_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
@@ -95,17 +117,20 @@ struct Shape {
   static constexpr int kThreads = 2 * kWaves * 64;
   static constexpr int BM = WM * TM * 32;            // tokens per tile
   static constexpr int BNR = WN * TN * 32;           // weight rows per tile (gate/up: half + half)
-  static constexpr int kInsA = BM / kRowsPerIns / kWaves;      // load instructions per wave and chunk
-  static constexpr int kInsB = BNR / kRowsPerIns / kWaves;
-  static constexpr int kStageBytes = (BM + BNR) * kRowB;
-  static_assert(BM % (kRowsPerIns * kWaves) == 0 && BNR % (kRowsPerIns * kWaves) == 0, "tile rows must divide evenly");
+  static constexpr int kInsA = BM / kRowsPerIns / kWaves;      // token-row load instructions per wave and chunk
+  template <int WB> static constexpr int ins_b() { return BNR / WFmt<WB>::kRowsPerIns / kWaves; }   // weight-row ones
+  template <int WB> static constexpr int stage_bytes() { return BM * kRowB + BNR * WFmt<WB>::kRowB; }
+  static_assert(BM % (kRowsPerIns * kWaves) == 0 && BNR % (16 * kWaves) == 0, "tile rows must divide evenly");
   static_assert((TM == 2 || TM == 4) && (TN == 2 || TN == 4), "the fragment reads are written for 2 or 4 MFMA tiles per wave and side");
 };
 
-template <int MODE, typename SH>
+template <int MODE, typename SH, int WB>
 __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(const StreamArgs a) {
+  typedef WFmt<WB> WF;
   constexpr int BM = SH::BM, BNR = SH::BNR, TM = SH::TM, TN = SH::TN;
-  constexpr int kThreads = SH::kThreads, kInsA = SH::kInsA, kInsB = SH::kInsB;
+  constexpr int kThreads = SH::kThreads, kInsA = SH::kInsA, kInsB = SH::template ins_b<WB>();
+  constexpr int kStageBytes = SH::template stage_bytes<WB>();
+  constexpr int kRowBW = WF::kRowB;                                // bytes of a weight tile row
   constexpr int kPerChunk = kInsA + kInsB;                         // loads of one wave per chunk
   constexpr int kOutCols = (MODE == kGateUp) ? BNR / 2 : BNR;     // output columns per tile
 
@@ -123,7 +148,7 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 
   // ---- tile list: tiles per group, exclusive prefix ----
   for (int g = tid; g < n_groups; g += kThreads) {
-    const Group G = resolve_group<S, MODE>(a, g);
+    const Group G = make_group<S, MODE, WB>(a, g, load_group_src<MODE>(a, g));
     s_cnt[g] = ((G.N + kOutCols - 1) / kOutCols) * ((G.m + BM - 1) / BM);
   }
   __syncthreads();
@@ -152,17 +177,20 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
   // ---- per-lane constants of the loads: instruction p of this wave fills tile rows
   // kRowsPerIns * (lw * kIns + p) + lane / kCols at physical column lane % kCols ----
   const int ld_sub = lane / kCols, ld_pc = lane % kCols;
+  const int ld_subw = lane / WF::kCols, ld_pcw = lane % WF::kCols;   // the same for weight rows
   // ---- per-lane constants of the fragment reads: row (lane & 31) of a 32-row block, logical
   // column 2 * kk + lane / 32; every block starts at a multiple of 32 rows, so the swizzle key
   // of the row depends on the lane only ----
   const unsigned lds0 = (unsigned)(size_t)s_tiles;
   const unsigned fkey = (unsigned)row_key(lane & 31);
+  const unsigned fkeyw = (unsigned)WF::key(lane & 31);
   const unsigned a_rd = lds0 + (unsigned)((wm * TM * 32 + (lane & 31)) * kRowB);
   const unsigned b_rd = lds0 + (unsigned)(BM * kRowB) +
-                        (unsigned)(((MODE == kGateUp ? wn * (TN / 2) * 32 : wn * TN * 32) + (lane & 31)) * kRowB);
-  // byte distance between the fragment rows of consecutive column tiles j
-  constexpr int kJ = 32 * kRowB;                                   // next 32 rows
-  constexpr int kUp = (MODE == kGateUp) ? (BNR / 2) * kRowB : (TN / 2) * kJ;   // j >= TN/2: the up rows / the next blocks
+                        (unsigned)(((MODE == kGateUp ? wn * (TN / 2) * 32 : wn * TN * 32) + (lane & 31)) * kRowBW);
+  // byte distance between the fragment rows of consecutive token blocks i / column tiles j
+  constexpr int kJ = 32 * kRowB;                                   // next 32 token rows
+  constexpr int kJw = 32 * kRowBW;                                 // next 32 weight rows
+  constexpr int kUp = (MODE == kGateUp) ? (BNR / 2) * kRowBW : (TN / 2) * kJw;   // j >= TN/2: the up rows / the next blocks
 
   for (int tile = lo_t + slot; tile < hi_t; tile += nslots) {
     int lo = 0, hi = n_groups;
@@ -170,7 +198,7 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
       const int mid = (lo + hi) >> 1;
       if (s_prefix[mid] <= tile) lo = mid; else hi = mid;
     }
-    const Group G = resolve_group<S, MODE>(a, lo);
+    const Group G = make_group<S, MODE, WB>(a, lo, load_group_src<MODE>(a, lo));
     const int local = tile - s_prefix[lo];
     const int mt = (G.m + BM - 1) / BM;
     const int n_tile = local / mt;                         // token tiles of one weight panel adjacent
@@ -201,22 +229,22 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 #pragma unroll
       for (int p = 0; p < kInsB; ++p) {
         // weight row of the tile: gate/up tiles hold BNR/2 rows of W_gate, then the same rows of W_up
-        const int br = kRowsPerIns * (lw * kInsB + p) + ld_sub;
+        const int br = WF::kRowsPerIns * (lw * kInsB + p) + ld_subw;
         int n;
         unsigned extra = 0;
         if (MODE == kGateUp) {
           n = n0 + (br % (BNR / 2));
-          if (br >= BNR / 2) extra = (unsigned)G.N * (unsigned)G.ldw * 2u;
+          if (br >= BNR / 2) extra = (unsigned)G.N * (unsigned)G.ldw * (unsigned)WB;
         } else {
           n = n0 + br;
         }
-        bcol[p] = (ld_pc ^ row_key(br)) * 8;
-        boff[p] = (n < G.N ? (unsigned)n * (unsigned)G.ldw * 2u + extra : kOob) + (unsigned)bcol[p] * 2u;
+        bcol[p] = (ld_pcw ^ WF::key(br)) * WF::kPerCol;
+        boff[p] = (n < G.N ? (unsigned)n * (unsigned)G.ldw * (unsigned)WB + extra : kOob) + (unsigned)bcol[p] * (unsigned)WB;
       }
       // chunk `kt` into stage `st`, then step the offsets to the next chunk
       auto issue = [&](int st, int kt) {
-        char* const sa = s_tiles + st * SH::kStageBytes + (lw * kInsA) * 1024;
-        char* const sb = s_tiles + st * SH::kStageBytes + BM * kRowB + (lw * kInsB) * 1024;
+        char* const sa = s_tiles + st * kStageBytes + (lw * kInsA) * 1024;
+        char* const sb = s_tiles + st * kStageBytes + BM * kRowB + (lw * kInsB) * 1024;
         const bool full = (kt + 1) * BK <= K;
 #pragma unroll
         for (int p = 0; p < kInsA; ++p) {
@@ -228,7 +256,7 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
         for (int p = 0; p < kInsB; ++p) {
           const unsigned off = full ? boff[p] : ((kt * BK + bcol[p] < K) ? boff[p] : kOob);
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_void*)(sb + p * 1024), 16, (int)off, 0, 0, 0);
-          boff[p] += kRowB;
+          boff[p] += kRowBW;
         }
       };
       // wait until at most `pending` whole chunks of this wave's loads are still in flight
@@ -275,41 +303,78 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
     constexpr int kParts = BK / 16;
     auto main_loop = [&](auto nb_tag) {
       constexpr int NB = decltype(nb_tag)::value;          // token blocks in use: 1 .. TM
-      auto read_frags = [&](int st, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
-        const unsigned col = (((unsigned)(kk * 2 + (lane >> 5))) ^ fkey) * 16u + (unsigned)(st * SH::kStageBytes);
+      // token fragments of k-step kk of the chunk in stage st (8-bit weights: k-step 2p + e reads
+      // the 16-byte column 4p + 2h + e, see the head of the file)
+      auto read_a = [&](int st, int kk, bf16x8 (&fa)[TM]) {
+        const unsigned lc = WB == 2 ? (unsigned)(kk * 2 + (lane >> 5)) : (unsigned)((kk >> 1) * 4 + (lane >> 5) * 2 + (kk & 1));
+        const unsigned col = (lc ^ fkey) * 16u + (unsigned)(st * kStageBytes);
         if constexpr (NB == 1) frag_read1<0>(fa[0], a_rd + col);
         else frag_read2<0, kJ>(fa[0], fa[1], a_rd + col);
         if constexpr (NB == 3) frag_read1<2 * kJ>(fa[2], a_rd + col);
         if constexpr (NB == 4) frag_read2<2 * kJ, 3 * kJ>(fa[2], fa[3], a_rd + col);
+      };
+      // weight fragments, 16 bytes per lane and column tile: bf16, the 8 k of k-step kk; 8-bit, the
+      // 2 x 8 codes of the k-steps 2c and 2c + 1
+      auto read_b = [&](int st, int c, bf16x8 (&fb)[TN]) {
+        const unsigned lc = (unsigned)(c * 2 + (lane >> 5));
+        const unsigned col = (lc ^ (WB == 2 ? fkey : fkeyw)) * 16u + (unsigned)(st * kStageBytes);
         if constexpr (TN == 2) {
           frag_read2<0, kUp>(fb[0], fb[1], b_rd + col);
         } else {
-          frag_read2<0, kJ>(fb[0], fb[1], b_rd + col);
-          frag_read2<kUp, kUp + kJ>(fb[2], fb[3], b_rd + col);
+          frag_read2<0, kJw>(fb[0], fb[1], b_rd + col);
+          frag_read2<kUp, kUp + kJw>(fb[2], fb[3], b_rd + col);
         }
       };
       bf16x8 fa[2][TM] = {}, fb[2][TN];
+      bf16x8 fr[TN];                                       // 8-bit weights: the codes of a pair of k-steps
+      auto widen = [&](bf16x8 (&dst)[TN], int e) {         // those of its k-step e
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const i32x4 w = __builtin_bit_cast(i32x4, fr[j]);
+          dst[j] = e ? widen_e4m3(w[2], w[3]) : widen_e4m3(w[0], w[1]);
+        }
+      };
       lds_barrier();                                       // barrier 0
-      read_frags(0, 0, fa[0], fb[0]);
-      frag_wait(fa[0]); frag_wait(fb[0]);
+      read_a(0, 0, fa[0]);
+      if constexpr (WB == 2) { read_b(0, 0, fb[0]); frag_wait(fa[0]); frag_wait(fb[0]); }
+      else { read_b(0, 0, fr); frag_wait(fa[0]); frag_wait(fr); widen(fb[0], 0); }
       int st = 0;                                          // stage of chunk kt
       for (int kt = 0; kt < nk; ++kt) {
         const int st_nx = st + 1 == kStages ? 0 : st + 1;  // stage of chunk kt+1
 #pragma unroll
         for (int kk = 0; kk < kParts; ++kk) {
           const int cur = kk & 1, nxt = (kk + 1) & 1;      // kParts is even: set 0 again holds k-step 0 of the next chunk
-          if (kk + 1 < kParts) {
-            read_frags(st, kk + 1, fa[nxt], fb[nxt]);
-          } else {
+          int st_rd = st, kk_rd = kk + 1;
+          if (kk + 1 == kParts) {
             lds_barrier();                                 // barrier kt+1
-            read_frags(st_nx, 0, fa[nxt], fb[nxt]);        // stale data behind the last chunk; never used
+            st_rd = st_nx; kk_rd = 0;                      // stale data behind the last chunk; never used
           }
+          read_a(st_rd, kk_rd, fa[nxt]);
+          if constexpr (WB == 2) {
+            read_b(st_rd, kk_rd, fb[nxt]);
 #pragma unroll
-          for (int i = 0; i < NB; ++i)
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+              for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+            frag_wait(fa[nxt]); frag_wait(fb[nxt]);
+          } else {
+            // Even k-step: the codes of the odd one are in fr already.  Odd k-step: fr is free (both
+            // halves widened) and takes the next pair.  The codes of the next k-step are widened behind
+            // the first token block's MFMAs, so that the conversions run while the matrix unit works.
+            if (kk & 1) read_b(st_rd, kk_rd >> 1, fr);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
-          frag_wait(fa[nxt]); frag_wait(fb[nxt]);
+              acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][j], acc[0][j], 0, 0, 0);
+            frag_wait(fa[nxt]);
+            if (kk & 1) frag_wait(fr);
+            widen(fb[nxt], (kk & 1) ? 0 : 1);
+#pragma unroll
+            for (int i = 1; i < NB; ++i)
+#pragma unroll
+              for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+          }
           __builtin_amdgcn_sched_barrier(0);               // keep the steps apart; free order inside a step
         }
         st = st_nx;
@@ -330,6 +395,23 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
     }
 
     // ---- epilogue: accumulator v of lane l is row 8*(v/4) + 4*(l/32) + v%4, column l%32 ----
+    // 8-bit weights: the scale of the weight row behind column tile j (gate/up: of the gate row and
+    // of the up row behind output column j)
+    float wsc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      wsc[j] = 1.f;
+      if (WB == 1) {
+        const float* sc = static_cast<const float*>(G.scale);
+        if (MODE == kGateUp) {
+          const int col = n0 + wn * (TN / 2) * 32 + (j % (TN / 2)) * 32 + (lane & 31);
+          if (col < G.N) wsc[j] = sc[(j >= TN / 2 ? G.N : 0) + col];
+        } else {
+          const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
+          if (col < G.N) wsc[j] = sc[col];
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -341,8 +423,9 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
           for (int j = 0; j < TN / 2; ++j) {
             const int col = n0 + wn * (TN / 2) * 32 + j * 32 + (lane & 31);
             if (col < G.N) {
-              const float gte = acc[i][j][v];
-              const float hv = gte / (1.f + __expf(-gte)) * acc[i][j + TN / 2][v];
+              const float gte = WB == 1 ? acc[i][j][v] * wsc[j] : acc[i][j][v];
+              const float upv = WB == 1 ? acc[i][j + TN / 2][v] * wsc[j + TN / 2] : acc[i][j + TN / 2][v];
+              const float hv = gte / (1.f + __expf(-gte)) * upv;
               const __bf16 o = (__bf16)hv;
               static_cast<S*>(G.out)[(size_t)r * G.N + col] = __builtin_bit_cast(uint16_t, o);
             }
@@ -351,31 +434,31 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
 #pragma unroll
           for (int j = 0; j < TN; ++j) {
             const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
-            if (col < G.N) static_cast<float*>(G.out)[(size_t)r * a.H + col] = acc[i][j][v];
+            if (col < G.N) static_cast<float*>(G.out)[(size_t)r * a.H + col] = WB == 1 ? acc[i][j][v] * wsc[j] : acc[i][j][v];
           }
         }
       }
   }
 }
 
-template <int MODE, typename SH>
+template <int MODE, typename SH, int WB>
 int launch_tiled_shape(const StreamArgs& a, hipStream_t s) {
-  constexpr size_t kLds = (size_t)kStages * SH::kStageBytes;
+  constexpr size_t kLds = (size_t)kStages * SH::template stage_bytes<WB>();
   static std::atomic<int> cached{0};
   int per_cu = cached.load(std::memory_order_relaxed);
   if (per_cu == 0) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_kernel<MODE, SH>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_kernel<MODE, SH, WB>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds) != hipSuccess)
       return hip_fail(hipGetLastError(), "tiled_kernel: LDS size attribute");
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, tiled_kernel<MODE, SH>, SH::kThreads, kLds) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, tiled_kernel<MODE, SH, WB>, SH::kThreads, kLds) != hipSuccess || n < 1) n = 1;
     per_cu = n;
     cached.store(n, std::memory_order_relaxed);
   }
   int grid = device_cu_count() * per_cu;
   grid = grid / 8 * 8;                                      // the XCD walk wants a multiple of 8
   if (grid < 8) grid = 8;
-  hipLaunchKernelGGL((tiled_kernel<MODE, SH>), dim3((unsigned)grid), dim3(SH::kThreads), kLds, s, a);
+  hipLaunchKernelGGL((tiled_kernel<MODE, SH, WB>), dim3((unsigned)grid), dim3(SH::kThreads), kLds, s, a);
   return hip_fail(hipGetLastError(), "tiled_kernel launch");
 }
 
@@ -386,10 +469,15 @@ typedef Shape<MOE_TILED_SHAPE> DefaultShape;
 
 }  // namespace
 
-int launch_tiled(StreamMode mode, const StreamArgs& a, hipStream_t s) {
-  if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape>(a, s);
-  if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape>(a, s);
-  return fail(MOE_E_BADARG, "tiled kernel: bad mode");
+int launch_tiled(StreamMode mode, int weight_format, const StreamArgs& a, hipStream_t s) {
+  if (weight_format == 2) {
+    if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 2>(a, s);
+    if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 2>(a, s);
+  } else if (weight_format == 1) {
+    if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 1>(a, s);
+    if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 1>(a, s);
+  }
+  return fail(MOE_E_BADARG, "tiled kernel: bad mode or weight format");
 }
 
 }  // namespace mm

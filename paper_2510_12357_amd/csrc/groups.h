@@ -35,6 +35,14 @@ __device__ __forceinline__ P* uniform(P* p) {
 
 __device__ __forceinline__ int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+// 8 E4M3 codes (two dwords, k ascending with the byte address) -> 8 bf16, exactly.
+__device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
+  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
+  const auto c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
+  return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
+}
+
 // One group of the grouped GEMM, fully resolved on the device (kept in LDS).
 struct Group {
   int m;            // token rows

@@ -218,12 +218,6 @@ struct Smem {
   unsigned char mx_scale[WB == 0 ? 2 : 1][WB == 0 ? Fmt<WB>::kRows * Fmt<WB>::kCols : 16];
 };
 
-// 8 E4M3 codes (two dwords, k ascending with the byte address) -> 8 bf16, exactly.
-__device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
-  const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(lo, false), b = __builtin_amdgcn_cvt_pk_f32_fp8(lo, true);
-  const auto c = __builtin_amdgcn_cvt_pk_f32_fp8(hi, false), d = __builtin_amdgcn_cvt_pk_f32_fp8(hi, true);
-  return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
-}
 
 // 8 E2M1 codes (one dword, k ascending with the nibble address) times the block scale (a power of
 // two as fp32) -> 8 bf16, exactly while the products stay in bf16's range.

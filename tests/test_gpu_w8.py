@@ -10,7 +10,7 @@ import oracle
 from paper_2510_12357_amd import binding as mm
 from paper_2510_12357_amd import workloads as wl
 from gpu_util import TOL_OUT, DeviceLayer, out_to_f64, rel_err, run_gpu_layer, run_oracle_layer
-from test_gpu_parity import check_layer
+from test_gpu_parity import check_layer, check_sampled_prefill
 
 pytestmark = pytest.mark.gpu
 
@@ -39,10 +39,37 @@ def test_fine60_decode_full_size(T):
     check_layer(wl.CONFIGS["fine60_decode"].with_(T=T, dtype="bf16w8"), seed=0)
 
 
+@pytest.mark.parametrize("T,seed", [(256, 4), (300, 6), (700, 7)])
+def test_tiled_regime_small_ragged(T, seed):
+    # T >= 256: the LDS-tiled kernel; ragged token tiles, weight tiles and K tails (K = 272, 144, 80: a
+    # partial last chunk of 64), experts without tokens, a shared expert cut into K chunks
+    check_layer(cfg_w8(T=T, fallback_ratio=0.3), seed=seed)
+    check_layer(cfg_w8(T=T, H=528, E=5, I=400, k_big=2, k_little=1, shared_I=(1200, 48), fallback_ratio=0.5), seed=seed + 10)
+
+
+def test_tiled_regime_every_code():
+    """T >= 256: all 256 codes in every position of a 16-byte column, in gate rows of one expert."""
+    check_every_code(T=256)
+
+
+def test_fine64_prefill_full_size_sampled():
+    cfg = wl.CONFIGS["fine64_prefill"].with_(dtype="bf16w8")
+    layer = wl.make_layer(cfg, seed=0)
+    dl = DeviceLayer(layer)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    b = run_gpu_layer(dl, logits=logits)
+    _, tokens = check_sampled_prefill(cfg, layer, b, logits, n_random=160, seed=0)
+    assert len(tokens) >= 256
+
+
 def test_every_code_reaches_the_sum_with_its_value():
+    check_every_code(T=16)
+
+
+def check_every_code(T):
     """One expert whose W_gate rows hold all 256 codes: the layer output equals the oracle's, i.e.
     the kernel's widening agrees with the format for every code that is not NaN."""
-    cfg = cfg_w8(T=16, H=256, E=2, I=16, k_big=1, k_little=1, shared_I=())
+    cfg = cfg_w8(T=T, H=256, E=2, I=16, k_big=1, k_little=1, shared_I=())
     layer = wl.make_layer(cfg, seed=5)
     codes = np.arange(256, dtype=np.uint8)
     codes[codes == 0x7F] = 0x7E
@@ -85,7 +112,7 @@ def test_limits_and_blob_size():
     assert mm.moe_expert_blob_bytes(mm.make_config(cfg.with_(dtype="bf16")), cfg.I) == 6 * cfg.H * cfg.I
     assert mm.moe_expert_blob_bytes(c, 12) == 0
     lib = mm.load_library()
-    for bad in (cfg.with_(T=256), cfg.with_(H=264), cfg.with_(I=136), cfg.with_(shared_I=(72,))):
+    for bad in (cfg.with_(H=264), cfg.with_(I=136), cfg.with_(shared_I=(72,))):
         cb = mm.make_config(bad)
         rc = lib.moe_combine(ctypes.byref(cb), None, None, None, None, None, None, None)
         assert rc == -3, (bad, rc)
