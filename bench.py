@@ -68,8 +68,12 @@ def workload_config(name: str, ratio: float):
         return wl.CONFIGS["fine64_prefill"].with_(fallback_ratio=ratio)
     if name == "fine64_prefill_w8":
         return wl.CONFIGS["fine64_prefill"].with_(fallback_ratio=ratio, dtype="bf16w8")
+    if name == "fine64_prefill_mx4":
+        return wl.CONFIGS["fine64_prefill"].with_(fallback_ratio=ratio, dtype="bf16mx4")
     if name == "coarse8_prefill":
         return wl.CONFIGS["coarse8"].with_(fallback_ratio=ratio)
+    if name == "coarse8_prefill_mx4":
+        return wl.CONFIGS["coarse8"].with_(fallback_ratio=ratio, dtype="bf16mx4")
     if name == "coarse8_prefill_w8":
         return wl.CONFIGS["coarse8"].with_(fallback_ratio=ratio, dtype="bf16w8")
     if name.startswith("coarse8_decode_b"):

@@ -32,7 +32,7 @@
  *     8 bits with one fp32 scale per weight row, which halves the bytes a decode step streams
  *     from HBM and the memory a layer takes.  It needs H, I and every shared_I to be multiples
  *     of 16.
- *     dtype MOE_BF16_MXFP4 (decode regime only, T < 256; not in the paper): as MOE_BF16, but
+ *     dtype MOE_BF16_MXFP4 (not in the paper): as MOE_BF16, but
  *     the expert weights are stored in the OCP microscaling format MXFP4 (4-bit elements with one
  *     power-of-two scale per 32 weights along the contraction): 4.25 bits per weight.  It needs
  *     H, I and every shared_I to be multiples of 128; moe_layer_decode does not take it.

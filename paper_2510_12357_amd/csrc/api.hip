@@ -75,8 +75,7 @@ int device_cu_count() {
   return cached_cu;
 }
 
-// Steps of this many tokens and more run the LDS-tiled kernels (bf16 and 8-bit weights; MXFP4
-// weights exist for the streaming kernel only).
+// Steps of this many tokens and more run the LDS-tiled kernels (bf16 activations).
 constexpr int kTiledMinT = 256;
 
 int validate_config(const moe_config* c) {
@@ -111,8 +110,6 @@ int validate_config(const moe_config* c) {
     if (!ok) return fail(MOE_E_UNSUPPORTED, "8-bit expert weights need H, I and every shared_I to be multiples of 16");
   }
   if (c->dtype == MOE_BF16_MXFP4) {
-    if (c->T >= kTiledMinT)
-      return fail(MOE_E_UNSUPPORTED, "MXFP4 expert weights are for the decode regime: T=%d, limit %d", c->T, kTiledMinT - 1);
     // a scale block is 32 weights along the contraction; the kernel fetches the scale bytes of a
     // row 16 at a time with 4-byte aligned loads, so a row must hold a multiple of 4 of them
     bool ok = c->H % 128 == 0 && c->I % 128 == 0;
@@ -335,8 +332,8 @@ extern "C" int moe_expert_ffn(const moe_config* cfg, const void* x, const int32_
   hipStream_t s = static_cast<hipStream_t>(stream);
   // Regime: with many tokens per step the experts see enough rows for LDS-tiled MFMA GEMMs;
   // below that the weights are streamed once through the skinny kernel.
-  const bool tiled = (cfg->dtype == MOE_BF16 || cfg->dtype == MOE_BF16_W8) && cfg->T >= kTiledMinT;
-  const int wfmt = cfg->dtype == MOE_BF16_W8 ? 1 : 2;
+  const bool tiled = cfg->dtype != MOE_FP32 && cfg->T >= kTiledMinT;
+  const int wfmt = cfg->dtype == MOE_BF16_W8 ? 1 : (cfg->dtype == MOE_BF16_MXFP4 ? 0 : 2);
   {
     ProfScope ps(kProfFfnGateUp, s);
     rc = tiled ? launch_tiled(kGateUp, wfmt, a, s) : launch_stream(kGateUp, cfg->dtype, a, s);

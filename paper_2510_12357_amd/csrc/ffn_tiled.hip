@@ -35,6 +35,12 @@
 //     wave widens the codes of the next k-step to bf16 (exact) between the MFMAs of the current one,
 //     and the row scale multiplies the fp32 sum in the epilogue.  Tokens, tile shape, pipeline and
 //     tile order are those of the bf16 kernel.
+//   * MXFP4 weights (WB = 0: 4-bit E2M1 codes, one E8M0 scale per 32 k): a weight tile row is 32
+//     bytes (32 rows per load instruction, key (row >> 3) & 1).  The 16 bytes a lane reads per
+//     column tile and chunk are the 32 codes of ONE scale block, i.e. of all four k-steps of the
+//     chunk: k-step e takes, in the lanes of half h, the 8 k behind 32 h + 8 e.  The lane fetches
+//     that block's scale byte itself, one chunk ahead, with a byte load (4 per lane and chunk),
+//     and code x scale is widened to bf16 in one instruction per two codes (exact).
 #include <atomic>
 #include <type_traits>
 
@@ -70,14 +76,19 @@ __device__ __forceinline__ constexpr int row_key(int row) { return (row >> kKeyS
 // Weight rows of a tile in LDS, by weight format (WB bytes per weight).
 template <int WB>
 struct WFmt {
-  static_assert(WB == 1 || WB == 2, "bf16 or 8-bit weights");
-  static constexpr int kRowB = BK * WB;              // bytes of a weight tile row
+  static_assert(WB == 0 || WB == 1 || WB == 2, "bf16, 8-bit or MXFP4 weights");
+  static constexpr int kRowB = WB ? BK * WB : BK / 2;   // bytes of a weight tile row
   static constexpr int kCols = kRowB / 16;           // its 16-byte columns
   static constexpr int kRowsPerIns = 1024 / kRowB;   // tile rows that one load instruction fills
-  static constexpr int kPerCol = 16 / WB;            // weights per 16-byte column
+  static constexpr int kPerCol = WB ? 16 / WB : 32;  // weights per 16-byte column
+  static constexpr int kStepsPerRead = WB == 2 ? 1 : (WB == 1 ? 2 : 4);   // MFMA k-steps fed by one 16-byte fragment read
+  static_assert(WB != 0 || BK == 64, "MXFP4: a chunk is two scale blocks");
   // 64-byte rows: four rows share 256 bytes of LDS, and 16 consecutive rows get every key once per
-  // residue of the row number mod 4
-  static __device__ __forceinline__ constexpr int key(int row) { return WB == 2 ? row_key(row) : (row >> 2) & (kCols - 1); }
+  // residue of the row number mod 4; 32-byte rows: eight rows share 256 bytes
+  static __device__ __forceinline__ constexpr int key(int row) {
+    return WB == 2 ? row_key(row) : (WB == 1 ? (row >> 2) & 3 : (row >> 3) & 1);
+  }
+  static __device__ __forceinline__ constexpr unsigned bytes(unsigned n) { return WB ? n * (unsigned)WB : n / 2u; }
 };
 
 // vmcnt(n): bits [3:0] and [15:14]; expcnt and lgkmcnt left at their maxima (no wait)
@@ -120,7 +131,7 @@ struct Shape {
   static constexpr int kInsA = BM / kRowsPerIns / kWaves;      // token-row load instructions per wave and chunk
   template <int WB> static constexpr int ins_b() { return BNR / WFmt<WB>::kRowsPerIns / kWaves; }   // weight-row ones
   template <int WB> static constexpr int stage_bytes() { return BM * kRowB + BNR * WFmt<WB>::kRowB; }
-  static_assert(BM % (kRowsPerIns * kWaves) == 0 && BNR % (16 * kWaves) == 0, "tile rows must divide evenly");
+  static_assert(BM % (kRowsPerIns * kWaves) == 0 && BNR % (32 * kWaves) == 0, "tile rows must divide evenly");
   static_assert((TM == 2 || TM == 4) && (TN == 2 || TN == 4), "the fragment reads are written for 2 or 4 MFMA tiles per wave and side");
 };
 
@@ -234,12 +245,12 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
         unsigned extra = 0;
         if (MODE == kGateUp) {
           n = n0 + (br % (BNR / 2));
-          if (br >= BNR / 2) extra = (unsigned)G.N * (unsigned)G.ldw * (unsigned)WB;
+          if (br >= BNR / 2) extra = (unsigned)G.N * WF::bytes((unsigned)G.ldw);
         } else {
           n = n0 + br;
         }
         bcol[p] = (ld_pcw ^ WF::key(br)) * WF::kPerCol;
-        boff[p] = (n < G.N ? (unsigned)n * (unsigned)G.ldw * (unsigned)WB + extra : kOob) + (unsigned)bcol[p] * (unsigned)WB;
+        boff[p] = (n < G.N ? (unsigned)n * WF::bytes((unsigned)G.ldw) + extra : kOob) + WF::bytes((unsigned)bcol[p]);
       }
       // chunk `kt` into stage `st`, then step the offsets to the next chunk
       auto issue = [&](int st, int kt) {
@@ -301,20 +312,36 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
     // one k-step earlier).  The fragments of the first k-step of chunk kt are read right behind
     // it, under those MFMAs.
     constexpr int kParts = BK / 16;
+    // MXFP4: the scale bytes of this lane's weight rows, one row of ldw / 32 bytes per weight row
+    // (gate/up: the up rows follow the N gate rows); a lane of half h needs block 2 kt + h of chunk kt
+    unsigned sc_row[TN];
+    __amdgpu_buffer_rsrc_t rsc = make_rsrc(a.x, 0);
+    if constexpr (WB == 0) {
+      const unsigned blocks = (unsigned)G.ldw >> 5;
+      rsc = make_rsrc(G.scale, (unsigned)((MODE == kGateUp ? 2 : 1) * G.N - 1) * blocks + ((unsigned)K >> 5));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        int n;
+        if (MODE == kGateUp) n = n0 + wn * (TN / 2) * 32 + (j % (TN / 2)) * 32 + (lane & 31);
+        else n = n0 + wn * TN * 32 + j * 32 + (lane & 31);
+        sc_row[j] = n < G.N ? (unsigned)((MODE == kGateUp && j >= TN / 2 ? G.N : 0) + n) * blocks : kOob;
+      }
+    }
     auto main_loop = [&](auto nb_tag) {
       constexpr int NB = decltype(nb_tag)::value;          // token blocks in use: 1 .. TM
       // token fragments of k-step kk of the chunk in stage st (8-bit weights: k-step 2p + e reads
       // the 16-byte column 4p + 2h + e, see the head of the file)
       auto read_a = [&](int st, int kk, bf16x8 (&fa)[TM]) {
-        const unsigned lc = WB == 2 ? (unsigned)(kk * 2 + (lane >> 5)) : (unsigned)((kk >> 1) * 4 + (lane >> 5) * 2 + (kk & 1));
+        const unsigned lc = WB == 2 ? (unsigned)(kk * 2 + (lane >> 5))
+                          : (WB == 1 ? (unsigned)((kk >> 1) * 4 + (lane >> 5) * 2 + (kk & 1)) : (unsigned)((lane >> 5) * 4 + kk));
         const unsigned col = (lc ^ fkey) * 16u + (unsigned)(st * kStageBytes);
         if constexpr (NB == 1) frag_read1<0>(fa[0], a_rd + col);
         else frag_read2<0, kJ>(fa[0], fa[1], a_rd + col);
         if constexpr (NB == 3) frag_read1<2 * kJ>(fa[2], a_rd + col);
         if constexpr (NB == 4) frag_read2<2 * kJ, 3 * kJ>(fa[2], fa[3], a_rd + col);
       };
-      // weight fragments, 16 bytes per lane and column tile: bf16, the 8 k of k-step kk; 8-bit, the
-      // 2 x 8 codes of the k-steps 2c and 2c + 1
+      // weight fragments, 16 bytes per lane and column tile: bf16, the 8 k of k-step c; 8-bit, the
+      // 2 x 8 codes of the k-steps 2c and 2c + 1; MXFP4 (c = 0), the 4 x 8 codes of the chunk
       auto read_b = [&](int st, int c, bf16x8 (&fb)[TN]) {
         const unsigned lc = (unsigned)(c * 2 + (lane >> 5));
         const unsigned col = (lc ^ (WB == 2 ? fkey : fkeyw)) * 16u + (unsigned)(st * kStageBytes);
@@ -326,18 +353,38 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
         }
       };
       bf16x8 fa[2][TM] = {}, fb[2][TN];
-      bf16x8 fr[TN];                                       // 8-bit weights: the codes of a pair of k-steps
-      auto widen = [&](bf16x8 (&dst)[TN], int e) {         // those of its k-step e
+      bf16x8 fr[TN];                                       // narrow formats: the codes of kPer k-steps
+      constexpr int kPer = WF::kStepsPerRead;
+      // MXFP4: the scale of this lane's block of the chunk, per column tile: in use (as fp32) and
+      // being loaded for the next chunk (as a byte)
+      float scf[TN];
+      unsigned scn[TN];
+      auto load_mx_scales = [&](int kt) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          scn[j] = __builtin_amdgcn_raw_buffer_load_b8(rsc, (int)(sc_row[j] == kOob ? kOob : sc_row[j] + (unsigned)(kt * 2 + (lane >> 5))), 0, 0);
+      };
+      auto take_mx_scales = [&]() {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) scf[j] = e8m0_to_f32(scn[j] & 0xffu);
+      };
+      auto widen = [&](bf16x8 (&dst)[TN], int e) {         // k-step e of the kPer in fr
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           const i32x4 w = __builtin_bit_cast(i32x4, fr[j]);
-          dst[j] = e ? widen_e4m3(w[2], w[3]) : widen_e4m3(w[0], w[1]);
+          if constexpr (WB == 1) dst[j] = e ? widen_e4m3(w[2], w[3]) : widen_e4m3(w[0], w[1]);
+          else dst[j] = widen_mx4(w[e & 3], scf[j]);
         }
       };
+      if constexpr (WB == 0) { load_mx_scales(0); }
       lds_barrier();                                       // barrier 0
       read_a(0, 0, fa[0]);
       if constexpr (WB == 2) { read_b(0, 0, fb[0]); frag_wait(fa[0]); frag_wait(fb[0]); }
-      else { read_b(0, 0, fr); frag_wait(fa[0]); frag_wait(fr); widen(fb[0], 0); }
+      else {
+        read_b(0, 0, fr); frag_wait(fa[0]); frag_wait(fr);
+        if constexpr (WB == 0) { take_mx_scales(); load_mx_scales(1); }
+        widen(fb[0], 0);
+      }
       int st = 0;                                          // stage of chunk kt
       for (int kt = 0; kt < nk; ++kt) {
         const int st_nx = st + 1 == kStages ? 0 : st + 1;  // stage of chunk kt+1
@@ -359,16 +406,21 @@ __global__ __launch_bounds__(SH::kThreads) MOE_TILED_ATTR void tiled_kernel(cons
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
             frag_wait(fa[nxt]); frag_wait(fb[nxt]);
           } else {
-            // Even k-step: the codes of the odd one are in fr already.  Odd k-step: fr is free (both
-            // halves widened) and takes the next pair.  The codes of the next k-step are widened behind
-            // the first token block's MFMAs, so that the conversions run while the matrix unit works.
-            if (kk & 1) read_b(st_rd, kk_rd >> 1, fr);
+            // fr holds the codes of kPer k-steps.  In the last of them fr is free (everything widened)
+            // and takes the next kPer; in the others the codes of the next k-step are in fr already.
+            // They are widened behind the first token block's MFMAs, so that the conversions run while
+            // the matrix unit works.
+            const bool kRead = (kk % kPer) == kPer - 1;     // known after unrolling
+            if (kRead) read_b(st_rd, kk_rd / kPer, fr);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
               acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][0], fb[cur][j], acc[0][j], 0, 0, 0);
             frag_wait(fa[nxt]);
-            if (kk & 1) frag_wait(fr);
-            widen(fb[nxt], (kk & 1) ? 0 : 1);
+            if (kRead) frag_wait(fr);
+            if constexpr (WB == 0) {
+              if (kRead) { take_mx_scales(); load_mx_scales(kt + 2); }   // the next chunk's scales in use, the one after on its way
+            }
+            widen(fb[nxt], (kk + 1) % kPer);
 #pragma unroll
             for (int i = 1; i < NB; ++i)
 #pragma unroll
@@ -476,6 +528,9 @@ int launch_tiled(StreamMode mode, int weight_format, const StreamArgs& a, hipStr
   } else if (weight_format == 1) {
     if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 1>(a, s);
     if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 1>(a, s);
+  } else if (weight_format == 0) {
+    if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 0>(a, s);
+    if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 0>(a, s);
   }
   return fail(MOE_E_BADARG, "tiled kernel: bad mode or weight format");
 }

@@ -43,6 +43,21 @@ __device__ __forceinline__ bf16x8 widen_e4m3(int lo, int hi) {
   return bf16x8{(__bf16)a[0], (__bf16)a[1], (__bf16)b[0], (__bf16)b[1], (__bf16)c[0], (__bf16)c[1], (__bf16)d[0], (__bf16)d[1]};
 }
 
+// 8 E2M1 codes (one dword, k ascending with the nibble address) times the block scale (a power of
+// two as fp32) -> 8 bf16, exactly while the products stay in bf16's range.
+__device__ __forceinline__ bf16x8 widen_mx4(int codes, float scale) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 0);
+  const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 1);
+  const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 2);
+  const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4((unsigned)codes, scale, 3);
+  return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+// An E8M0 byte as fp32: 2^(b - 127); 0 is the subnormal 2^-127, 255 is NaN.
+__device__ __forceinline__ float e8m0_to_f32(unsigned b) {
+  return __uint_as_float(b == 0 ? 0x00400000u : (b == 255 ? 0x7fc00000u : b << 23));
+}
+
 // One group of the grouped GEMM, fully resolved on the device (kept in LDS).
 struct Group {
   int m;            // token rows

@@ -92,7 +92,7 @@ int launch_stream(StreamMode mode, int dtype, const StreamArgs& a, hipStream_t s
 int launch_stream_lds(StreamMode mode, int weight_format, const StreamArgs& a, hipStream_t s);
 
 // ---- large-m grouped GEMM on LDS-tiled MFMA (prefill regime; bf16 activations) ---------------
-// weight_format: 2 = bf16, 1 = 8-bit codes with row scales
+// weight_format: 2 = bf16, 1 = 8-bit codes with row scales, 0 = MXFP4
 int launch_tiled(StreamMode mode, int weight_format, const StreamArgs& a, hipStream_t s);
 
 // ---- a whole decode step in one launch (decode_step.hip) -------------------------------------

@@ -10,7 +10,7 @@ import oracle
 from paper_2510_12357_amd import binding as mm
 from paper_2510_12357_amd import workloads as wl
 from gpu_util import TOL_OUT, DeviceLayer, out_to_f64, rel_err, run_gpu_layer, run_oracle_layer
-from test_gpu_parity import check_layer
+from test_gpu_parity import check_layer, check_sampled_prefill
 
 pytestmark = pytest.mark.gpu
 
@@ -39,11 +39,37 @@ def test_fine60_decode_full_size(T):
     check_layer(wl.CONFIGS["fine60_decode"].with_(T=T, dtype="bf16mx4"), seed=0)
 
 
+@pytest.mark.parametrize("T,seed", [(256, 4), (300, 6), (700, 7)])
+def test_tiled_regime_small_ragged(T, seed):
+    # T >= 256: the LDS-tiled kernel; ragged token and weight tiles, several 64-k chunks per contraction,
+    # experts without tokens, a shared expert cut into K chunks
+    check_layer(cfg_mx(T=T, fallback_ratio=0.3), seed=seed)
+    check_layer(cfg_mx(T=T, H=640, E=5, I=384, k_big=2, k_little=1, shared_I=(1152, 128), fallback_ratio=0.5), seed=seed + 10)
+
+
+def test_tiled_regime_every_code_and_scales():
+    check_every_code(T=256)
+
+
+def test_fine64_prefill_full_size_sampled():
+    cfg = wl.CONFIGS["fine64_prefill"].with_(dtype="bf16mx4")
+    layer = wl.make_layer(cfg, seed=0)
+    dl = DeviceLayer(layer)
+    logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
+    b = run_gpu_layer(dl, logits=logits)
+    _, tokens = check_sampled_prefill(cfg, layer, b, logits, n_random=160, seed=0)
+    assert len(tokens) >= 256
+
+
 def test_every_code_and_a_range_of_scales_reach_the_sum():
+    check_every_code(T=16)
+
+
+def check_every_code(T):
     """One expert whose W_gate rows hold all 16 codes in every position of a block, under block
     scales from 2^-20 to 2^6: the layer output equals the oracle's, i.e. the kernel's widening agrees
     with the format for every code, and its scales sit with the right rows and blocks."""
-    cfg = cfg_mx(T=16, H=256, E=2, I=128, k_big=1, k_little=1, shared_I=())
+    cfg = cfg_mx(T=T, H=256, E=2, I=128, k_big=1, k_little=1, shared_I=())
     layer = wl.make_layer(cfg, seed=5)
     HI = cfg.H * cfg.I
     for e in range(cfg.E):
@@ -83,7 +109,7 @@ def test_limits_and_blob_size():
     assert mm.moe_expert_blob_bytes(c, cfg.I) == wl.mx4_blob_bytes(cfg.H, cfg.I) == wl.make_expert_blob(cfg, 0, 0).size
     assert mm.moe_expert_blob_bytes(c, cfg.shared_I[0]) == wl.mx4_blob_bytes(cfg.H, cfg.shared_I[0])
     lib = mm.load_library()
-    for bad in (cfg.with_(T=256), cfg.with_(H=288), cfg.with_(I=160), cfg.with_(shared_I=(96,))):
+    for bad in (cfg.with_(H=288), cfg.with_(I=160), cfg.with_(shared_I=(96,))):
         cb = mm.make_config(bad)
         rc = lib.moe_combine(ctypes.byref(cb), None, None, None, None, None, None, None)
         assert rc == -3, (bad, rc)
