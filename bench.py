@@ -699,6 +699,28 @@ def time_workload(mm, torch, cfg, steps: int, warmup: int, L: int = 0, profile: 
     return res
 
 
+def time_plain_read(mm, torch, gib: int = 2, reps: int = 10):
+    """What a kernel that only reads gets out of the memory of this device: the library's plain
+    streaming-read kernel over a buffer far larger than the caches (context for the roofline
+    fractions, which are quoted against the published 8 TB/s)."""
+    buf = torch.ones(gib << 28, dtype=torch.int32, device="cuda")          # gib GiB
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for _ in range(2):
+        mm.moe_profile_plain_read(buf, sink)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        mm.moe_profile_plain_read(buf, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    gbs = buf.numel() * 4 / (us * 1e-6) / 1e9
+    del buf
+    torch.cuda.empty_cache()
+    return dict(bytes=gib << 30, us_per_pass=us, GBps=gbs, frac_of_published_peak=gbs / HBM_PEAK_GBS,
+                note="moe_profile_plain_read: 16-byte loads, 8 in flight per lane, 8192 workgroups")
+
+
 def algorithmic_work(cfg, P: float, D: float):
     """Bytes and flops one step must move / do (weights of the D touched experts once, the shared
     experts, the router, activations in and out; flops of the P pair FFNs, shared FFNs, router)."""
@@ -943,6 +965,7 @@ def main():
 
     if not args.no_extra:
         others = {}
+        extra["plain_read"] = time_plain_read(mm, torch)
         k2, w2 = max(20, args.steps // 4), max(5, args.warmup // 2)
         names = [n for n in ("fine60_decode_b1", "fine60_decode_b8", "fine60_decode_b32", "fine60_decode_b64",
                              "fine64_prefill", "coarse8_prefill", "coarse8_decode_b1", "tiny_fp32",

@@ -114,6 +114,12 @@ int moe_device_info(int32_t* n_cu, int32_t* is_gfx950);
 int moe_profile_enable(int on);
 int moe_profile_read(int kind, int64_t* launches, double* total_ms);
 
+/* Measurement aid, not part of the method: one kernel that reads `bytes` bytes of the device
+ * buffer `buf` (16-byte aligned) once and does nothing else, enqueued on `stream`.  Timing it gives
+ * the read bandwidth the device delivers to a plain streaming kernel, the yardstick next to the
+ * published peak.  `sink` is a device int32 the kernel may write (it does not for ordinary data). */
+int moe_profile_plain_read(const void* buf, size_t bytes, int32_t* sink, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Selection stage (Sec. II-A) with the big-little rule (Sec. III-A, Alg. 1).
  *

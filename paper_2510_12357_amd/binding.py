@@ -25,7 +25,7 @@ MOE_OK = 0
 ERRORS = {-1: "MOE_E_BADARG", -2: "MOE_E_SHAPE", -3: "MOE_E_UNSUPPORTED", -4: "MOE_E_HIP",
           -5: "MOE_E_CACHE_FULL", -6: "MOE_E_WORKSPACE"}
 
-EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence",
+EXPORTS = ("moe_last_error", "moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_profile_plain_read", "moe_route", "moe_token_confidence",
            "moe_dispatch_workspace_bytes", "moe_dispatch", "moe_dispatch_from", "moe_combine_add",
            "moe_expert_ffn_workspace_bytes", "moe_expert_blob_bytes",
            "moe_shared_out_slabs", "moe_layer_decode_workspace_bytes", "moe_layer_decode_init",
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.moe_profile_enable.argtypes = [ctypes.c_int]
     lib.moe_profile_read.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int64),
                                      ctypes.POINTER(ctypes.c_double)]
+    lib.moe_profile_plain_read.argtypes = [vp, sz, vp, vp]
     lib.moe_route.argtypes = [cfgp, vp, vp, vp, vp, vp, ctypes.c_int, vp, vp, vp, vp, vp]
     lib.moe_token_confidence.argtypes = [vp, i32, i32, vp, vp]
     lib.moe_dispatch_workspace_bytes.argtypes = [cfgp]
@@ -132,7 +133,7 @@ def load_library() -> ctypes.CDLL:
     for name in ("moe_prefetcher_set_in_flight_limit", "moe_prefetcher_set_yield_to_demand", "moe_prefetcher_predict", "moe_prefetcher_predicted",
                  "moe_prefetcher_advance"):
         getattr(lib, name).restype = ctypes.c_int
-    for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_route", "moe_token_confidence", "moe_dispatch",
+    for name in ("moe_device_info", "moe_profile_enable", "moe_profile_read", "moe_profile_plain_read", "moe_route", "moe_token_confidence", "moe_dispatch",
                  "moe_dispatch_from", "moe_combine_add",
                  "moe_expert_ffn", "moe_combine", "expert_cache_fetch", "moe_expert_ffn_cached", "moe_cache_snapshot",
                  "moe_cache_sync", "moe_cache_set_prefetch_limit", "moe_cache_emulate_link"):
@@ -191,6 +192,11 @@ PROFILE_KINDS = ("router_gemm", "route_topk", "dispatch", "ffn_gate_up", "ffn_do
 
 def moe_profile_enable(on: bool) -> None:
     _check(load_library().moe_profile_enable(int(bool(on))))
+
+
+def moe_profile_plain_read(buf, sink) -> None:
+    """One plain streaming read of the tensor `buf` on the current stream (measurement aid)."""
+    _check(load_library().moe_profile_plain_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream(None)))
 
 
 def moe_profile_read(kind: int):

@@ -499,3 +499,16 @@ def test_one_launch_router_equals_the_two_kernels(dtype, T, E, kb):
     np.testing.assert_allclose(b1.topk_w.cpu().numpy(), w, rtol=2e-6, atol=1e-9)
     assert rel_err(b1.logits.cpu().numpy(), oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)) <= \
         (TOL_OUT if dtype == "bf16" else 1e-4)
+
+
+def test_plain_read_measurement_aid():
+    """The plain streaming-read kernel runs over an odd-sized buffer, leaves ordinary data and its
+    sink alone, and refuses a misaligned buffer."""
+    buf = torch.arange(3 * 1024 * 1024 + 5, dtype=torch.int32, device="cuda")
+    keep = buf.clone()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    mm.moe_profile_plain_read(buf, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, keep) and int(sink.item()) == 0
+    with pytest.raises(mm.MoeError):
+        mm.moe_profile_plain_read(buf[1:], sink)
