@@ -644,13 +644,13 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
       if (real && (k + 1) * KC <= it.K) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16, (int)addr[i], 0, 0, 0);
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16, (int)addr[i], 0, 0, kStreamOnce);
       } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int kk = k * KC + (int)a_col[i] * (16 / WB);
           __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(stage + i * 1024), 16,
-                                                   (int)((real && kk < it.K) ? addr[i] : kOob), 0, 0, 0);
+                                                   (int)((real && kk < it.K) ? addr[i] : kOob), 0, 0, kStreamOnce);
         }
       }
       if (real) {

@@ -10,6 +10,9 @@ namespace {
 
 constexpr int kMaxGroups = MOE_MAX_EXPERTS + kMaxSlabs;
 constexpr unsigned kOob = 0x80000000u;   // offset no buffer reaches (every buffer is < 2 GiB)
+// cache policy of the decode kernels' weight loads ("nt"): a weight is read once per step, so its
+// lines are the first to leave the caches again and the activations stay
+constexpr int kStreamOnce = 2;
 
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
