@@ -75,7 +75,7 @@ constexpr int kReads = kRowBytes / 16 / 4 / kKParts;
 #define MOE_DECODE_ST_AUX 16
 #endif
 #ifndef MOE_DECODE_POLL_SLEEP
-#define MOE_DECODE_POLL_SLEEP 48
+#define MOE_DECODE_POLL_SLEEP 16
 #endif
 constexpr int kCoherent = 16;                // cache policy bit sc1 of buffer loads / stores: coherent across the device
 constexpr int kCoherentLd = MOE_DECODE_LD_AUX, kCoherentSt = MOE_DECODE_ST_AUX;   // the bulk data: activations, y
