@@ -970,7 +970,7 @@ def main():
         names = [n for n in ("fine60_decode_b1", "fine60_decode_b8", "fine60_decode_b32", "fine60_decode_b64",
                              "fine64_prefill", "coarse8_prefill", "coarse8_decode_b1", "tiny_fp32",
                              "fine60_decode_b1_w8", "fine60_decode_b64_w8", "fine60_decode_b1_mx4",
-                             "fine60_decode_b64_mx4") if n != args.workload]
+                             "fine60_decode_b64_mx4", "fine64_prefill_w8", "fine64_prefill_mx4") if n != args.workload]
         for name in names:
             c2 = workload_config(name, args.ratio)
             r2 = time_workload(mm, torch, c2, k2, w2)
