@@ -525,13 +525,16 @@ int launch_tiled(StreamMode mode, int weight_format, const StreamArgs& a, hipStr
   if (weight_format == 2) {
     if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 2>(a, s);
     if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 2>(a, s);
-  } else if (weight_format == 1) {
+  }
+#if MOE_TILED_BK == 64   // the narrow formats are written for 64-k chunks
+  else if (weight_format == 1) {
     if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 1>(a, s);
     if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 1>(a, s);
   } else if (weight_format == 0) {
     if (mode == kGateUp) return launch_tiled_shape<kGateUp, DefaultShape, 0>(a, s);
     if (mode == kDown) return launch_tiled_shape<kDown, DefaultShape, 0>(a, s);
   }
+#endif
   return fail(MOE_E_BADARG, "tiled kernel: bad mode or weight format");
 }
 
