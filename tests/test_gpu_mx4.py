@@ -88,8 +88,10 @@ def check_every_code(T):
     assert rel_err(out_to_f64(b.out), ref["out"]) <= TOL_OUT
 
 
-def test_little_pass_then_fallback_pass():
-    cfg = cfg_mx(T=48, shared_I=(128,))
+@pytest.mark.parametrize("T", [48, 300])
+def test_little_pass_then_fallback_pass(T):
+    # T = 300: both passes in the tiled regime, the second with routed experts only
+    cfg = cfg_mx(T=T, shared_I=(128,))
     layer = wl.make_layer(cfg, seed=8)
     dl = DeviceLayer(layer)
     logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)

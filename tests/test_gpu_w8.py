@@ -89,8 +89,10 @@ def check_every_code(T):
     assert rel_err(out_to_f64(b.out), ref["out"]) <= TOL_OUT
 
 
-def test_little_pass_then_fallback_pass():
-    cfg = cfg_w8(T=48, shared_I=(80,))
+@pytest.mark.parametrize("T", [48, 300])
+def test_little_pass_then_fallback_pass(T):
+    # T = 300: both passes in the tiled regime, the second with routed experts only
+    cfg = cfg_w8(T=T, shared_I=(80,))
     layer = wl.make_layer(cfg, seed=8)
     dl = DeviceLayer(layer)
     logits = oracle.gate_logits(layer.x, layer.Wg, layer.gate_bias)
