@@ -720,7 +720,7 @@ def time_plain_read(mm, torch, gib: int = 2, reps: int = 10):
     del buf
     torch.cuda.empty_cache()
     return dict(bytes=gib << 30, us_per_pass=us, GBps=gbs, frac_of_published_peak=gbs / HBM_PEAK_GBS,
-                note="moe_profile_plain_read: 16-byte loads, 8 in flight per lane, 8192 workgroups")
+                note="moe_profile_plain_read: one workgroup of four waves per CU, 16 non-temporal 16-byte loads in flight per lane")
 
 
 def algorithmic_work(cfg, P: float, D: float):
