@@ -172,8 +172,10 @@ _SIDE = {}
 
 def side_stream(torch):
     """Second stream (default priority) on which the shared experts run under the router kernels."""
-    # Off by default: it gained 3-4 % at 64 tokens but costs more than it hides at small batches,
-    # and it splits the dominant kernel into two launches.  MOE_BENCH_OVERLAP=1 turns it on.
+    # Off by default: with the current kernels it LOSES (60-expert layer, us per step with / without:
+    # b = 24 164 / 148, b = 32 188 / 167, b = 64 235 / 205): two persistent launches on two streams take
+    # each other's CUs, and the dominant kernel is split into two launches.  MOE_BENCH_OVERLAP=1 turns
+    # it on.
     if "s" not in _SIDE:
         _SIDE["s"] = torch.cuda.Stream() if os.environ.get("MOE_BENCH_OVERLAP") else None
     return _SIDE["s"]
