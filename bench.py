@@ -959,6 +959,8 @@ def main():
     cpu_in = None if args.no_cpu else cpu_inputs(torch, cfg, main_res["_layers"])
 
     step_floor_us = max(work["step_bytes"] / HBM_PEAK_GBS / 1e3, work["step_flops"] / MFMA_BF16_PEAK_TFLOPS / 1e6)
+    # alongside the dominant kernel's fraction: the whole step against its own roofline floor
+    roofline["step_frac"] = step_floor_us / (main_res["ms_per_step"] * 1e3)
     extra = dict(kernels_us={k: round(v["avg_us"], 2) for k, v in kern.items()},
                  step_algorithmic_bytes=work["step_bytes"], step_algorithmic_flops=work["step_flops"],
                  step_roofline_floor_us=step_floor_us,
