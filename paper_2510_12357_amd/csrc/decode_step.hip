@@ -456,6 +456,20 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   const int tid = threadIdx.x, lane = tid & 63, wave = uni(tid >> 6);
   const int q = lane >> 4, c16 = lane & 15;
   const int G = gridDim.x;
+  // Place in the item list.  Workgroups b and b + G/2 of a launch of two workgroups per CU share a
+  // CU (the dispatcher fills every CU once before it comes back to the first).  The router's
+  // workgroups are the last of the grid; their CU-mates are put right in front of them in the order
+  // the items are dealt in, i.e. they are the last to get an item of segment A: while the selection
+  // is computed, the router's loads do not queue behind a weight stream on their own CU.
+  int vb = (int)blockIdx.x;
+  {
+    const int R = min(a.T * a.route_split, G / 4), half = G / 2;
+    if ((G & 1) == 0) {
+      const int b = (int)blockIdx.x;
+      if (b >= half - R && b < half) vb = G - 2 * R + (b - (half - R));      // CU-mates of the router's workgroups
+      else if (b >= half && b < G - R) vb = b - R;                           // the others close the gap
+    }
+  }
   const int n_groups = a.n_shared + a.E + a.n_slabs + a.E;
   const int gA = a.n_shared;                                  // groups of segment A
 
@@ -476,7 +490,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   if (tid == 0) sm.dep_seq = 0;
   // (the last workgroups of the grid: they get the fewest items of segment A, i.e. they would wait
   // for the selection first of all)
-  const int route_id = G - 1 - (int)blockIdx.x;
+  const int route_id = G - 1 - vb;
   if (route_id < a.T * a.route_split) {
     const int t = route_id / a.route_split, part = route_id - t * a.route_split;
     const __amdgpu_buffer_rsrc_t rl = make_rsrc(a.logits, kWholeBuffer);
@@ -527,7 +541,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
 
   // Iteration at which this workgroup's loaders issue their first chunk behind segment A: all A
   // items have K = H.  Both kinds of waves run the dispatch block at the top of that iteration.
-  const int my_A = total_A > (int)blockIdx.x ? (total_A - (int)blockIdx.x + G - 1) / G : 0;
+  const int my_A = total_A > vb ? (total_A - vb + G - 1) / G : 0;
   const int s_star = my_A * ((a.H + KC - 1) / KC);
   int total = total_A;                                        // items known so far
 
@@ -618,7 +632,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
 
   if (wave < kWorkers) {
     // =================================== loader ===================================
-    DItem it = decode_item<WB>(a, sm, blockIdx.x, total, n_groups, wave, lane);
+    DItem it = decode_item<WB>(a, sm, vb, total, n_groups, wave, lane);
     DItem nx = it;
     bool nx_known = false;
     int j = 0, k = 0, drain = 0, s = 0;
@@ -632,7 +646,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
     __amdgpu_buffer_rsrc_t rs = make_rsrc(it.w0, it.wbytes);
     MM_WAIT_VMCNT(0);
     auto set_item = [&]() {
-      it = nx_known ? nx : decode_item<WB>(a, sm, blockIdx.x + j * G, total, n_groups, wave, lane);
+      it = nx_known ? nx : decode_item<WB>(a, sm, vb + j * G, total, n_groups, wave, lane);
       nx_known = false;
       rs = make_rsrc(it.w0, it.wbytes);
 #pragma unroll
@@ -659,8 +673,8 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
         for (int i = 0; i < 4; ++i) addr[i] += kRowBytes;
         // the next item is decoded under the loads of this one's first chunk when the list is known
         // that far (LDS and registers only: nothing joins the counted loads)
-        if (k == 1 && (block_done || (int)blockIdx.x + (j + 1) * G < total_A)) {
-          nx = decode_item<WB>(a, sm, blockIdx.x + (j + 1) * G, total, n_groups, wave, lane);
+        if (k == 1 && (block_done || vb + (j + 1) * G < total_A)) {
+          nx = decode_item<WB>(a, sm, vb + (j + 1) * G, total, n_groups, wave, lane);
           nx_known = true;
         }
         if (k == it.nch) { ++j; k = 0; set_item(); }
@@ -681,7 +695,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   } else {
     // =================================== computer ===================================
     const int c = wave - kWorkers, tw = c & 1, kp = c >> 1;
-    DItem cur = decode_item<WB>(a, sm, blockIdx.x, total, n_groups, c, lane);
+    DItem cur = decode_item<WB>(a, sm, vb, total, n_groups, c, lane);
     int j = 0, k = 0;
     int pending = 0, started = 0;
     int pub = -1, pub_down = 0;     // counter this wave still has to bump for outputs it stored (-1: none)
@@ -837,7 +851,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
     bool nx_known = false;
     int look = 0;                     // this lane's shard of nx's dependency counter
     auto peek = [&]() {
-      nx = decode_item<WB>(a, sm, blockIdx.x + (j + 1) * G, total, n_groups, c, lane);
+      nx = decode_item<WB>(a, sm, vb + (j + 1) * G, total, n_groups, c, lane);
       nx_known = true;
       look = (nx.valid && nx.dep >= 0) ? shard_load(a.sync, nx.dep, lane) : 0;
     };
@@ -862,7 +876,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
 
     for (int s = 0;; ++s) {
       if (!block_done && s == s_star) { dispatch_block(); block_done = true; }
-      if (!nx_known && cur.valid && (block_done || (int)blockIdx.x + (j + 1) * G < total_A)) peek();
+      if (!nx_known && cur.valid && (block_done || vb + (j + 1) * G < total_A)) peek();
       lds_barrier();                                          // "landed"
       MM_TRACE_IT(4, s);
       publish();
@@ -885,7 +899,7 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
           // The next item.  If nothing stands in its way (no dependency, or the early look found it
           // met), its first token rows go out here, in front of the barrier, as within an item.
           const bool had_look = nx_known;
-          cur = nx_known ? nx : decode_item<WB>(a, sm, blockIdx.x + j * G, total, n_groups, c, lane);
+          cur = nx_known ? nx : decode_item<WB>(a, sm, vb + j * G, total, n_groups, c, lane);
           nx_known = false;
           bool ready = cur.valid && cur.dep < 0;
           if (cur.valid && cur.dep >= 0 && had_look) ready = shard_sum(look) >= cur.dep_want;
