@@ -185,13 +185,13 @@ SEPARATE_CALLS = False
 
 
 def one_launch(cfg) -> bool:
-    """Which decode steps run as one launch (moe_layer_decode): at most 16 tokens, bf16 weights, and
+    """Which decode steps run as one launch (moe_layer_decode): at most 32 tokens, bf16 weights, and
     shared experts to stream while the selection is computed - where it was measured to be the faster
     of the two ways through the C ABI (60-expert layer, one launch against separate calls, us per
-    step: b = 1 45 / 52, b = 8 82 / 88, b = 16 121 / 122, b = 24 150 / 148, b = 32 170 / 167,
-    b = 48 195 / 192, b = 64 208 / 207; without shared experts nothing hides the selection, and the
+    step: b = 1 43 / 51, b = 8 79 / 88, b = 16 119 / 122, b = 24 147 / 148, b = 32 166 / 168,
+    b = 48 196 / 192, b = 64 211 / 205; without shared experts nothing hides the selection, and the
     8-bit instance of the kernel is short of registers; those steps take the separate calls)."""
-    return not SEPARATE_CALLS and 0 < cfg.T <= 16 and cfg.dtype == "bf16" and len(cfg.shared_I) > 0
+    return not SEPARATE_CALLS and 0 < cfg.T <= 32 and cfg.dtype == "bf16" and len(cfg.shared_I) > 0
 
 
 def run_steps(mm, torch, layers: DeviceLayers, bufs, n: int, first: int = 0):

@@ -461,10 +461,14 @@ __global__ __launch_bounds__(kThreadsD) __attribute__((amdgpu_waves_per_eu(4, 4)
   // workgroups are the last of the grid; their CU-mates are put right in front of them in the order
   // the items are dealt in, i.e. they are the last to get an item of segment A: while the selection
   // is computed, the router's loads do not queue behind a weight stream on their own CU.
+  // (Only when segment A leaves those workgroups without an item; with more items than that the
+  // order would merely shift work between workgroups, and the plain order is the faster one.)
   int vb = (int)blockIdx.x;
   {
     const int R = min(a.T * a.route_split, G / 4), half = G / 2;
-    if ((G & 1) == 0) {
+    int n_a = 0;
+    for (int g = 0; g < a.n_shared; ++g) n_a += ((a.shared_I[g] + 15) / 16) * ((a.T + kTok - 1) / kTok);
+    if ((G & 1) == 0 && n_a + 2 * R <= G) {
       const int b = (int)blockIdx.x;
       if (b >= half - R && b < half) vb = G - 2 * R + (b - (half - R));      // CU-mates of the router's workgroups
       else if (b >= half && b < G - R) vb = b - R;                           // the others close the gap
